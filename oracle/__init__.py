@@ -1,0 +1,227 @@
+"""SALR CPU oracle -- TEST INFRASTRUCTURE, not part of the product.
+
+Python face of ``oracle/salr_oracle.c`` (plain C, fp64) plus the few numpy-only checks that need an
+SVD or the normal distribution.  Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline``
+leg of ``bench.py`` may import this package; the HIP library and its binding never do, and this
+package imports nothing from them.
+
+All bf16 tensors are ``numpy.uint16`` arrays of raw bit patterns.  Orientation: W-hat is
+``[N = out, K = in]`` (the transpose of the paper's ``W in R^{d_in x d_out}``), the bitmap is
+``[N, ceil(K/32)]`` uint32 with bit t of word w = column ``32 w + t``.
+
+Pins (see tests/test_oracle_*.py): the mask against a brute-force rank count, the paper's printed
+rule and Theorem 1's closed form and worked example; encode/decode against each other, the paper's
+byte-mask/LUT decoder, popcount identities and hand-worked masks; the linear against pure-Python
+loops, numpy fp64 matmul in the special cases that reduce to it, and the per-adapter sum; the SVD
+residual against Theorem 3's bound.  No function here is "parity unpinned".
+"""
+from __future__ import annotations
+
+import ctypes
+import math
+import os
+from statistics import NormalDist
+from typing import Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libsalr_oracle.so")
+_lib = None
+
+_u16p = ctypes.POINTER(ctypes.c_uint16)
+_u32p = ctypes.POINTER(ctypes.c_uint32)
+_f64p = ctypes.POINTER(ctypes.c_double)
+_i8p = ctypes.POINTER(ctypes.c_int8)
+_i64 = ctypes.c_int64
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH) or os.path.getmtime(_LIB_PATH) < os.path.getmtime(
+            os.path.join(_HERE, "salr_oracle.c")):
+        from . import build as _build
+        _build.build(force=True)
+    lib = ctypes.CDLL(_LIB_PATH)
+    lib.salr_oracle_threads.restype = ctypes.c_int
+    lib.salr_oracle_words_per_row.restype = _i64
+    lib.salr_oracle_words_per_row.argtypes = [_i64]
+    lib.salr_oracle_mask_topk_rows.argtypes = [_u16p, _i64, _i64, _i64, _u16p]
+    lib.salr_oracle_mask_threshold.argtypes = [_u16p, _i64, ctypes.c_uint16, _u16p]
+    lib.salr_oracle_encode.argtypes = [_u16p, _i64, _i64, _u32p, _u16p, _i64, _u32p]
+    lib.salr_oracle_decode.argtypes = [_u32p, _u16p, _u32p, _i64, _i64, _u16p]
+    lib.salr_oracle_decode_lut.argtypes = [_u32p, _u16p, _u32p, _i64, _i64, _u16p]
+    lib.salr_oracle_build_lut.argtypes = [_i8p]
+    lib.salr_oracle_build_lut.restype = None
+    lib.salr_oracle_linear.argtypes = [_u16p, _i64, _i64, _i64, _u16p, _u16p, _u16p, _i64, _f64p]
+    lib.salr_oracle_adapter_accumulate.argtypes = [_u16p, _i64, _i64, _i64, _u16p, _u16p, _i64, _f64p]
+    _lib = lib
+    return lib
+
+
+def _p(a: Optional[np.ndarray], typ):
+    if a is None:
+        return ctypes.cast(None, typ)
+    return a.ctypes.data_as(typ)
+
+
+def _c(a, dtype) -> np.ndarray:
+    a = np.ascontiguousarray(a)
+    if a.dtype != dtype:
+        raise TypeError(f"expected {dtype}, got {a.dtype}")
+    return a
+
+
+def threads() -> int:
+    """Threads the OpenMP loops of the oracle use on this machine."""
+    return int(_load().salr_oracle_threads())
+
+
+def words_per_row(cols: int) -> int:
+    return int(_load().salr_oracle_words_per_row(cols))
+
+
+def mask_topk_rows(w: np.ndarray, keep: int) -> np.ndarray:
+    """Per-row magnitude pruning (Sec. 2): keep the ``keep`` largest |w| of every row, ties to the
+    lower column, +0.0 elsewhere."""
+    w = _c(w, np.uint16)
+    rows, cols = w.shape
+    out = np.empty_like(w)
+    rc = _load().salr_oracle_mask_topk_rows(_p(w, _u16p), rows, cols, int(keep), _p(out, _u16p))
+    if rc:
+        raise RuntimeError(f"mask_topk_rows failed ({rc})")
+    return out
+
+
+def mask_threshold(w: np.ndarray, t_mag: int) -> np.ndarray:
+    """The rule as printed in Sec. 2: keep iff |w| > T for one threshold magnitude (bf16 pattern)."""
+    w = _c(w, np.uint16)
+    out = np.empty_like(w)
+    rc = _load().salr_oracle_mask_threshold(_p(w, _u16p), w.size, int(t_mag), _p(out, _u16p))
+    if rc:
+        raise RuntimeError("mask_threshold failed")
+    return out
+
+
+def encode(w_hat: np.ndarray) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """Bitmap + packed nonzeros + row offsets of a dense (already pruned) matrix (Sec. 3.3)."""
+    w_hat = _c(w_hat, np.uint16)
+    rows, cols = w_hat.shape
+    wpr = words_per_row(cols)
+    bitmap = np.empty((rows, wpr), dtype=np.uint32)
+    offsets = np.empty(rows + 1, dtype=np.uint32)
+    lib = _load()
+    rc = lib.salr_oracle_encode(_p(w_hat, _u16p), rows, cols, _p(bitmap, _u32p), _p(None, _u16p), 0,
+                                _p(offsets, _u32p))
+    if rc:
+        raise RuntimeError(f"encode (count) failed ({rc})")
+    nnz = int(offsets[rows])
+    values = np.empty(nnz, dtype=np.uint16)
+    rc = lib.salr_oracle_encode(_p(w_hat, _u16p), rows, cols, _p(bitmap, _u32p), _p(values, _u16p), nnz,
+                                _p(offsets, _u32p))
+    if rc:
+        raise RuntimeError(f"encode failed ({rc})")
+    return bitmap, values, offsets
+
+
+def decode(bitmap: np.ndarray, values: np.ndarray, row_offsets: np.ndarray, rows: int, cols: int,
+           use_lut: bool = False) -> np.ndarray:
+    """Dense matrix back from the format.  ``use_lut`` selects the paper's byte-mask + lookup-table
+    decoder instead of the running-cursor one."""
+    bitmap = _c(bitmap, np.uint32)
+    values = _c(values, np.uint16)
+    row_offsets = _c(row_offsets, np.uint32)
+    out = np.empty((rows, cols), dtype=np.uint16)
+    fn = _load().salr_oracle_decode_lut if use_lut else _load().salr_oracle_decode
+    rc = fn(_p(bitmap, _u32p), _p(values, _u16p), _p(row_offsets, _u32p), rows, cols, _p(out, _u16p))
+    if rc:
+        raise RuntimeError(f"decode failed ({rc})")
+    return out
+
+
+def build_lut() -> np.ndarray:
+    """The 256 x 8 table of Sec. 3.3: entry [m, t] = index of bit t among m's set bits, or -1."""
+    lut = np.empty((256, 8), dtype=np.int8)
+    _load().salr_oracle_build_lut(_p(lut, _i8p))
+    return lut
+
+
+def linear(x: np.ndarray, w_hat: np.ndarray, a_cat: Optional[np.ndarray], b_cat: Optional[np.ndarray]
+           ) -> np.ndarray:
+    """Y = X What^T + (X A_cat) B_cat in fp64 (Sec. 3.2).  ``a_cat``/``b_cat`` None means R = 0."""
+    x = _c(x, np.uint16)
+    w_hat = _c(w_hat, np.uint16)
+    M, K = x.shape
+    N, K2 = w_hat.shape
+    if K != K2:
+        raise ValueError("K mismatch")
+    R = 0
+    if a_cat is not None:
+        a_cat = _c(a_cat, np.uint16)
+        b_cat = _c(b_cat, np.uint16)
+        R = a_cat.shape[1]
+        if a_cat.shape != (K, R) or b_cat.shape != (R, N):
+            raise ValueError("adapter shapes")
+    y = np.empty((M, N), dtype=np.float64)
+    rc = _load().salr_oracle_linear(_p(x, _u16p), M, K, N, _p(w_hat, _u16p),
+                                    _p(a_cat if R else None, _u16p), _p(b_cat if R else None, _u16p), R,
+                                    _p(y, _f64p))
+    if rc:
+        raise RuntimeError(f"linear failed ({rc})")
+    return y
+
+
+def linear_per_adapter(x: np.ndarray, w_hat: np.ndarray, As: Sequence[np.ndarray],
+                       Bs: Sequence[np.ndarray]) -> np.ndarray:
+    """y = x What^T + sum_i (x A_i) B_i, one adapter at a time (Sec. 3.2 before concatenation)."""
+    y = linear(x, w_hat, None, None)
+    x = _c(x, np.uint16)
+    M, K = x.shape
+    N = w_hat.shape[0]
+    for a, b in zip(As, Bs):
+        a = _c(a, np.uint16)
+        b = _c(b, np.uint16)
+        r = a.shape[1]
+        rc = _load().salr_oracle_adapter_accumulate(_p(x, _u16p), M, K, N, _p(a, _u16p), _p(b, _u16p), r,
+                                                    _p(y, _f64p))
+        if rc:
+            raise RuntimeError("adapter_accumulate failed")
+    return y
+
+
+# ---------------------------------------------------------------------------------------------------
+# numpy-only checks of the paper's closed forms
+# ---------------------------------------------------------------------------------------------------
+
+def pruning_mse_closed_form(p: float, sigma: float = 1.0) -> float:
+    """Theorem 1: MSE(p) = 2 sigma^2 [Phi(t_p) - 1/2 - t_p phi(t_p)], t_p = Phi^{-1}((1+p)/2)."""
+    nd = NormalDist()
+    t = nd.inv_cdf((1.0 + p) / 2.0)
+    phi = math.exp(-0.5 * t * t) / math.sqrt(2.0 * math.pi)
+    return 2.0 * sigma * sigma * (nd.cdf(t) - 0.5 - t * phi)
+
+
+def bf16_to_f64(bits: np.ndarray) -> np.ndarray:
+    b = np.ascontiguousarray(bits, dtype=np.uint16)
+    return (b.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+
+
+def svd_residual_check(w: np.ndarray, w_hat: np.ndarray, r: int) -> Tuple[float, float]:
+    """Sec. 3.1 / Theorem 3: E = W - What, E_r = rank-r truncated SVD of E.
+    Returns (||E||_F^2 / (N K),  ||E - E_r||_F^2 / ||E||_F^2)."""
+    E = bf16_to_f64(w) - bf16_to_f64(w_hat)
+    s = np.linalg.svd(E, compute_uv=False)
+    total = float(np.sum(s * s))
+    tail = float(np.sum(s[r:] ** 2))
+    return total / E.size, (tail / total if total > 0 else 0.0)
+
+
+def svd_residual_adapter(w: np.ndarray, w_hat: np.ndarray, r: int) -> Tuple[np.ndarray, np.ndarray]:
+    """The residual adapter of Sec. 3.1 in our orientation, fp64: with E = U S V^T ([N, K]),
+    A = V_r S_r^{1/2} ([K, r]) and B = S_r^{1/2} U_r^T ([r, N]) so that A B = E_r^T."""
+    E = bf16_to_f64(w) - bf16_to_f64(w_hat)
+    U, s, Vt = np.linalg.svd(E, full_matrices=False)
+    rs = np.sqrt(s[:r])
+    return Vt[:r].T * rs[None, :], (U[:, :r] * rs[None, :]).T

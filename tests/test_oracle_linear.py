@@ -1,0 +1,132 @@
+"""Pins for the oracle's layer output (paper Sec. 3.2) and SVD residual (Sec. 3.1, Theorem 3).  CPU only."""
+import numpy as np
+import pytest
+
+import oracle
+import salr_workloads as wl
+
+
+def _f64(bits):
+    return oracle.bf16_to_f64(bits)
+
+
+def _small_problem(M, K, N, ranks, seed, density=0.5, std_ab=0.05):
+    rng = np.random.default_rng(seed)
+    x = wl.gaussian_bf16((M, K), 1.0, seed + 1)
+    w = wl.gaussian_bf16((N, K), 0.02, seed + 2)
+    w[rng.random((N, K)) >= density] = 0
+    As = [wl.gaussian_bf16((K, r), std_ab, seed + 10 + i) for i, r in enumerate(ranks)]
+    Bs = [wl.gaussian_bf16((r, N), std_ab, seed + 20 + i) for i, r in enumerate(ranks)]
+    return x, w, As, Bs
+
+
+def test_linear_against_pure_python_loops():
+    # all four dims different so that a transposed operand cannot pass
+    M, K, N, ranks = 3, 11, 5, (2, 1)
+    x, w, As, Bs = _small_problem(M, K, N, ranks, 1)
+    a_cat, b_cat = wl.concat_adapters(As, Bs)
+    R = sum(ranks)
+    xf, wf, af, bf = (_f64(t).tolist() for t in (x, w, a_cat, b_cat))
+    expect = [[0.0] * N for _ in range(M)]
+    for m in range(M):
+        t = [sum(xf[m][k] * af[k][r] for k in range(K)) for r in range(R)]
+        for n in range(N):
+            base = sum(xf[m][k] * wf[n][k] for k in range(K))
+            expect[m][n] = base + sum(t[r] * bf[r][n] for r in range(R))
+    got = oracle.linear(x, w, a_cat, b_cat)
+    np.testing.assert_allclose(got, np.array(expect), rtol=1e-12, atol=1e-15)
+
+
+def test_linear_special_cases_reduce_to_numpy_matmul():
+    M, K, N, ranks = 7, 96, 40, (4, 4)
+    x, w, As, Bs = _small_problem(M, K, N, ranks, 2)
+    a_cat, b_cat = wl.concat_adapters(As, Bs)
+    X, W, A, B = _f64(x), _f64(w), _f64(a_cat), _f64(b_cat)
+    # R = 0: plain X What^T
+    np.testing.assert_allclose(oracle.linear(x, w, None, None), X @ W.T, rtol=1e-12, atol=1e-14)
+    # What = 0: pure low-rank term
+    z = np.zeros_like(w)
+    np.testing.assert_allclose(oracle.linear(x, z, a_cat, b_cat), (X @ A) @ B, rtol=1e-12, atol=1e-16)
+    # p = 0 (dense weight): textbook GEMM plus adapters
+    wd = wl.gaussian_bf16((N, K), 0.02, 99)
+    np.testing.assert_allclose(oracle.linear(x, wd, a_cat, b_cat), X @ _f64(wd).T + (X @ A) @ B,
+                               rtol=1e-12, atol=1e-14)
+    # full expression
+    np.testing.assert_allclose(oracle.linear(x, w, a_cat, b_cat), X @ W.T + (X @ A) @ B, rtol=1e-12, atol=1e-14)
+
+
+def test_identity_rows_read_out_the_effective_weight():
+    K, N, ranks = 24, 9, (3,)
+    _, w, As, Bs = _small_problem(1, K, N, ranks, 3)
+    a_cat, b_cat = wl.concat_adapters(As, Bs)
+    eye = wl.f32_to_bf16_bits(np.eye(K, dtype=np.float32))
+    got = oracle.linear(eye, w, a_cat, b_cat)          # [K, N]: row k = column k of What^T + A B
+    np.testing.assert_allclose(got, _f64(w).T + _f64(a_cat) @ _f64(b_cat), rtol=1e-12, atol=1e-16)
+
+
+def test_concatenated_equals_per_adapter_sum():
+    M, K, N, ranks = 4, 64, 48, (8, 8, 4)
+    x, w, As, Bs = _small_problem(M, K, N, ranks, 4)
+    a_cat, b_cat = wl.concat_adapters(As, Bs)
+    assert a_cat.shape == (K, 20) and b_cat.shape == (20, N)
+    np.testing.assert_allclose(oracle.linear(x, w, a_cat, b_cat), oracle.linear_per_adapter(x, w, As, Bs),
+                               rtol=1e-12, atol=1e-15)
+
+
+def test_linearity_in_x():
+    M, K, N, ranks = 5, 32, 16, (4,)
+    x1, w, As, Bs = _small_problem(M, K, N, ranks, 5)
+    a_cat, b_cat = wl.concat_adapters(As, Bs)
+    # x2 = 2 * x1 is exact in bf16
+    x2 = wl.f32_to_bf16_bits(2.0 * wl.bf16_bits_to_f32(x1))
+    np.testing.assert_allclose(oracle.linear(x2, w, a_cat, b_cat), 2.0 * oracle.linear(x1, w, a_cat, b_cat),
+                               rtol=1e-13, atol=0)
+
+
+def test_linear_through_the_codec():
+    """decode(encode(What)) feeds the same output: the format is transparent to the layer."""
+    cfg = wl.CONFIGS["tiny"]
+    w_hat = oracle.mask_topk_rows(wl.dense_weight(cfg, rows=64), cfg.keep(500))
+    bitmap, values, offsets = oracle.encode(w_hat)
+    w_back = oracle.decode(bitmap, values, offsets, 64, cfg.K, use_lut=True)
+    x = wl.activations(cfg, 2)
+    np.testing.assert_array_equal(oracle.linear(x, w_back, None, None), oracle.linear(x, w_hat, None, None))
+
+
+@pytest.mark.parametrize("N,K,r", [(512, 512, 8), (512, 512, 16), (256, 384, 16)])
+def test_theorem3_svd_residual_bound(N, K, r):
+    """||E - E_r||_F^2 <= (1 - r/q) ||E||_F^2 for every matrix; for iid-like residuals the ratio also
+    stays above 1 - r (sqrt(N) + sqrt(K))^2 / (N K) (largest singular values of a random matrix)."""
+    cfg = wl.CONFIGS["tiny"]
+    w = wl.gaussian_bf16((N, K), cfg.std_w, 1234 + N + K)
+    w_hat = oracle.mask_topk_rows(w, K - K // 2)
+    mse, ratio = oracle.svd_residual_check(w, w_hat, r)
+    q = min(N, K)
+    assert ratio <= 1.0 - r / q + 1e-12
+    assert ratio >= 1.0 - r * (np.sqrt(N) + np.sqrt(K)) ** 2 / (N * K) - 0.01
+    # ||E||_F^2 / (NK) is Theorem 1's MSE(p)
+    assert abs(mse / oracle.pruning_mse_closed_form(0.5, cfg.std_w) - 1.0) < 0.03
+
+
+def test_theorem3_equality_for_flat_spectrum():
+    # E with all singular values equal (a scaled orthogonal matrix): the bound is attained
+    q = 16
+    rng = np.random.default_rng(0)
+    Q, _ = np.linalg.qr(rng.standard_normal((q, q)))
+    s = np.linalg.svd(Q, compute_uv=False)
+    for r in (1, 4, 15):
+        assert abs(np.sum(s[r:] ** 2) / np.sum(s ** 2) - (1 - r / q)) < 1e-12
+
+
+def test_residual_adapter_reconstructs_truncated_svd():
+    N, K, r = 48, 80, 6
+    w = wl.gaussian_bf16((N, K), 0.02, 77)
+    w_hat = oracle.mask_topk_rows(w, K // 2)
+    A, B = oracle.svd_residual_adapter(w, w_hat, r)
+    assert A.shape == (K, r) and B.shape == (r, N)
+    E = _f64(w) - _f64(w_hat)
+    U, s, Vt = np.linalg.svd(E, full_matrices=False)
+    E_r = (U[:, :r] * s[:r]) @ Vt[:r]
+    np.testing.assert_allclose(A @ B, E_r.T, atol=1e-12)
+    _, ratio = oracle.svd_residual_check(w, w_hat, r)
+    assert abs(np.linalg.norm(E - E_r) ** 2 / np.linalg.norm(E) ** 2 - ratio) < 1e-12
