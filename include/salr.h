@@ -1,0 +1,135 @@
+/*
+ * salr.h -- C boundary of the MI355X (gfx950) library for the SALR inference linear layer
+ *
+ *     Y[M,N] = X[M,K] * decode(bitmap, values)[N,K]^T  +  (X[M,K] * A_cat[K,R]) * B_cat[R,N]
+ *
+ * (paper Sec. 3.2 for the concatenated adapters, Sec. 3.3 for the bitmap format and the
+ * decode/GEMM pipeline).
+ *
+ * Conventions for every entry point
+ *   - bf16 tensors are passed as pointers to their raw 16-bit patterns (uint16_t), row-major.
+ *   - Orientation: the frozen pruned weight W-hat is [N = out features, K = in features]; the
+ *     bits of one bitmap row run along K, the contraction dimension.  (The paper writes the
+ *     transpose, y = xW with W in R^{d_in x d_out}.)
+ *   - All data pointers are DEVICE pointers owned by the caller, 16-byte aligned at their base.
+ *     The library allocates nothing, frees nothing and never synchronises: every call only
+ *     enqueues kernels on `stream` (a hipStream_t passed as void*, NULL = default stream).
+ *   - Arguments are validated on the host before anything is enqueued; on a non-zero status no
+ *     kernel has been launched and no output has been touched.
+ *   - Sizes are int64_t; a dimension of 0 is legal and makes the call a no-op (SALR_OK).
+ *
+ * The sparse format (Sec. 3.3, "Mapping Sparse Weights")
+ *   bitmap      [rows, ceil(cols/32)] uint32.  Bit t (least significant first) of word w of a row
+ *               is column 32*w + t: 1 iff the entry is nonzero.  Seen as bytes this is the paper's
+ *               byte mask, bit t of byte b = column 8*b + t.  Pad bits of a row's last word are 0.
+ *   values      [nnz] bf16 patterns: the nonzero entries in row-major order (the paper's v).
+ *               As an INPUT the buffer must be readable up to the next multiple of 16 bytes past its
+ *               nnz elements (the padding is loaded by vector reads, its contents are never used);
+ *               it may be NULL only when nnz == 0.
+ *   row_offsets [rows + 1] uint32: row_offsets[n] = number of nonzeros before row n, so
+ *               row_offsets[rows] = nnz.  (The paper leaves open how a row's start in v is found;
+ *               this array is that.)  nnz must be < 2^32.
+ *   "Nonzero" is a value test: +0.0 and -0.0 are zero (and decode to +0.0); NaN and Inf are nonzero
+ *   and are carried bit for bit.
+ */
+#ifndef SALR_H
+#define SALR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SALR_OK = 0,
+    SALR_ERR_INVALID_ARG = 1, /* null pointer where data is required, negative size            */
+    SALR_ERR_SHAPE = 2,       /* sizes violate a stated constraint                              */
+    SALR_ERR_CAPACITY = 3,    /* values buffer or workspace smaller than required               */
+    SALR_ERR_UNSUPPORTED = 4, /* legal request that this build has no kernel for                */
+    SALR_ERR_HIP = 5          /* the HIP runtime reported an error while enqueuing              */
+} salr_status_t;
+
+/* Static, NUL-terminated description of a status code (host memory, never freed). */
+const char* salr_status_string(salr_status_t status);
+
+/* ceil(cols / 32): uint32 words per bitmap row.  Returns -1 for cols < 0. */
+int64_t salr_bitmap_words_per_row(int64_t cols);
+
+/*
+ * salr_encode_bitmap -- Sec. 3.3: B[n][k] = [W-hat[n][k] != 0], v = nonzeros in row-major order.
+ *
+ *   w_dense          in   [rows, cols] bf16, already pruned (zeros where entries were removed)
+ *   bitmap           out  [rows, ceil(cols/32)] uint32
+ *   values           out  [values_capacity] bf16; NULL = count only (bitmap and row_offsets are
+ *                         still produced, so a caller can size `values` from row_offsets[rows])
+ *   values_capacity  in   elements available in `values` (ignored when values == NULL)
+ *   row_offsets      out  [rows + 1] uint32; row_offsets[rows] = nnz stays on the device
+ *
+ * If nnz exceeds values_capacity the kernel never writes past the buffer: entries with index
+ * >= values_capacity are dropped, row_offsets still holds the true counts, and it is the caller who
+ * compares row_offsets[rows] with the capacity (the library cannot know nnz without a sync).
+ * Errors: INVALID_ARG (null w_dense/bitmap/row_offsets, negative size), SHAPE (rows * cols or a
+ * dimension beyond 2^31 - 1 rows / 2^31 - 32 cols), HIP.
+ */
+salr_status_t salr_encode_bitmap(const uint16_t* w_dense, int64_t rows, int64_t cols, uint32_t* bitmap,
+                                 uint16_t* values, int64_t values_capacity, uint32_t* row_offsets,
+                                 void* stream);
+
+/*
+ * salr_decode -- Sec. 3.3, the reconstruction rule: for byte block b of row n with mask m,
+ * W-hat[n][8b+t] = (bit t of m) ? segment[popcount(m & (2^t - 1))] : 0, where the block's segment
+ * starts at row_offsets[n] + popcount of the row's earlier bits.  (The paper tabulates
+ * popcount(m & (2^t - 1)) in a 256 x 8 lookup table; the result is the same.)
+ *
+ *   bitmap, values, row_offsets  in   the format above
+ *   w_dense_out                  out  [rows, cols] bf16; clear bits give +0.0 (0x0000)
+ *
+ * The format is trusted: offsets that point outside `values` are the caller's error.
+ * Errors: INVALID_ARG (null bitmap/row_offsets/w_dense_out with rows*cols > 0), SHAPE, HIP.
+ */
+salr_status_t salr_decode(const uint32_t* bitmap, const uint16_t* values, const uint32_t* row_offsets,
+                          int64_t rows, int64_t cols, uint16_t* w_dense_out, void* stream);
+
+/*
+ * Bytes of device workspace salr_sparse_lowrank_linear needs for these sizes (0 is possible).
+ * It holds T = X * A_cat and nothing that outlives the call.  Returns 0 for invalid sizes.
+ */
+size_t salr_linear_workspace_bytes(int64_t M, int64_t K, int64_t N, int64_t R);
+
+/*
+ * salr_sparse_lowrank_linear -- the layer of Sec. 3.2 / 3.3:
+ *
+ *     Y = X * W-hat^T + (X * A_cat) * B_cat
+ *
+ * with W-hat decoded on the fly from the bitmap format (decode stage feeding the matrix-core
+ * stage, Sec. 3.3 "Pipeline Design") and all adapters applied as ONE concatenated pair
+ * A_cat = [A_1 ... A_n], B_cat = [B_1; ...; B_n] (Sec. 3.2).  bf16 inputs, fp32 accumulation,
+ * T = X * A_cat rounded once to bf16, Y rounded to bf16 (nearest even).  No bias and no LoRA scale:
+ * fold alpha/r into B_cat.
+ *
+ *   x            in   [M, K] bf16
+ *   bitmap       in   [N, K/32] uint32      } W-hat, [N, K], in the format above
+ *   values       in   [nnz] bf16            }
+ *   row_offsets  in   [N + 1] uint32        }
+ *   a_cat        in   [K, R] bf16; may be NULL iff R == 0
+ *   b_cat        in   [R, N] bf16; may be NULL iff R == 0
+ *   y            out  [M, N] bf16, overwritten
+ *   workspace    --   at least salr_linear_workspace_bytes(M, K, N, R) bytes, 256-byte aligned;
+ *                     may be NULL when that size is 0.  Contents before and after are unspecified.
+ *
+ * Constraints: K % 32 == 0 (else SHAPE); R <= 256 (else UNSUPPORTED); M, N < 2^31.
+ * Errors: INVALID_ARG, SHAPE, CAPACITY (workspace too small), UNSUPPORTED, HIP.
+ * Calls that share a workspace must be ordered by the stream.
+ */
+salr_status_t salr_sparse_lowrank_linear(const uint16_t* x, int64_t M, int64_t K, int64_t N,
+                                         const uint32_t* bitmap, const uint16_t* values,
+                                         const uint32_t* row_offsets, const uint16_t* a_cat,
+                                         const uint16_t* b_cat, int64_t R, uint16_t* y, void* workspace,
+                                         size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SALR_H */

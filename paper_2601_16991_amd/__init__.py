@@ -1,0 +1,175 @@
+"""MI355X-native SALR linear layer: thin Python binding over the C boundary in ``include/salr.h``.
+
+The three operations keep their C names (``salr_encode_bitmap``, ``salr_decode``,
+``salr_sparse_lowrank_linear``); this module only marshals arguments: torch CUDA tensors supply
+device memory and the current stream, every step of the computation runs in the HIP kernels of
+``libsalr_hip.so``.  There is no CPU or PyTorch fallback: a missing library is an ImportError.
+
+bf16 tensors may be given as ``torch.bfloat16`` or as their raw patterns (``torch.int16`` /
+``torch.uint16``); bitmap and row offsets are ``torch.int32`` / ``torch.uint32``.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsalr_hip.so")
+
+SALR_OK, SALR_ERR_INVALID_ARG, SALR_ERR_SHAPE, SALR_ERR_CAPACITY, SALR_ERR_UNSUPPORTED, SALR_ERR_HIP = range(6)
+
+_lib = None
+_vp = ctypes.c_void_p
+_i64 = ctypes.c_int64
+
+
+class SalrError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = int(status)
+        msg = lib().salr_status_string(status).decode()
+        super().__init__(f"{where}: {msg} (status {status})")
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded C-ABI library.  Built by ``paper_2601_16991_amd/build.py`` (or __graft_entry__.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: run `python paper_2601_16991_amd/build.py` first")
+        L = ctypes.CDLL(LIB_PATH)
+        L.salr_status_string.restype = ctypes.c_char_p
+        L.salr_status_string.argtypes = [ctypes.c_int]
+        L.salr_bitmap_words_per_row.restype = _i64
+        L.salr_bitmap_words_per_row.argtypes = [_i64]
+        L.salr_encode_bitmap.restype = ctypes.c_int
+        L.salr_encode_bitmap.argtypes = [_vp, _i64, _i64, _vp, _vp, _i64, _vp, _vp]
+        L.salr_decode.restype = ctypes.c_int
+        L.salr_decode.argtypes = [_vp, _vp, _vp, _i64, _i64, _vp, _vp]
+        L.salr_linear_workspace_bytes.restype = ctypes.c_size_t
+        L.salr_linear_workspace_bytes.argtypes = [_i64, _i64, _i64, _i64]
+        L.salr_sparse_lowrank_linear.restype = ctypes.c_int
+        L.salr_sparse_lowrank_linear.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _vp,
+                                                 ctypes.c_size_t, _vp]
+        _lib = L
+    return _lib
+
+
+_BF16_TYPES = (torch.bfloat16, torch.int16, torch.uint16)
+_U32_TYPES = (torch.int32, torch.uint32)
+
+
+def _ptr(t: Optional[torch.Tensor], kinds, name: str) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise TypeError(f"{name} must be a CUDA tensor")
+    if t.dtype not in kinds:
+        raise TypeError(f"{name}: dtype {t.dtype} not in {kinds}")
+    if not t.is_contiguous():
+        raise TypeError(f"{name} must be contiguous")
+    return t.data_ptr() if t.numel() > 0 else None
+
+
+def _stream(stream) -> Optional[int]:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream or None
+
+
+def _check(status: int, where: str) -> None:
+    if status != SALR_OK:
+        raise SalrError(status, where)
+
+
+def salr_bitmap_words_per_row(cols: int) -> int:
+    return int(lib().salr_bitmap_words_per_row(cols))
+
+
+def salr_encode_bitmap(w_dense: torch.Tensor, bitmap: torch.Tensor, values: Optional[torch.Tensor],
+                       row_offsets: torch.Tensor, stream=None) -> None:
+    """Enqueue the encoder.  ``values`` None = count only; its length is the capacity."""
+    rows, cols = w_dense.shape
+    cap = 0 if values is None else values.numel()
+    st = lib().salr_encode_bitmap(_ptr(w_dense, _BF16_TYPES, "w_dense"), rows, cols, _ptr(bitmap, _U32_TYPES, "bitmap"),
+                                  _ptr(values, _BF16_TYPES, "values"), cap, _ptr(row_offsets, _U32_TYPES, "row_offsets"),
+                                  _stream(stream))
+    _check(st, "salr_encode_bitmap")
+
+
+def salr_decode(bitmap: torch.Tensor, values: torch.Tensor, row_offsets: torch.Tensor, rows: int, cols: int,
+                w_dense_out: torch.Tensor, stream=None) -> None:
+    st = lib().salr_decode(_ptr(bitmap, _U32_TYPES, "bitmap"), _ptr(values, _BF16_TYPES, "values"),
+                           _ptr(row_offsets, _U32_TYPES, "row_offsets"), rows, cols,
+                           _ptr(w_dense_out, _BF16_TYPES, "w_dense_out"), _stream(stream))
+    _check(st, "salr_decode")
+
+
+def salr_linear_workspace_bytes(M: int, K: int, N: int, R: int) -> int:
+    return int(lib().salr_linear_workspace_bytes(M, K, N, R))
+
+
+def salr_sparse_lowrank_linear(x: torch.Tensor, bitmap: torch.Tensor, values: torch.Tensor,
+                               row_offsets: torch.Tensor, a_cat: Optional[torch.Tensor],
+                               b_cat: Optional[torch.Tensor], y: torch.Tensor,
+                               workspace: Optional[torch.Tensor], stream=None) -> None:
+    """Enqueue Y = X What^T + (X A_cat) B_cat.  Shapes: x [M,K], bitmap [N,K/32], a_cat [K,R], b_cat [R,N], y [M,N]."""
+    M, K = x.shape
+    N = y.shape[1]
+    R = 0 if a_cat is None else a_cat.shape[1]
+    if y.shape[0] != M or bitmap.shape[0] != N or row_offsets.numel() != N + 1:
+        raise ValueError("inconsistent shapes")
+    if R and (tuple(a_cat.shape) != (K, R) or tuple(b_cat.shape) != (R, N)):
+        raise ValueError("adapter shapes")
+    ws_ptr = None if workspace is None else workspace.data_ptr()
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = lib().salr_sparse_lowrank_linear(_ptr(x, _BF16_TYPES, "x"), M, K, N, _ptr(bitmap, _U32_TYPES, "bitmap"),
+                                          _ptr(values, _BF16_TYPES, "values"),
+                                          _ptr(row_offsets, _U32_TYPES, "row_offsets"),
+                                          _ptr(a_cat, _BF16_TYPES, "a_cat"), _ptr(b_cat, _BF16_TYPES, "b_cat"), R,
+                                          _ptr(y, _BF16_TYPES, "y"), ws_ptr, ws_bytes, _stream(stream))
+    _check(st, "salr_sparse_lowrank_linear")
+
+
+# ---------------------------------------------------------------------------------------------------
+# Convenience wrappers: allocate the outputs with torch, then call the entry points above.
+# ---------------------------------------------------------------------------------------------------
+
+def values_alloc(nnz: int, device) -> torch.Tensor:
+    """A packed-values buffer of nnz elements whose storage is padded to a multiple of 16 bytes."""
+    padded = (nnz + 7) // 8 * 8
+    return torch.empty(max(padded, 8), dtype=torch.int16, device=device)[:nnz]
+
+
+def encode(w_dense: torch.Tensor) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
+    """(bitmap, values, row_offsets) of an already pruned dense matrix; two passes with one sync
+    in between to size ``values``."""
+    rows, cols = w_dense.shape
+    dev = w_dense.device
+    bitmap = torch.empty((rows, salr_bitmap_words_per_row(cols)), dtype=torch.int32, device=dev)
+    offsets = torch.empty(rows + 1, dtype=torch.int32, device=dev)
+    salr_encode_bitmap(w_dense, bitmap, None, offsets)
+    nnz = int(offsets[-1].item()) & 0xFFFFFFFF
+    values = values_alloc(nnz, dev)
+    salr_encode_bitmap(w_dense, bitmap, values, offsets)
+    return bitmap, values, offsets
+
+
+def decode(bitmap: torch.Tensor, values: torch.Tensor, row_offsets: torch.Tensor, rows: int, cols: int
+           ) -> torch.Tensor:
+    out = torch.empty((rows, cols), dtype=torch.int16, device=bitmap.device)
+    salr_decode(bitmap, values, row_offsets, rows, cols, out)
+    return out
+
+
+def linear(x, bitmap, values, row_offsets, a_cat, b_cat, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    M, K = x.shape
+    N = bitmap.shape[0]
+    R = 0 if a_cat is None else a_cat.shape[1]
+    y = torch.empty((M, N), dtype=x.dtype, device=x.device)
+    need = salr_linear_workspace_bytes(M, K, N, R)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    salr_sparse_lowrank_linear(x, bitmap, values, row_offsets, a_cat, b_cat, y, workspace)
+    return y

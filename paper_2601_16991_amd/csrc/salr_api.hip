@@ -1,0 +1,85 @@
+// C boundary: argument validation on the host, then kernels enqueued on the caller's stream.
+#include "../../include/salr.h"
+
+#include "salr_internal.hpp"
+
+namespace {
+
+constexpr int64_t kMaxRows = 2147483647LL;        // gridDim.x
+constexpr int64_t kMaxCols = 2147483647LL - 31;   // so that ceil(cols/32)*32 stays in int32 range
+constexpr int64_t kMaxRank = 256;
+constexpr int64_t kMaxM = 65535LL * 64;           // gridDim.y of the tiled kernels
+
+size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+}  // namespace
+
+extern "C" {
+
+const char* salr_status_string(salr_status_t status) {
+    switch (status) {
+        case SALR_OK: return "ok";
+        case SALR_ERR_INVALID_ARG: return "invalid argument (null pointer or negative size)";
+        case SALR_ERR_SHAPE: return "sizes violate a constraint of this entry point";
+        case SALR_ERR_CAPACITY: return "buffer or workspace too small";
+        case SALR_ERR_UNSUPPORTED: return "unsupported request";
+        case SALR_ERR_HIP: return "HIP runtime error while enqueuing";
+    }
+    return "unknown status";
+}
+
+int64_t salr_bitmap_words_per_row(int64_t cols) { return cols < 0 ? -1 : (cols + 31) / 32; }
+
+salr_status_t salr_encode_bitmap(const uint16_t* w_dense, int64_t rows, int64_t cols, uint32_t* bitmap,
+                                 uint16_t* values, int64_t values_capacity, uint32_t* row_offsets, void* stream) {
+    if (rows < 0 || cols < 0) return SALR_ERR_INVALID_ARG;
+    if (!row_offsets) return SALR_ERR_INVALID_ARG;
+    if (rows > 0 && cols > 0 && (!w_dense || !bitmap)) return SALR_ERR_INVALID_ARG;
+    if (values && values_capacity < 0) return SALR_ERR_INVALID_ARG;
+    if (rows > kMaxRows || cols > kMaxCols) return SALR_ERR_SHAPE;
+    if (cols > 0 && rows > (int64_t)0xFFFFFFFFLL / cols) return SALR_ERR_SHAPE;  // nnz must fit uint32
+    hipError_t e = salr::launch_encode(w_dense, rows, cols, bitmap, values, values_capacity, row_offsets,
+                                       static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SALR_OK : SALR_ERR_HIP;
+}
+
+salr_status_t salr_decode(const uint32_t* bitmap, const uint16_t* values, const uint32_t* row_offsets, int64_t rows,
+                          int64_t cols, uint16_t* w_dense_out, void* stream) {
+    if (rows < 0 || cols < 0) return SALR_ERR_INVALID_ARG;
+    if (rows > 0 && cols > 0 && (!bitmap || !row_offsets || !w_dense_out)) return SALR_ERR_INVALID_ARG;
+    if (rows > kMaxRows || cols > kMaxCols) return SALR_ERR_SHAPE;
+    hipError_t e = salr::launch_decode(bitmap, values, row_offsets, rows, cols, w_dense_out,
+                                       static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SALR_OK : SALR_ERR_HIP;
+}
+
+size_t salr_linear_workspace_bytes(int64_t M, int64_t K, int64_t N, int64_t R) {
+    if (M <= 0 || K < 0 || N <= 0 || R <= 0 || R > kMaxRank) return 0;
+    return round_up((size_t)M * (size_t)salr::adapter_rank_padded(R) * sizeof(uint16_t), 256);
+}
+
+salr_status_t salr_sparse_lowrank_linear(const uint16_t* x, int64_t M, int64_t K, int64_t N, const uint32_t* bitmap,
+                                         const uint16_t* values, const uint32_t* row_offsets, const uint16_t* a_cat,
+                                         const uint16_t* b_cat, int64_t R, uint16_t* y, void* workspace,
+                                         size_t workspace_bytes, void* stream) {
+    if (M < 0 || K < 0 || N < 0 || R < 0) return SALR_ERR_INVALID_ARG;
+    if (M == 0 || N == 0) return SALR_OK;
+    if (!y || !row_offsets) return SALR_ERR_INVALID_ARG;
+    if (K > 0 && (!x || !bitmap)) return SALR_ERR_INVALID_ARG;
+    if (R > 0 && (!a_cat || !b_cat)) return SALR_ERR_INVALID_ARG;
+    if (K % 32 != 0) return SALR_ERR_SHAPE;
+    if (N > kMaxRows || K > kMaxCols) return SALR_ERR_SHAPE;
+    if (R > kMaxRank || M > kMaxM) return SALR_ERR_UNSUPPORTED;
+    const size_t need = salr_linear_workspace_bytes(M, K, N, R);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return SALR_ERR_CAPACITY;
+    salr::LinearArgs a;
+    a.x = x; a.M = M; a.K = K; a.N = N;
+    a.bitmap = bitmap; a.values = values; a.row_offsets = row_offsets;
+    a.a_cat = a_cat; a.b_cat = b_cat; a.R = R;
+    a.y = y;
+    a.t = static_cast<uint16_t*>(workspace);
+    hipError_t e = salr::launch_linear(a, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SALR_OK : SALR_ERR_HIP;
+}
+
+}  // extern "C"

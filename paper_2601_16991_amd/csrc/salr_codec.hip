@@ -1,0 +1,203 @@
+// Bitmap encoder and standalone decoder (paper Sec. 3.3, "Mapping Sparse Weights").
+//
+// Encoding is three launches on the caller's stream:
+//   1. encode_count_kernel   one workgroup per row: bitmap words + the row's nonzero count
+//   2. row_scan_kernel       one workgroup: counts -> row_offsets (exclusive prefix, in place)
+//   3. encode_compact_kernel one workgroup per row: order-preserving compaction of the nonzeros
+// Decoding is one launch, one workgroup per row.  All of it is integer/bit work; the traffic is the
+// dense matrix (2 B/element) against bitmap + values (1/8 + 2(1-p) B/element).
+#include "salr_device.hpp"
+#include "salr_internal.hpp"
+
+namespace salr {
+
+constexpr int kCodecThreads = 256;             // 4 waves
+constexpr int kUnit = 8;                       // columns per thread per step = one byte of bitmap
+constexpr int kChunkValuesMax = kCodecThreads * kUnit;  // packed values one step can own
+
+// Eight consecutive bf16 of a row starting at column 8u, zero-filled past the row end.
+template <bool kVec>
+__device__ __forceinline__ uint4 load_unit(const uint16_t* row, int64_t cols, int64_t u) {
+    uint4 q = make_uint4(0, 0, 0, 0);
+    const int64_t k0 = u * kUnit;
+    if (k0 >= cols) return q;
+    if constexpr (kVec) {
+        q = *reinterpret_cast<const uint4*>(row + k0);
+    } else {
+        uint32_t e[kUnit];
+#pragma unroll
+        for (int j = 0; j < kUnit; ++j) e[j] = (k0 + j < cols) ? row[k0 + j] : 0u;
+        q.x = e[0] | (e[1] << 16);
+        q.y = e[2] | (e[3] << 16);
+        q.z = e[4] | (e[5] << 16);
+        q.w = e[6] | (e[7] << 16);
+    }
+    return q;
+}
+
+__device__ __forceinline__ uint32_t unit_elem(const uint4& q, int j) {
+    const uint32_t d = (j < 2) ? q.x : (j < 4) ? q.y : (j < 6) ? q.z : q.w;
+    return (j & 1) ? (d >> 16) : (d & 0xFFFFu);
+}
+
+template <bool kVec>
+__global__ __launch_bounds__(kCodecThreads) void encode_count_kernel(const uint16_t* __restrict__ w,
+                                                                     int64_t cols, int64_t wpr,
+                                                                     uint32_t* __restrict__ bitmap,
+                                                                     uint32_t* __restrict__ row_offsets) {
+    __shared__ uint32_t scratch[kCodecThreads / kWave];
+    const int64_t n = blockIdx.x;
+    const uint16_t* row = w + n * cols;
+    const int64_t units = wpr * 4;  // whole words: pad bytes are produced as zeros
+    uint32_t count = 0;
+    for (int64_t base = 0; base < units; base += kCodecThreads) {
+        const int64_t u = base + threadIdx.x;
+        const uint32_t m = nonzero_mask8(load_unit<kVec>(row, cols, u));
+        count += __popc(m);
+        // four neighbouring lanes hold the four bytes of one word
+        const uint32_t b1 = __shfl_down(m, 1, kWave);
+        const uint32_t b2 = __shfl_down(m, 2, kWave);
+        const uint32_t b3 = __shfl_down(m, 3, kWave);
+        if ((threadIdx.x & 3) == 0 && u < units) bitmap[n * wpr + (u >> 2)] = m | (b1 << 8) | (b2 << 16) | (b3 << 24);
+    }
+#pragma unroll
+    for (int d = kWave / 2; d > 0; d >>= 1) count += __shfl_down(count, d, kWave);
+    if (lane_id() == 0) scratch[threadIdx.x / kWave] = count;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t s = 0;
+        for (int i = 0; i < kCodecThreads / kWave; ++i) s += scratch[i];
+        row_offsets[n + 1] = s;  // the scan turns counts into offsets in place
+    }
+}
+
+constexpr int kScanThreads = 1024;
+
+// row_offsets[1..rows] holds per-row counts on entry and inclusive prefix sums on exit; [0] = 0.
+__global__ __launch_bounds__(kScanThreads) void row_scan_kernel(uint32_t* __restrict__ row_offsets, int64_t rows) {
+    __shared__ uint32_t scratch[kScanThreads / kWave];
+    uint32_t carry = 0;
+    for (int64_t base = 0; base < rows; base += kScanThreads) {
+        const int64_t i = base + threadIdx.x;
+        const uint32_t v = (i < rows) ? row_offsets[i + 1] : 0u;
+        uint32_t total;
+        const uint32_t excl = block_exclusive_scan<kScanThreads>(v, scratch, total);
+        if (i < rows) row_offsets[i + 1] = carry + excl + v;
+        carry += total;
+    }
+    if (threadIdx.x == 0) row_offsets[0] = 0;
+}
+
+template <bool kVec>
+__global__ __launch_bounds__(kCodecThreads) void encode_compact_kernel(const uint16_t* __restrict__ w,
+                                                                       int64_t cols,
+                                                                       const uint32_t* __restrict__ row_offsets,
+                                                                       uint16_t* __restrict__ values,
+                                                                       int64_t capacity) {
+    __shared__ uint32_t scratch[kCodecThreads / kWave];
+    const int64_t n = blockIdx.x;
+    const uint16_t* row = w + n * cols;
+    const int64_t units = (cols + kUnit - 1) / kUnit;
+    int64_t cursor = row_offsets[n];
+    for (int64_t base = 0; base < units; base += kCodecThreads) {
+        const int64_t u = base + threadIdx.x;
+        const uint4 q = load_unit<kVec>(row, cols, u);
+        const uint32_t m = nonzero_mask8(q);
+        uint32_t total;
+        const uint32_t excl = block_exclusive_scan<kCodecThreads>(__popc(m), scratch, total);
+        int64_t idx = cursor + excl;
+#pragma unroll
+        for (int j = 0; j < kUnit; ++j) {
+            if ((m >> j) & 1u) {
+                if (idx < capacity) values[idx] = (uint16_t)unit_elem(q, j);
+                ++idx;
+            }
+        }
+        cursor += total;
+    }
+}
+
+// Standalone decoder: per step the workgroup owns 2048 columns of its row; the packed values of the
+// step are one contiguous piece of `values`, copied to LDS with aligned dword loads and expanded there.
+template <bool kVec>
+__global__ __launch_bounds__(kCodecThreads) void decode_kernel(const uint32_t* __restrict__ bitmap,
+                                                               const uint16_t* __restrict__ values,
+                                                               const uint32_t* __restrict__ row_offsets,
+                                                               int64_t rows, int64_t cols, int64_t wpr,
+                                                               uint16_t* __restrict__ out) {
+    __shared__ uint32_t stage[kChunkValuesMax / 2 + 8];
+    __shared__ uint32_t lut[kNibbleLutWords];
+    __shared__ uint32_t scratch[kCodecThreads / kWave];
+    nibble_lut_init(lut);
+    __syncthreads();
+    const int64_t n = blockIdx.x;
+    const uint8_t* mask_bytes = reinterpret_cast<const uint8_t*>(bitmap + n * wpr);
+    const uint32_t* values32 = reinterpret_cast<const uint32_t*>(values);
+    uint16_t* row_out = out + n * cols;
+    const int64_t units = (cols + kUnit - 1) / kUnit;
+    const int64_t nnz = row_offsets[rows];
+    int64_t g = row_offsets[n];  // element index in `values` of the next unread value of this row
+    for (int64_t base = 0; base < units; base += kCodecThreads) {
+        const int64_t u = base + threadIdx.x;
+        const uint32_t m = (u < units) ? mask_bytes[u] : 0u;
+        uint32_t total;
+        const uint32_t excl = block_exclusive_scan<kCodecThreads>(__popc(m), scratch, total);
+        const uint32_t parity = (uint32_t)(g & 1);
+        const int64_t gdw = g >> 1;
+        const uint32_t ndw = (parity + total + 1) >> 1;
+        for (uint32_t j = threadIdx.x; j < ndw; j += kCodecThreads) {
+            const int64_t e = 2 * (gdw + j);
+            uint32_t d;
+            if (e + 1 < nnz) d = values32[gdw + j];
+            else d = (e < nnz) ? (uint32_t)values[e] : 0u;  // last, half-filled dword of the array
+            stage[j] = d;
+        }
+        __syncthreads();
+        if (u < units) {
+            const uint4 q = expand_byte(stage, lut, parity + excl, m);
+            const int64_t k0 = u * kUnit;
+            if constexpr (kVec) {
+                *reinterpret_cast<uint4*>(row_out + k0) = q;
+            } else {
+#pragma unroll
+                for (int j = 0; j < kUnit; ++j)
+                    if (k0 + j < cols) row_out[k0 + j] = (uint16_t)unit_elem(q, j);
+            }
+        }
+        g += total;
+        // the next step's block scan synchronises before `stage` is overwritten
+    }
+}
+
+static bool vec_ok(const void* p, int64_t cols) {
+    return (cols % kUnit == 0) && ((reinterpret_cast<uintptr_t>(p) & 15u) == 0);
+}
+
+hipError_t launch_encode(const uint16_t* w, int64_t rows, int64_t cols, uint32_t* bitmap, uint16_t* values,
+                         int64_t capacity, uint32_t* row_offsets, hipStream_t stream) {
+    const int64_t wpr = (cols + 31) / 32;
+    const bool vec = vec_ok(w, cols);
+    if (rows > 0) {
+        if (vec) hipLaunchKernelGGL(encode_count_kernel<true>, dim3((unsigned)rows), dim3(kCodecThreads), 0, stream, w, cols, wpr, bitmap, row_offsets);
+        else hipLaunchKernelGGL(encode_count_kernel<false>, dim3((unsigned)rows), dim3(kCodecThreads), 0, stream, w, cols, wpr, bitmap, row_offsets);
+    }
+    hipLaunchKernelGGL(row_scan_kernel, dim3(1), dim3(kScanThreads), 0, stream, row_offsets, rows);
+    if (values != nullptr && rows > 0 && cols > 0) {
+        if (vec) hipLaunchKernelGGL(encode_compact_kernel<true>, dim3((unsigned)rows), dim3(kCodecThreads), 0, stream, w, cols, row_offsets, values, capacity);
+        else hipLaunchKernelGGL(encode_compact_kernel<false>, dim3((unsigned)rows), dim3(kCodecThreads), 0, stream, w, cols, row_offsets, values, capacity);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_decode(const uint32_t* bitmap, const uint16_t* values, const uint32_t* row_offsets, int64_t rows,
+                         int64_t cols, uint16_t* out, hipStream_t stream) {
+    if (rows == 0 || cols == 0) return hipSuccess;
+    const int64_t wpr = (cols + 31) / 32;
+    if (vec_ok(out, cols))
+        hipLaunchKernelGGL(decode_kernel<true>, dim3((unsigned)rows), dim3(kCodecThreads), 0, stream, bitmap, values, row_offsets, rows, cols, wpr, out);
+    else
+        hipLaunchKernelGGL(decode_kernel<false>, dim3((unsigned)rows), dim3(kCodecThreads), 0, stream, bitmap, values, row_offsets, rows, cols, wpr, out);
+    return hipGetLastError();
+}
+
+}  // namespace salr

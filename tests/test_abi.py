@@ -1,0 +1,93 @@
+"""The C-ABI library loads, exports every symbol include/salr.h declares, and validates arguments on
+the host before any launch.  No GPU needed: no call here reaches a kernel."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "salr.h")
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(salr_[a-z_0-9]+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2601_16991_amd as salr
+    if not os.path.exists(salr.LIB_PATH):
+        from paper_2601_16991_amd import build
+        build.build()
+    return salr.lib()
+
+
+def test_header_declares_the_three_operations():
+    names = _declared_functions()
+    for required in ("salr_encode_bitmap", "salr_decode", "salr_sparse_lowrank_linear"):
+        assert required in names
+
+
+def test_every_declared_symbol_is_exported(lib):
+    for name in _declared_functions():
+        assert hasattr(lib, name), name
+
+
+def test_status_strings(lib):
+    seen = set()
+    for code in range(6):
+        s = lib.salr_status_string(code)
+        assert s and s not in seen
+        seen.add(s)
+
+
+def test_words_per_row(lib):
+    assert lib.salr_bitmap_words_per_row(0) == 0
+    assert lib.salr_bitmap_words_per_row(1) == 1
+    assert lib.salr_bitmap_words_per_row(32) == 1
+    assert lib.salr_bitmap_words_per_row(33) == 2
+    assert lib.salr_bitmap_words_per_row(14336) == 448
+    assert lib.salr_bitmap_words_per_row(-1) == -1
+
+
+def test_workspace_bytes(lib):
+    assert lib.salr_linear_workspace_bytes(16, 4096, 4096, 0) == 0
+    assert lib.salr_linear_workspace_bytes(0, 4096, 4096, 32) == 0
+    assert lib.salr_linear_workspace_bytes(16, 4096, 4096, 32) == 16 * 32 * 2
+    assert lib.salr_linear_workspace_bytes(16, 4096, 4096, 16) == 16 * 32 * 2   # rank padded to 32
+    assert lib.salr_linear_workspace_bytes(1, 4096, 4096, 64) == 256            # rounded to 256 B
+    assert lib.salr_linear_workspace_bytes(16, 4096, 4096, 1000) == 0
+
+
+def test_host_validation_rejects_before_launch(lib):
+    import paper_2601_16991_amd as salr
+    fake = 0x1000  # never dereferenced: every call below fails validation first
+    # negative sizes
+    assert lib.salr_encode_bitmap(fake, -1, 8, fake, None, 0, fake, None) == salr.SALR_ERR_INVALID_ARG
+    assert lib.salr_decode(fake, fake, fake, 4, -2, fake, None) == salr.SALR_ERR_INVALID_ARG
+    # null pointers
+    assert lib.salr_encode_bitmap(None, 4, 8, fake, None, 0, fake, None) == salr.SALR_ERR_INVALID_ARG
+    assert lib.salr_encode_bitmap(fake, 4, 8, fake, None, 0, None, None) == salr.SALR_ERR_INVALID_ARG
+    assert lib.salr_decode(None, fake, fake, 4, 8, fake, None) == salr.SALR_ERR_INVALID_ARG
+    # nnz would not fit 32 bits
+    assert lib.salr_encode_bitmap(fake, 1 << 20, 1 << 20, fake, None, 0, fake, None) == salr.SALR_ERR_SHAPE
+    # linear: K not a multiple of 32, rank too large, workspace missing / too small, null adapters
+    args = dict(M=4, K=64, N=8, R=4)
+
+    def lin(M=4, K=64, N=8, R=4, x=fake, a=fake, b=fake, ws=fake, ws_bytes=1 << 20, y=fake):
+        return lib.salr_sparse_lowrank_linear(x, M, K, N, fake, fake, fake, a, b, R, y, ws, ws_bytes, None)
+
+    assert lin(K=40) == salr.SALR_ERR_SHAPE
+    assert lin(R=257) == salr.SALR_ERR_UNSUPPORTED
+    assert lin(ws=None) == salr.SALR_ERR_CAPACITY
+    assert lin(ws_bytes=16) == salr.SALR_ERR_CAPACITY
+    assert lin(a=None) == salr.SALR_ERR_INVALID_ARG
+    assert lin(x=None) == salr.SALR_ERR_INVALID_ARG
+    assert lin(y=None) == salr.SALR_ERR_INVALID_ARG
+    assert lin(M=-1) == salr.SALR_ERR_INVALID_ARG
+    # empty problems are no-ops
+    assert lin(M=0) == salr.SALR_OK
+    assert lin(N=0) == salr.SALR_OK

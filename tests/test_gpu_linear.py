@@ -1,0 +1,133 @@
+"""GPU parity: salr_sparse_lowrank_linear through the C boundary vs the fp64 CPU oracle.
+
+Bar: max |Y - Y_ref| <= 1e-2 * max |Y_ref| (bf16 inputs, fp32 accumulation, bf16 output)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import salr_workloads as wl
+from gpu_util import dev, to_dev_u16, to_dev_u32, to_host_u16, y_to_f64
+
+pytestmark = pytest.mark.gpu
+
+REL_TOL = 1e-2
+
+
+def _salr():
+    import paper_2601_16991_amd as salr
+    return salr
+
+
+def _run(x, w_hat, a_cat, b_cat):
+    salr = _salr()
+    rb, rv, ro = oracle.encode(w_hat)
+    y = salr.linear(to_dev_u16(x), to_dev_u32(rb), to_dev_u16(rv), to_dev_u32(ro),
+                    None if a_cat is None else to_dev_u16(a_cat), None if b_cat is None else to_dev_u16(b_cat))
+    torch.cuda.synchronize()
+    return y_to_f64(y)
+
+
+def _assert_close(y, y_ref, label, rel=REL_TOL):
+    scale = float(np.max(np.abs(y_ref))) if y_ref.size else 0.0
+    err = float(np.max(np.abs(y - y_ref))) if y_ref.size else 0.0
+    print(f"[linear] {label}: max|d|={err:.3e} scale={scale:.3e} rel={err / scale if scale else 0:.2e}", flush=True)
+    assert err <= rel * scale + 1e-30, f"{label}: {err} > {rel} * {scale}"
+
+
+def _problem(M, K, N, ranks, seed, density=0.5, std_ab=0.01):
+    rng = np.random.default_rng(seed)
+    x = wl.gaussian_bf16((M, K), 1.0, seed + 1)
+    w = wl.gaussian_bf16((N, K), 0.02, seed + 2)
+    w[rng.random((N, K)) >= density] = 0
+    As = [wl.gaussian_bf16((K, r), std_ab, seed + 10 + i) for i, r in enumerate(ranks)]
+    Bs = [wl.gaussian_bf16((r, N), std_ab, seed + 20 + i) for i, r in enumerate(ranks)]
+    a_cat, b_cat = wl.concat_adapters(As, Bs) if ranks else (None, None)
+    return x, w, a_cat, b_cat
+
+
+def test_tiny_config():
+    cfg = wl.CONFIGS["tiny"]
+    w_hat = oracle.mask_topk_rows(wl.dense_weight(cfg), cfg.keep(500))
+    x = wl.activations(cfg, cfg.Ms[0])
+    a_cat, b_cat = wl.concat_adapters(*wl.adapters(cfg))
+    _assert_close(_run(x, w_hat, a_cat, b_cat), oracle.linear(x, w_hat, a_cat, b_cat), "tiny")
+
+
+@pytest.mark.parametrize("M,K,N,ranks", [
+    (1, 64, 16, (8,)), (3, 96, 40, (4, 4)), (17, 128, 100, (16, 16)), (65, 256, 130, (5,)), (100, 32, 64, (33,)),
+    (16, 512, 64, ()), (130, 160, 70, (64, 64, 64, 64)), (2, 2048, 48, (1,)), (64, 64, 64, (32,)),
+])
+def test_ragged_shapes(M, K, N, ranks):
+    x, w, a_cat, b_cat = _problem(M, K, N, ranks, 31 * M + K + N, std_ab=0.05)
+    _assert_close(_run(x, w, a_cat, b_cat), oracle.linear(x, w, a_cat, b_cat), f"M{M} K{K} N{N} R{sum(ranks)}")
+
+
+def test_adapter_term_alone():
+    """What = 0 isolates (X A_cat) B_cat: the tolerance is then relative to the adapter term itself."""
+    x, w, a_cat, b_cat = _problem(16, 512, 256, (16, 16), 5)
+    z = np.zeros_like(w)
+    _assert_close(_run(x, z, a_cat, b_cat), oracle.linear(x, z, a_cat, b_cat), "adapters only")
+
+
+def test_adapter_term_by_difference():
+    """Y - Y|R=0 against the oracle's adapter term: a mangled adapter cannot hide behind the base product."""
+    cfg = wl.CONFIGS["tiny"]
+    w_hat = oracle.mask_topk_rows(wl.dense_weight(cfg), cfg.keep(500))
+    x = wl.activations(cfg, 16)
+    a_cat, b_cat = wl.concat_adapters(*wl.adapters(cfg, std=0.05))
+    y_full = _run(x, w_hat, a_cat, b_cat)
+    y_base = _run(x, w_hat, None, None)
+    ref_delta = oracle.linear(x, np.zeros_like(w_hat), a_cat, b_cat)
+    ref_full = oracle.linear(x, w_hat, a_cat, b_cat)
+    # two bf16 roundings of Y (each <= 2^-9 relative to |Y|) bound the difference's error
+    tol = 2 * 2.0 ** -8 * float(np.max(np.abs(ref_full))) + 1e-2 * float(np.max(np.abs(ref_delta)))
+    err = float(np.max(np.abs((y_full - y_base) - ref_delta)))
+    print(f"[linear] adapter by difference: err={err:.3e} tol={tol:.3e} |delta|={np.max(np.abs(ref_delta)):.3e}", flush=True)
+    assert err <= tol
+    assert float(np.max(np.abs(ref_delta))) > 4 * tol  # the check has teeth
+
+
+def test_no_adapters_dense_and_empty_weight():
+    x, w, _, _ = _problem(8, 256, 96, (), 9, density=1.0)   # p = 0: every bit set
+    _assert_close(_run(x, w, None, None), oracle.linear(x, w, None, None), "dense bitmap")
+    z = np.zeros_like(w)
+    y = _run(x, z, None, None)
+    assert (y == 0).all()
+
+
+def test_identity_activations_read_out_weights_exactly():
+    """X = I: Y rows are columns of What (exactly representable), so the result is bit-exact."""
+    K, N = 64, 48
+    _, w, _, _ = _problem(1, K, N, (), 11)
+    eye = wl.f32_to_bf16_bits(np.eye(K, dtype=np.float32))
+    y = _run(eye, w, None, None)
+    assert np.array_equal(y, oracle.bf16_to_f64(w).T)
+
+
+def test_q_proj_full_size_all_M():
+    cfg = wl.CONFIGS["llama3_8b_q_proj"]
+    w_hat = oracle.mask_topk_rows(wl.dense_weight(cfg), cfg.keep(500))
+    a_cat, b_cat = wl.concat_adapters(*wl.adapters(cfg))
+    salr = _salr()
+    rb, rv, ro = oracle.encode(w_hat)
+    d = (to_dev_u32(rb), to_dev_u16(rv), to_dev_u32(ro), to_dev_u16(a_cat), to_dev_u16(b_cat))
+    for M in cfg.Ms:
+        x = wl.activations(cfg, M)
+        y = salr.linear(to_dev_u16(x), *d)
+        torch.cuda.synchronize()
+        _assert_close(y_to_f64(y), oracle.linear(x, w_hat, a_cat, b_cat), f"q_proj M={M}")
+
+
+def test_gate_up_prefill_sampled_rows():
+    """Full-size launch (M = 2048); the oracle checks a fixed sample of 8 rows of X across all N."""
+    cfg = wl.CONFIGS["llama3_8b_gate_up_proj"]
+    M = cfg.Ms[0]
+    w_hat = oracle.mask_topk_rows(wl.dense_weight(cfg), cfg.keep(500))
+    a_cat, b_cat = wl.concat_adapters(*wl.adapters(cfg))
+    x = wl.activations(cfg, M)
+    y = _run(x, w_hat, a_cat, b_cat)
+    rows = np.array([0, 1, 63, 64, 777, 1024, 2046, 2047])
+    y_ref = oracle.linear(np.ascontiguousarray(x[rows]), w_hat, a_cat, b_cat)
+    _assert_close(y[rows], y_ref, "gate/up M=2048 (8 sampled rows)")
+    assert np.isfinite(y).all()
