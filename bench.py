@@ -1,0 +1,351 @@
+#!/usr/bin/env python3
+"""Benchmark of the SALR bitmap-sparse + concatenated-LoRA linear on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-extras] [--no-cpu-baseline]
+
+A step is one call of salr_sparse_lowrank_linear (decode stage, contraction, both adapter stages) on
+the Llama-3-8B q_proj-shaped layer (W [4096, 4096], 50 % per-row magnitude sparsity, two rank-16
+adapters concatenated, X [16, 4096]) with all operands resident in HBM.  Successive steps rotate over
+enough distinct encoded copies of the weight that the cycled footprint exceeds twice the 256 MB
+Infinity Cache, so the weight stream comes from HBM, not from cache.
+
+Prints ONE JSON line on stdout (everything else goes to stderr):
+  value     = algorithmic bytes of one call / wall-clock time per step (whole job, K steps bracketed
+              by synchronize), GB/s;
+  roofline  = the fused kernel's own duration from HIP events recorded around its launch (a second
+              pass of K steps, same rotation), against the 8 TB/s HBM peak;
+  cpu_baseline = the CPU oracle (fp64, OpenMP) timed on this machine's host cores on the same workload.
+Extra keys report the other batch sizes, the prefill-sized gate/up layer against the bf16 MFMA peak,
+the dense bf16 GEMM (hipBLASLt via torch.matmul) under the same rotation, and encode/decode.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "TFLOP/s & HBM GB/s of bitmap-sparse+LoRA linear vs roofline; speedup vs dense"
+HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+ROTATE_BYTES = 640 * 1024 * 1024
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+class HipEvents:
+    """hipEvent_t pairs through the HIP runtime that torch already loaded."""
+
+    def __init__(self, n):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+        self.pairs = []
+        for _ in range(n):
+            a, b = ctypes.c_void_p(), ctypes.c_void_p()
+            assert self.hip.hipEventCreate(ctypes.byref(a)) == 0
+            assert self.hip.hipEventCreate(ctypes.byref(b)) == 0
+            self.pairs.append((a, b))
+
+    def elapsed_ms(self):
+        out = []
+        for a, b in self.pairs:
+            self.hip.hipEventSynchronize(b)
+            ms = ctypes.c_float()
+            rc = self.hip.hipEventElapsedTime(ctypes.byref(ms), a, b)
+            assert rc == 0, rc
+            out.append(ms.value)
+        return out
+
+    def close(self):
+        for a, b in self.pairs:
+            self.hip.hipEventDestroy(a)
+            self.hip.hipEventDestroy(b)
+        self.pairs = []
+
+
+def magnitude_mask_rows_device(w_i16, keep):
+    """Input synthesis for the benchmark (not part of the timed path): per-row magnitude top-`keep`
+    with ties to the lower column, done with torch on the GPU."""
+    import torch
+    mag = w_i16.to(torch.int32) & 0x7FFF
+    idx = torch.sort(mag, dim=1, descending=True, stable=True).indices[:, :keep]
+    out = torch.zeros_like(w_i16)
+    out.scatter_(1, idx, w_i16.gather(1, idx))
+    return out
+
+
+class Layer:
+    """Encoded weight copies + adapters of one synthetic layer on the device."""
+
+    def __init__(self, cfg, permille, max_copies=64):
+        import numpy as np
+        import torch
+        import paper_2601_16991_amd as salr
+        import salr_workloads as wl
+        dev = torch.device("cuda:0")
+        self.cfg, self.permille = cfg, permille
+        w = torch.from_numpy(wl.dense_weight(cfg).view(np.int16)).to(dev)
+        self.w_hat = magnitude_mask_rows_device(w, cfg.keep(permille))
+        del w
+        bitmap, values, offsets = salr.encode(self.w_hat)
+        torch.cuda.synchronize()
+        self.nnz = int(values.numel())
+        assert self.nnz == cfg.N * cfg.keep(permille), (self.nnz, cfg.N * cfg.keep(permille))
+        enc_bytes = bitmap.numel() * 4 + self.nnz * 2 + offsets.numel() * 4
+        self.ncopies = int(min(max_copies, max(2, -(-ROTATE_BYTES // enc_bytes))))
+        self.enc = [(bitmap, values, offsets)]
+        for _ in range(self.ncopies - 1):
+            v = salr.values_alloc(self.nnz, dev)
+            v.copy_(values)
+            self.enc.append((bitmap.clone(), v, offsets.clone()))
+        As, Bs = wl.adapters(cfg)
+        a_cat, b_cat = wl.concat_adapters(As, Bs)
+        self.a_cat = torch.from_numpy(a_cat.view(np.int16)).to(dev)
+        self.b_cat = torch.from_numpy(b_cat.view(np.int16)).to(dev)
+        self.R = cfg.R
+
+    def dense_copies(self):
+        import torch
+        n = int(min(32, max(2, -(-ROTATE_BYTES // (self.w_hat.numel() * 2)))))
+        return [self.w_hat.view(torch.bfloat16).clone() for _ in range(n)]
+
+
+def time_linear(layer, M, steps, warmup, events=False):
+    """(ms per step by wall clock, list of per-launch kernel ms from HIP events or None)."""
+    import numpy as np
+    import torch
+    import paper_2601_16991_amd as salr
+    import salr_workloads as wl
+    cfg = layer.cfg
+    dev = torch.device("cuda:0")
+    x = torch.from_numpy(wl.activations(cfg, M).view(np.int16)).to(dev)
+    y = torch.empty((M, cfg.N), dtype=torch.int16, device=dev)
+    ws_bytes = salr.salr_linear_workspace_bytes(M, cfg.K, cfg.N, layer.R)
+    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
+
+    def call(i):
+        b, v, o = layer.enc[i % layer.ncopies]
+        salr.salr_sparse_lowrank_linear(x, b, v, o, layer.a_cat, layer.b_cat, y, ws)
+
+    for i in range(warmup):
+        call(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        call(i)
+    torch.cuda.synchronize()
+    ms_wall = (time.perf_counter() - t0) * 1e3 / steps
+    kernel_ms = None
+    if events:
+        ev = HipEvents(steps)
+        for i in range(steps):
+            a, b = ev.pairs[i]
+            salr.salr_set_kernel_timing_events(a, b)
+            call(i)
+        salr.salr_set_kernel_timing_events(None, None)
+        torch.cuda.synchronize()
+        kernel_ms = ev.elapsed_ms()
+        ev.close()
+    return ms_wall, kernel_ms
+
+
+def time_dense(layer, M, steps, warmup, with_lora):
+    import numpy as np
+    import torch
+    import salr_workloads as wl
+    cfg = layer.cfg
+    dev = torch.device("cuda:0")
+    x = torch.from_numpy(wl.activations(cfg, M).view(np.int16)).to(dev).view(torch.bfloat16)
+    ws = layer.dense_copies()
+    a = layer.a_cat.view(torch.bfloat16)
+    b = layer.b_cat.view(torch.bfloat16)
+
+    def call(i):
+        y = torch.matmul(x, ws[i % len(ws)].t())
+        if with_lora:
+            y = y + torch.matmul(torch.matmul(x, a), b)
+        return y
+
+    for i in range(warmup):
+        call(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        call(i)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def time_codec(layer, steps):
+    import torch
+    import paper_2601_16991_amd as salr
+    cfg = layer.cfg
+    bitmap, values, offsets = layer.enc[0]
+    out = torch.empty((cfg.N, cfg.K), dtype=torch.int16, device=bitmap.device)
+    res = {}
+    for name, fn in (("decode", lambda: salr.salr_decode(bitmap, values, offsets, cfg.N, cfg.K, out)),
+                     ("encode", lambda: salr.salr_encode_bitmap(layer.w_hat, bitmap, values, offsets))):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        nbytes = 2 * cfg.N * cfg.K + cfg.N * cfg.K // 8 + 2 * layer.nnz + 4 * (cfg.N + 1)
+        res[name] = {"ms": round(ms, 4), "GB/s": round(nbytes / ms / 1e6, 1)}
+    return res
+
+
+def cpu_baseline(cfg, permille, M, alg_bytes, budget_s=10.0, max_reps=50):
+    import numpy as np
+    import oracle
+    import salr_workloads as wl
+    w_hat = oracle.mask_topk_rows(wl.dense_weight(cfg), cfg.keep(permille))
+    x = wl.activations(cfg, M)
+    a_cat, b_cat = wl.concat_adapters(*wl.adapters(cfg))
+    oracle.linear(x[:1], w_hat, a_cat, b_cat)  # warm the library
+    reps, t0 = 0, time.perf_counter()
+    while True:
+        oracle.linear(x, w_hat, a_cat, b_cat)
+        reps += 1
+        el = time.perf_counter() - t0
+        if el >= budget_s or reps >= max_reps:
+            break
+    s = el / reps
+    return {"value": round(alg_bytes / s / 1e9, 4), "unit": "GB/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"{reps} full calls of the fp64 oracle linear on the same workload (M={M}, all {cfg.N} outputs), "
+                      f"{s * 1e3:.1f} ms per call"}
+
+
+def load_traffic(workload_key):
+    """HBM traffic per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE), if a summary was committed."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get(workload_key)
+    except Exception:
+        return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--no-extras", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
+              "(no collectives, no sharding in this library)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2601_16991_amd as salr
+    import salr_workloads as wl
+    salr.lib()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    log("device:", torch.cuda.get_device_name(0))
+
+    cfg = wl.CONFIGS["llama3_8b_q_proj"]
+    permille, M = 500, 16
+    t_prep = time.perf_counter()
+    layer = Layer(cfg, permille)
+    log(f"prepared {cfg.name}: nnz={layer.nnz} copies={layer.ncopies} ({time.perf_counter() - t_prep:.1f}s)")
+
+    alg_bytes = wl.algorithmic_bytes(M, cfg.K, cfg.N, layer.R, layer.nnz)
+    alg_flops = wl.algorithmic_flops(M, cfg.K, cfg.N, layer.R)
+    ms_wall, kernel_ms = time_linear(layer, M, args.steps, args.warmup, events=True)
+    k_avg = float(np.mean(kernel_ms))
+    k_med = float(np.median(kernel_ms))
+    log(f"M={M}: wall {ms_wall * 1e3:.2f} us/step, kernel avg {k_avg * 1e3:.2f} us (median {k_med * 1e3:.2f})")
+    dense_ms = time_dense(layer, M, args.steps, args.warmup, with_lora=False)
+    dense_lora_ms = time_dense(layer, M, args.steps, args.warmup, with_lora=True)
+    log(f"dense bf16 GEMM {dense_ms * 1e3:.2f} us, dense + unfused LoRA {dense_lora_ms * 1e3:.2f} us")
+
+    achieved = alg_bytes / (k_avg * 1e-3) / 1e9
+    result = {
+        "metric": METRIC,
+        "value": round(alg_bytes / (ms_wall * 1e-3) / 1e9, 2),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_wall, 6),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name} W[{cfg.N},{cfg.K}] p=0.{permille // 100} R={layer.R} M={M}",
+                   "weight_copies_rotated": layer.ncopies, "algorithmic_bytes": alg_bytes,
+                   "algorithmic_flops": alg_flops},
+        "tflops": round(alg_flops / (ms_wall * 1e-3) / 1e12, 3),
+        "speedup_vs_dense_gemm": round(dense_ms / ms_wall, 3),
+        "speedup_vs_dense_gemm_plus_lora": round(dense_lora_ms / ms_wall, 3),
+        "dense_gemm_ms": round(dense_ms, 6),
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": load_traffic(f"{cfg.name}_M{M}"),
+                     "kernel": "fused decode+GEMM kernel of salr_sparse_lowrank_linear",
+                     "kernel_avg_us": round(k_avg * 1e3, 3), "kernel_median_us": round(k_med * 1e3, 3)},
+    }
+
+    if not args.no_extras:
+        extras = {}
+        for m in (1, 4):
+            w_ms, k_ms = time_linear(layer, m, args.steps, args.warmup, events=True)
+            ab = wl.algorithmic_bytes(m, cfg.K, cfg.N, layer.R, layer.nnz)
+            d_ms = time_dense(layer, m, args.steps, args.warmup, with_lora=False)
+            extras[f"{cfg.name}_M{m}"] = {
+                "ms_per_step": round(w_ms, 6), "GB/s": round(ab / w_ms / 1e6, 1),
+                "kernel_avg_us": round(float(np.mean(k_ms)) * 1e3, 3),
+                "hbm_frac_kernel": round(ab / (float(np.mean(k_ms)) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                "speedup_vs_dense_gemm": round(d_ms / w_ms, 3)}
+            log(f"M={m}: {extras[f'{cfg.name}_M{m}']}")
+        extras["codec_" + cfg.name] = time_codec(layer, 20)
+        log("codec:", extras["codec_" + cfg.name])
+        del layer
+        torch.cuda.empty_cache()
+        # prefill-sized, MFMA-bound layer
+        cfg2 = wl.CONFIGS["llama3_8b_gate_up_proj"]
+        m2 = cfg2.Ms[0]
+        layer2 = Layer(cfg2, 500, max_copies=4)
+        steps2 = max(5, min(args.steps, 30))
+        w_ms, k_ms = time_linear(layer2, m2, steps2, 3, events=True)
+        fl = wl.algorithmic_flops(m2, cfg2.K, cfg2.N, layer2.R)
+        d_ms = time_dense(layer2, m2, steps2, 3, with_lora=False)
+        k2 = float(np.mean(k_ms))
+        extras[f"{cfg2.name}_M{m2}"] = {
+            "ms_per_step": round(w_ms, 5), "TFLOP/s": round(fl / w_ms / 1e9, 1),
+            "kernel_avg_us": round(k2 * 1e3, 2), "mfma_frac_kernel": round(fl / (k2 * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+            "dense_gemm_ms": round(d_ms, 5), "dense_gemm_TFLOP/s": round(2 * m2 * cfg2.N * cfg2.K / d_ms / 1e9, 1),
+            "speedup_vs_dense_gemm": round(d_ms / w_ms, 3)}
+        log(f"{cfg2.name} M={m2}: {extras[f'{cfg2.name}_M{m2}']}")
+        del layer2
+        result["extras"] = extras
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, permille, M, alg_bytes)
+        log("cpu_baseline:", result["cpu_baseline"])
+    else:
+        result["cpu_baseline"] = None
+
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

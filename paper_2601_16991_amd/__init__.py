@@ -53,6 +53,8 @@ def lib() -> ctypes.CDLL:
         L.salr_sparse_lowrank_linear.restype = ctypes.c_int
         L.salr_sparse_lowrank_linear.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _vp,
                                                  ctypes.c_size_t, _vp]
+        L.salr_set_kernel_timing_events.restype = None
+        L.salr_set_kernel_timing_events.argtypes = [_vp, _vp]
         _lib = L
     return _lib
 
@@ -130,6 +132,11 @@ def salr_sparse_lowrank_linear(x: torch.Tensor, bitmap: torch.Tensor, values: to
                                           _ptr(a_cat, _BF16_TYPES, "a_cat"), _ptr(b_cat, _BF16_TYPES, "b_cat"), R,
                                           _ptr(y, _BF16_TYPES, "y"), ws_ptr, ws_bytes, _stream(stream))
     _check(st, "salr_sparse_lowrank_linear")
+
+
+def salr_set_kernel_timing_events(start_event: Optional[int], stop_event: Optional[int]) -> None:
+    """Measurement hook: hipEvent_t handles (as integers) recorded around the fused kernel; None, None = off."""
+    lib().salr_set_kernel_timing_events(start_event, stop_event)
 
 
 # ---------------------------------------------------------------------------------------------------

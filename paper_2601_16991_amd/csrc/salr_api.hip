@@ -82,4 +82,9 @@ salr_status_t salr_sparse_lowrank_linear(const uint16_t* x, int64_t M, int64_t K
     return e == hipSuccess ? SALR_OK : SALR_ERR_HIP;
 }
 
+void salr_set_kernel_timing_events(void* start_event, void* stop_event) {
+    salr::g_timing_events.start = static_cast<hipEvent_t>(start_event);
+    salr::g_timing_events.stop = static_cast<hipEvent_t>(stop_event);
+}
+
 }  // extern "C"

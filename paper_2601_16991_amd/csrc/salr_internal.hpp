@@ -31,4 +31,11 @@ struct LinearArgs {
 
 hipError_t launch_linear(const LinearArgs& args, hipStream_t stream);
 
+// Optional events recorded around the fused kernel's launch (measurement hook of the boundary).
+struct TimingEvents {
+    hipEvent_t start = nullptr;
+    hipEvent_t stop = nullptr;
+};
+extern thread_local TimingEvents g_timing_events;
+
 }  // namespace salr

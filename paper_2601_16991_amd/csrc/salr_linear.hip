@@ -195,6 +195,8 @@ __global__ __launch_bounds__(kGenThreads) void linear_generic_kernel(
         }
 }
 
+thread_local TimingEvents g_timing_events;
+
 hipError_t launch_linear(const LinearArgs& a, hipStream_t stream) {
     if (a.M == 0 || a.N == 0) return hipSuccess;
     const int R = (int)a.R;
@@ -203,9 +205,13 @@ hipError_t launch_linear(const LinearArgs& a, hipStream_t stream) {
         hipLaunchKernelGGL(adapter_t_kernel, dim3((unsigned)a.M), dim3(kAdapterThreads), 0, stream, a.x, a.a_cat, a.K, R,
                            Rpad, a.t);
     }
+    const TimingEvents ev = g_timing_events;
+    const bool timed = ev.start != nullptr && ev.stop != nullptr;
+    if (timed) (void)hipEventRecord(ev.start, stream);
     dim3 grid((unsigned)((a.N + kGenTN - 1) / kGenTN), (unsigned)((a.M + kGenTM - 1) / kGenTM));
     hipLaunchKernelGGL(linear_generic_kernel, grid, dim3(kGenThreads), 0, stream, a.x, a.M, a.K, a.N, a.bitmap, a.values,
                        a.row_offsets, a.t, a.b_cat, R, Rpad, a.y);
+    if (timed) (void)hipEventRecord(ev.stop, stream);
     return hipGetLastError();
 }
 
