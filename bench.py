@@ -134,9 +134,11 @@ def time_linear(layer, M, steps, warmup, events=False):
     ws_bytes = salr.salr_linear_workspace_bytes(M, cfg.K, cfg.N, layer.R)
     ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
 
+    calls = [salr.PreparedLinear(x, b, v, o, layer.a_cat, layer.b_cat, y, ws) for (b, v, o) in layer.enc]
+    stream = torch.cuda.current_stream().cuda_stream or None
+
     def call(i):
-        b, v, o = layer.enc[i % layer.ncopies]
-        salr.salr_sparse_lowrank_linear(x, b, v, o, layer.a_cat, layer.b_cat, y, ws)
+        calls[i % layer.ncopies].run(stream)
 
     for i in range(warmup):
         call(i)

@@ -131,10 +131,10 @@ salr_status_t salr_sparse_lowrank_linear(const uint16_t* x, int64_t M, int64_t K
 
 /*
  * Measurement hook (not part of the method): when both events are non-NULL, the next calls of
- * salr_sparse_lowrank_linear on this host thread record `start_event` immediately before and
- * `stop_event` immediately after the launch of the fused decode+GEMM kernel (the adapter pre-kernel,
- * when one is used, stays outside the pair), on the stream of that call.  Both are hipEvent_t passed
- * as void*, created by the caller with timing enabled.  Pass NULL, NULL to switch the hook off.
+ * salr_sparse_lowrank_linear on this host thread attach the two events to the launch of the fused
+ * decode+GEMM kernel: `start_event` takes the time the kernel begins executing and `stop_event` the
+ * time it ends (the adapter pre-kernel stays outside the pair).  Both are hipEvent_t passed as
+ * void*, created by the caller with timing enabled.  Pass NULL, NULL to switch the hook off.
  */
 void salr_set_kernel_timing_events(void* start_event, void* stop_event);
 

@@ -134,6 +134,33 @@ def salr_sparse_lowrank_linear(x: torch.Tensor, bitmap: torch.Tensor, values: to
     _check(st, "salr_sparse_lowrank_linear")
 
 
+class PreparedLinear:
+    """The argument list of one salr_sparse_lowrank_linear call, marshalled once: ``run()`` is then a
+    single foreign call on the stream that is current at that moment (for launch-bound loops)."""
+
+    def __init__(self, x, bitmap, values, row_offsets, a_cat, b_cat, y, workspace):
+        M, K = x.shape
+        N = y.shape[1]
+        R = 0 if a_cat is None else a_cat.shape[1]
+        if y.shape[0] != M or bitmap.shape[0] != N or row_offsets.numel() != N + 1:
+            raise ValueError("inconsistent shapes")
+        if R and (tuple(a_cat.shape) != (K, R) or tuple(b_cat.shape) != (R, N)):
+            raise ValueError("adapter shapes")
+        self._keep = (x, bitmap, values, row_offsets, a_cat, b_cat, y, workspace)
+        ws_ptr = None if workspace is None else workspace.data_ptr()
+        ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+        self._args = (_ptr(x, _BF16_TYPES, "x"), M, K, N, _ptr(bitmap, _U32_TYPES, "bitmap"),
+                      _ptr(values, _BF16_TYPES, "values"), _ptr(row_offsets, _U32_TYPES, "row_offsets"),
+                      _ptr(a_cat, _BF16_TYPES, "a_cat"), _ptr(b_cat, _BF16_TYPES, "b_cat"), R,
+                      _ptr(y, _BF16_TYPES, "y"), ws_ptr, ws_bytes)
+        self._fn = lib().salr_sparse_lowrank_linear
+
+    def run(self, stream_handle: Optional[int] = None) -> None:
+        st = self._fn(*self._args, stream_handle)
+        if st != SALR_OK:
+            raise SalrError(st, "salr_sparse_lowrank_linear")
+
+
 def salr_set_kernel_timing_events(start_event: Optional[int], stop_event: Optional[int]) -> None:
     """Measurement hook: hipEvent_t handles (as integers) recorded around the fused kernel; None, None = off."""
     lib().salr_set_kernel_timing_events(start_event, stop_event)

@@ -10,8 +10,6 @@ constexpr int64_t kMaxCols = 2147483647LL - 31;   // so that ceil(cols/32)*32 st
 constexpr int64_t kMaxRank = 256;
 constexpr int64_t kMaxM = 65535LL * 64;           // gridDim.y of the tiled kernels
 
-size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
-
 }  // namespace
 
 extern "C" {
@@ -55,7 +53,7 @@ salr_status_t salr_decode(const uint32_t* bitmap, const uint16_t* values, const 
 
 size_t salr_linear_workspace_bytes(int64_t M, int64_t K, int64_t N, int64_t R) {
     if (M <= 0 || K < 0 || N <= 0 || R <= 0 || R > kMaxRank) return 0;
-    return round_up((size_t)M * (size_t)salr::adapter_rank_padded(R) * sizeof(uint16_t), 256);
+    return salr::linear_workspace_bytes(M, R);
 }
 
 salr_status_t salr_sparse_lowrank_linear(const uint16_t* x, int64_t M, int64_t K, int64_t N, const uint32_t* bitmap,

@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stddef.h>
 #include <stdint.h>
 
@@ -26,10 +27,8 @@ struct LinearArgs {
     const uint16_t* b_cat;
     int64_t R;
     uint16_t* y;
-    uint16_t* t;  // workspace: [M, adapter_rank_padded(R)] bf16
+    uint16_t* t;  // workspace (see linear_workspace_bytes)
 };
-
-hipError_t launch_linear(const LinearArgs& args, hipStream_t stream);
 
 // Optional events recorded around the fused kernel's launch (measurement hook of the boundary).
 struct TimingEvents {
@@ -37,5 +36,30 @@ struct TimingEvents {
     hipEvent_t stop = nullptr;
 };
 extern thread_local TimingEvents g_timing_events;
+
+// Launch `kernel`; when both events are set they receive the kernel's own begin/end timestamps.
+#define SALR_LAUNCH(kernel, grid, block, stream, ev, ...)                                                    \
+    do {                                                                                                      \
+        if ((ev).start != nullptr && (ev).stop != nullptr)                                                    \
+            hipExtLaunchKernelGGL(kernel, grid, block, 0, stream, (ev).start, (ev).stop, 0, __VA_ARGS__);     \
+        else                                                                                                  \
+            hipLaunchKernelGGL(kernel, grid, block, 0, stream, __VA_ARGS__);                                  \
+    } while (0)
+
+// Small-batch path: M <= kStreamMaxM; T = X * A_cat arrives as kStreamTSlices split-K partials (fp32).
+constexpr int64_t kStreamMaxM = 64;
+constexpr int kStreamTSlices = 16;
+
+// Workspace the linear needs: the small-batch path keeps fp32 split-K partials of T, the tiled path T in bf16.
+inline size_t linear_workspace_bytes(int64_t M, int64_t R) {
+    if (M <= 0 || R <= 0) return 0;
+    const size_t rp = (size_t)adapter_rank_padded(R);
+    const size_t b = (M <= kStreamMaxM) ? (size_t)kStreamTSlices * (size_t)M * rp * sizeof(float)
+                                        : (size_t)M * rp * sizeof(uint16_t);
+    return (b + 255) / 256 * 256;
+}
+
+hipError_t launch_linear(const LinearArgs& args, hipStream_t stream);
+hipError_t launch_linear_stream(const LinearArgs& args, hipStream_t stream, const TimingEvents& ev);
 
 }  // namespace salr

@@ -4,19 +4,13 @@
 //   adapter_t_kernel        T = X * A_cat, fp32 accumulation, stored bf16 in the workspace
 //   linear_generic_kernel   any shape: 64 x 64 output tile per workgroup, decode of a 64 x 32 weight
 //                           tile into LDS per k-step, bf16 MFMA, adapters as extra k-steps
+#include <hip/hip_ext.h>
+
 #include "salr_device.hpp"
 #include "salr_internal.hpp"
+#include "salr_linear_common.hpp"
 
 namespace salr {
-
-__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x0040u);  // quiet NaN
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
-}
-
-__device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
 
 // ---------------------------------------------------------------------------------------------------
 // T[m, r] = sum_k X[m, k] * A_cat[k, r]   (Sec. 3.2: the first of the two concatenated GEMMs)
@@ -199,6 +193,7 @@ thread_local TimingEvents g_timing_events;
 
 hipError_t launch_linear(const LinearArgs& a, hipStream_t stream) {
     if (a.M == 0 || a.N == 0) return hipSuccess;
+    if (a.M <= kStreamMaxM) return launch_linear_stream(a, stream, g_timing_events);
     const int R = (int)a.R;
     const int Rpad = (int)adapter_rank_padded(a.R);
     if (R > 0) {
@@ -206,12 +201,9 @@ hipError_t launch_linear(const LinearArgs& a, hipStream_t stream) {
                            Rpad, a.t);
     }
     const TimingEvents ev = g_timing_events;
-    const bool timed = ev.start != nullptr && ev.stop != nullptr;
-    if (timed) (void)hipEventRecord(ev.start, stream);
     dim3 grid((unsigned)((a.N + kGenTN - 1) / kGenTN), (unsigned)((a.M + kGenTM - 1) / kGenTM));
-    hipLaunchKernelGGL(linear_generic_kernel, grid, dim3(kGenThreads), 0, stream, a.x, a.M, a.K, a.N, a.bitmap, a.values,
-                       a.row_offsets, a.t, a.b_cat, R, Rpad, a.y);
-    if (timed) (void)hipEventRecord(ev.stop, stream);
+    SALR_LAUNCH(linear_generic_kernel, grid, dim3(kGenThreads), stream, ev, a.x, a.M, a.K, a.N, a.bitmap, a.values,
+                a.row_offsets, (const uint16_t*)a.t, a.b_cat, R, Rpad, a.y);
     return hipGetLastError();
 }
 
