@@ -61,5 +61,6 @@ inline size_t linear_workspace_bytes(int64_t M, int64_t R) {
 
 hipError_t launch_linear(const LinearArgs& args, hipStream_t stream);
 hipError_t launch_linear_stream(const LinearArgs& args, hipStream_t stream, const TimingEvents& ev);
+hipError_t launch_linear_tiled(const LinearArgs& args, hipStream_t stream, const TimingEvents& ev);
 
 }  // namespace salr

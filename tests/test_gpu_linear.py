@@ -57,6 +57,10 @@ def test_tiny_config():
 @pytest.mark.parametrize("M,K,N,ranks", [
     (1, 64, 16, (8,)), (3, 96, 40, (4, 4)), (17, 128, 100, (16, 16)), (65, 256, 130, (5,)), (100, 32, 64, (33,)),
     (16, 512, 64, ()), (130, 160, 70, (64, 64, 64, 64)), (2, 2048, 48, (1,)), (64, 64, 64, (32,)),
+    # M > 64 with K % 128 == 0: the tiled MFMA path, ragged in both tile dimensions
+    (300, 512, 300, (16, 16)), (257, 128, 513, (7,)), (70, 384, 64, ()), (65, 1024, 1030, (40, 60)),
+    # M in 17..64: the streaming path with 2 and 4 m-tiles
+    (33, 640, 50, (8,)), (48, 4096, 32, (16, 16)), (64, 96, 17, ()),
 ])
 def test_ragged_shapes(M, K, N, ranks):
     x, w, a_cat, b_cat = _problem(M, K, N, ranks, 31 * M + K + N, std_ab=0.05)
@@ -88,12 +92,25 @@ def test_adapter_term_by_difference():
     assert float(np.max(np.abs(ref_delta))) > 4 * tol  # the check has teeth
 
 
-def test_no_adapters_dense_and_empty_weight():
-    x, w, _, _ = _problem(8, 256, 96, (), 9, density=1.0)   # p = 0: every bit set
+@pytest.mark.parametrize("M", [8, 200])
+def test_no_adapters_dense_and_empty_weight(M):
+    x, w, _, _ = _problem(M, 256, 96, (), 9, density=1.0)   # p = 0: every bit set
     _assert_close(_run(x, w, None, None), oracle.linear(x, w, None, None), "dense bitmap")
     z = np.zeros_like(w)
     y = _run(x, z, None, None)
     assert (y == 0).all()
+
+
+@pytest.mark.parametrize("M", [4, 96])
+def test_mixed_density_rows(M):
+    """Rows that are empty, dense and in between inside one tile (piece lengths 0 .. 64 per chunk)."""
+    x, w, a_cat, b_cat = _problem(M, 512, 80, (8,), 21, density=0.5)
+    w[3, :] = 0
+    w[5, :] = wl.gaussian_bf16((512,), 0.02, 5)
+    w[5, (w[5] & 0x7FFF) == 0] = 0x3C00
+    w[7, 100:400] = 0
+    w[9, :128] = 0x3C00
+    _assert_close(_run(x, w, a_cat, b_cat), oracle.linear(x, w, a_cat, b_cat), f"mixed density M={M}")
 
 
 def test_identity_activations_read_out_weights_exactly():
