@@ -32,11 +32,11 @@ struct XPair {
     uint4 a, b;      // 16 bf16 of one X row
 };
 
-struct ValueChunk {
-    uint4 q0, q1, q2, q3, q4;  // this thread's share (every second vector) of the row's piece
-    uint32_t off;    // element offset of the piece inside its first vector
-    uint32_t nv;     // vectors in the piece
-};
+// One staged value chunk of a row lives in plain registers (named per ring slot): the thread's share of
+// the piece (every second 16-byte vector), the piece's first vector, the index of its last vector, the
+// element offset of the piece inside its first vector and its vector count.
+#define SALR_VC_DECL(n) uint4 n##_q0, n##_q1, n##_q2; const uint4* n##_vb; uint32_t n##_last, n##_off, n##_nv
+#define SALR_VC_ARGS(n) n##_q0, n##_q1, n##_q2, n##_vb, n##_last, n##_off, n##_nv
 
 __global__ __launch_bounds__(kTiledThreads) void linear_tiled_kernel(
     const uint16_t* __restrict__ x, int64_t M, int64_t K, int64_t N, const uint32_t* __restrict__ bitmap,
@@ -92,35 +92,35 @@ __global__ __launch_bounds__(kTiledThreads) void linear_tiled_kernel(
         p[1] = src.b;
     };
     // request the packed values of the next chunk of this row (bitmap words w0, w1)
-    auto v_issue = [&](ValueChunk& vc, uint32_t w0, uint32_t w1) {
+    auto v_issue = [&](uint4& q0, uint4& q1, uint4& q2, const uint4*& vb, uint32_t& last, uint32_t& off, uint32_t& nv,
+                       uint32_t w0, uint32_t w1) {
         const uint32_t len = __popc(w0) + __popc(w1);
-        vc.off = cur & 7u;
-        vc.nv = len ? (vc.off + len + 7u) >> 3 : 0u;
-        const uint4* vb = vc.nv ? values128 + (cur >> 3) : reinterpret_cast<const uint4*>(x);
-        const uint32_t last = vc.nv ? vc.nv - 1u : 0u;
+        off = cur & 7u;
+        nv = len ? (off + len + 7u) >> 3 : 0u;
+        vb = nv ? values128 + (cur >> 3) : reinterpret_cast<const uint4*>(x);
+        last = nv ? nv - 1u : 0u;
         cur += len;
-        auto fetch = [&](uint32_t v) { return vb[v < last ? v : last]; };  // clamped, not predicated
-        vc.q0 = fetch(h);
-        vc.q1 = fetch(h + 2);
-        vc.q2 = fetch(h + 4);
-        if (__builtin_amdgcn_ballot_w64(vc.nv > 6u)) {  // denser than ~70 %: wave-uniform branch
-            vc.q3 = fetch(h + 6);
-            vc.q4 = fetch(h + 8);
-        }
-    };
-    // park the chunk in the row's LDS slot (only the row's own two threads ever touch the slot)
-    auto v_store = [&](const ValueChunk& vc) {
-        uint4* sv = reinterpret_cast<uint4*>(slot);
-        sv[h] = vc.q0;
-        sv[h + 2] = vc.q1;
-        sv[h + 4] = vc.q2;
-        if (__builtin_amdgcn_ballot_w64(vc.nv > 6u)) {
-            sv[h + 6] = vc.q3;
-            if (h == 0) sv[8] = vc.q4;  // the slot holds 9 vectors
-        }
-        __builtin_amdgcn_wave_barrier();
+        // clamped, not predicated: the three requests go out back to back.  Vectors 6..8 exist only in
+        // pieces denser than ~70 %; v_store fetches them on the spot.
+        q0 = vb[h < last ? h : last];
+        q1 = vb[h + 2 < last ? h + 2 : last];
+        q2 = vb[h + 4 < last ? h + 4 : last];
     };
     uint32_t c_local = 0;  // cursor inside the slot
+    // park the chunk in the row's LDS slot (only the row's own two threads ever touch the slot)
+    auto v_store = [&](const uint4& q0, const uint4& q1, const uint4& q2, const uint4* vb, uint32_t last, uint32_t off,
+                       uint32_t nv) {
+        uint4* sv = reinterpret_cast<uint4*>(slot);
+        sv[h] = q0;
+        sv[h + 2] = q1;
+        sv[h + 4] = q2;
+        if (__builtin_amdgcn_ballot_w64(nv > 6u)) {  // rare, wave-uniform
+            sv[h + 6] = vb[h + 6 < last ? h + 6 : last];
+            if (h == 0) sv[8] = vb[8u < last ? 8u : last];  // the slot holds 9 vectors
+        }
+        __builtin_amdgcn_wave_barrier();
+        c_local = off;  // the slot's cursor restarts at the piece's offset
+    };
     // expand this thread's two byte masks of `word` into Ws[buf]
     auto decode = [&](int buf, uint32_t word) {
         const uint32_t half = (word >> (16 * h)) & 0xFFFFu;
@@ -140,77 +140,89 @@ __global__ __launch_bounds__(kTiledThreads) void linear_tiled_kernel(
     auto mfma_step = [&](int buf) {
         const uint16_t* xa = &Xs[buf][(wm * 128 + frag_row) * kPitch + frag_k];
         const uint16_t* wb = &Ws[buf][(wn * 64 + frag_row) * kPitch + frag_k];
-#pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-            const bf16x8 a0 = *reinterpret_cast<const bf16x8*>(xa + 0 * 32 * kPitch + 16 * kk);
-            const bf16x8 a1 = *reinterpret_cast<const bf16x8*>(xa + 1 * 32 * kPitch + 16 * kk);
-            const bf16x8 a2 = *reinterpret_cast<const bf16x8*>(xa + 2 * 32 * kPitch + 16 * kk);
-            const bf16x8 a3 = *reinterpret_cast<const bf16x8*>(xa + 3 * 32 * kPitch + 16 * kk);
-            const bf16x8 b0 = *reinterpret_cast<const bf16x8*>(wb + 0 * 32 * kPitch + 16 * kk);
-            const bf16x8 b1 = *reinterpret_cast<const bf16x8*>(wb + 1 * 32 * kPitch + 16 * kk);
-            acc00 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b0, acc00, 0, 0, 0);
-            acc01 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b1, acc01, 0, 0, 0);
-            acc10 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b0, acc10, 0, 0, 0);
-            acc11 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b1, acc11, 0, 0, 0);
-            acc20 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2, b0, acc20, 0, 0, 0);
-            acc21 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2, b1, acc21, 0, 0, 0);
-            acc30 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a3, b0, acc30, 0, 0, 0);
-            acc31 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a3, b1, acc31, 0, 0, 0);
-        }
+        auto frag = [](const uint16_t* p) { return *reinterpret_cast<const bf16x8*>(p); };
+        // all twelve 16-byte fragment reads of the step are in flight before the first MFMA issues
+        const bf16x8 a00 = frag(xa), a10 = frag(xa + 32 * kPitch), a20 = frag(xa + 64 * kPitch), a30 = frag(xa + 96 * kPitch);
+        const bf16x8 b00 = frag(wb), b10 = frag(wb + 32 * kPitch);
+        const bf16x8 a01 = frag(xa + 16), a11 = frag(xa + 32 * kPitch + 16), a21 = frag(xa + 64 * kPitch + 16),
+                     a31 = frag(xa + 96 * kPitch + 16);
+        const bf16x8 b01 = frag(wb + 16), b11 = frag(wb + 32 * kPitch + 16);
+        acc00 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a00, b00, acc00, 0, 0, 0);
+        acc01 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a00, b10, acc01, 0, 0, 0);
+        acc10 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a10, b00, acc10, 0, 0, 0);
+        acc11 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a10, b10, acc11, 0, 0, 0);
+        acc20 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a20, b00, acc20, 0, 0, 0);
+        acc21 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a20, b10, acc21, 0, 0, 0);
+        acc30 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a30, b00, acc30, 0, 0, 0);
+        acc31 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a30, b10, acc31, 0, 0, 0);
+        acc00 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a01, b01, acc00, 0, 0, 0);
+        acc01 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a01, b11, acc01, 0, 0, 0);
+        acc10 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a11, b01, acc10, 0, 0, 0);
+        acc11 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a11, b11, acc11, 0, 0, 0);
+        acc20 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a21, b01, acc20, 0, 0, 0);
+        acc21 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a21, b11, acc21, 0, 0, 0);
+        acc30 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a31, b01, acc30, 0, 0, 0);
+        acc31 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a31, b11, acc31, 0, 0, 0);
     };
 
     // ---- prologue: bitmap of 3 super-steps, values of chunks 0 and 1, X of steps 0..2, tile 0 decoded
     uint4 bm0 = load_bitmap(0), bm1 = load_bitmap(1), bm2 = load_bitmap(2);
     XPair xr0 = load_x(0), xr1;
-    ValueChunk vc0, vc1;
-    v_issue(vc0, bm0.x, bm0.y);
-    v_issue(vc1, bm0.z, bm0.w);
+    SALR_VC_DECL(vc0);
+    SALR_VC_DECL(vc1);
+    v_issue(SALR_VC_ARGS(vc0), bm0.x, bm0.y);
+    v_issue(SALR_VC_ARGS(vc1), bm0.z, bm0.w);
     __syncthreads();  // lut
     store_x(0, xr0);
     xr1 = load_x(1);
     xr0 = load_x(2);
-    v_store(vc0);
-    c_local = vc0.off;
+    v_store(SALR_VC_ARGS(vc0));
     decode(0, bm0.x);
-    v_issue(vc0, bm1.x, bm1.y);  // chunk 2
+    v_issue(SALR_VC_ARGS(vc0), bm1.x, bm1.y);  // chunk 2
     __syncthreads();
 
-    // ---- main loop: one super-step (4 k-steps, 2 value chunks, one bitmap vector) per iteration
+    // ---- main loop: one super-step (4 k-steps, 2 value chunks, one bitmap vector) per iteration.
+    // Within a k-step the MFMAs read buffer s%2 while the loaders fill buffer (s+1)%2, so the two halves
+    // may run in either order: waves 0-3 fill first, waves 4-7 multiply first.  Waves w and w+4 share a
+    // SIMD, so on every SIMD one wave's decode overlaps the other wave's MFMAs.
+    const bool fill_first = wave < 4;
     for (int64_t q = 0; q < supers; ++q) {
         const int64_t s0 = 4 * q;
         // step s0 (tile in buffer 0): decode tile s0+1 from chunk 2q, word 1
+        if (!fill_first) mfma_step(0);
         store_x(1, xr1);
         xr1 = load_x(s0 + 3);
         decode(1, bm0.y);
-        mfma_step(0);
+        if (fill_first) mfma_step(0);
         __syncthreads();
         // step s0+1 (buffer 1): chunk 2q+1 becomes current; decode tile s0+2, word 2; request chunk 2q+3
+        if (!fill_first) mfma_step(1);
         store_x(0, xr0);
         xr0 = load_x(s0 + 4);
-        v_store(vc1);
-        c_local = vc1.off;
+        v_store(SALR_VC_ARGS(vc1));
         decode(0, bm0.z);
-        v_issue(vc1, bm1.z, bm1.w);
-        mfma_step(1);
+        v_issue(SALR_VC_ARGS(vc1), bm1.z, bm1.w);
+        if (fill_first) mfma_step(1);
         __syncthreads();
         // step s0+2 (buffer 0): decode tile s0+3, word 3
+        if (!fill_first) mfma_step(0);
         store_x(1, xr1);
         xr1 = load_x(s0 + 5);
         decode(1, bm0.w);
-        mfma_step(0);
+        if (fill_first) mfma_step(0);
         __syncthreads();
         // step s0+3 (buffer 1): chunk 2q+2 becomes current; decode tile s0+4 (word 0 of the next super-step);
         // request chunk 2q+4; rotate the bitmap ring
+        if (!fill_first) mfma_step(1);
         store_x(0, xr0);
         xr0 = load_x(s0 + 6);
-        v_store(vc0);
-        c_local = vc0.off;
+        v_store(SALR_VC_ARGS(vc0));
         decode(0, bm1.x);
-        v_issue(vc0, bm2.x, bm2.y);
+        v_issue(SALR_VC_ARGS(vc0), bm2.x, bm2.y);
         bm0 = bm1;
         bm1 = bm2;
         bm2 = load_bitmap(q + 3);
-        mfma_step(1);
+        if (fill_first) mfma_step(1);
         __syncthreads();
     }
 
@@ -261,7 +273,7 @@ __global__ __launch_bounds__(kTiledThreads) void linear_tiled_kernel(
 // rank tile of 16 columns), 4 waves split K, 16x16x32 bf16 MFMAs, LDS reduction, bf16 output
 // [M, Rpad] with zero padding columns.
 // ---------------------------------------------------------------------------------------------------
-constexpr int kTmWaves = 4;
+constexpr int kTmWaves = 16;
 
 __global__ __launch_bounds__(kTmWaves * 64) void adapter_t_mfma_kernel(const uint16_t* __restrict__ x, int64_t M, int64_t K,
                                                                        const uint16_t* __restrict__ a_cat, int R, int Rpad,
@@ -277,6 +289,7 @@ __global__ __launch_bounds__(kTmWaves * 64) void adapter_t_mfma_kernel(const uin
     f32x4 acc[4];
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
     for (int64_t u = wave; u < units; u += kTmWaves) {
         const int64_t k0 = (u << 5) + 8 * g;
         uint32_t e[8];
