@@ -49,6 +49,7 @@ extern thread_local TimingEvents g_timing_events;
 // Small-batch path: M <= kStreamMaxM; T = X * A_cat arrives as kStreamTSlices split-K partials (fp32).
 constexpr int64_t kStreamMaxM = 64;
 constexpr int kStreamTSlices = 16;
+constexpr int kMaxRankPadded = 256;  // R <= 256: pitch of the T tile the streaming kernels keep in LDS
 
 // Workspace the linear needs: the small-batch path keeps fp32 split-K partials of T, the tiled path T in bf16.
 inline size_t linear_workspace_bytes(int64_t M, int64_t R) {

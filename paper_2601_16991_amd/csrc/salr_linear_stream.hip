@@ -29,20 +29,21 @@ constexpr int kStreamRows = 16;         // weight rows per workgroup
 constexpr int kChunkWords = 4;          // bitmap words per row per chunk (128 columns)
 constexpr int kSlotDwords = 68;         // LDS per row per chunk: 17 vectors of 16 B (128 values + misalignment)
 constexpr int kMaxVecPerLane = 5;       // 17 vectors over the 4 lanes of a row
-constexpr int kMaxRankPadded = 256;     // pitch of the T tile in LDS (R <= 256)
 
-template <int MT>
+template <int MT, int NV>
 struct StreamStage {
     uint4 bm;                           // the chunk's 4 bitmap words of this lane's row
-    uint4 vq[kMaxVecPerLane];           // this lane's share of the row's packed-value piece
+    uint4 vq[NV];                       // this lane's share of the row's packed-value piece
     uint4 xq[kChunkWords * MT];         // X operands of the chunk's 4 k-steps
     uint32_t off;                       // element offset of the piece inside its first 16-byte vector
     uint32_t nv;                        // vectors in the piece
 };
 
 // MT m-tiles of 16 rows, NW waves per workgroup, S chunks in flight per wave.
-template <int MT, int NW, int S, bool kVecBitmap>
-__global__ __launch_bounds__(NW * 64) void linear_stream_kernel(
+// kOwnPrefix: every wave popcounts the bitmap words left of its slice itself (short rows), so the
+// workgroup needs no barrier before the stream starts; otherwise the waves exchange slice counts.
+template <int MT, int NW, int S, bool kVecBitmap, bool kOwnPrefix>
+__global__ __launch_bounds__(NW * 64, (S == 2 && MT == 1) ? 4 : 1) void linear_stream_kernel(
     const uint16_t* __restrict__ x, int M, int64_t K, int64_t N, const uint32_t* __restrict__ bitmap,
     const uint16_t* __restrict__ values, const uint32_t* __restrict__ row_offsets,
     const float* __restrict__ t_partial, const uint16_t* __restrict__ b_cat, int R, int Rpad,
@@ -54,7 +55,7 @@ __global__ __launch_bounds__(NW * 64) void linear_stream_kernel(
     constexpr int kTRows = 16 * MT;
     __shared__ __attribute__((aligned(16))) uint32_t smem[kSmemDwords];
     __shared__ __attribute__((aligned(16))) uint16_t t_lds[kTRows * kMaxRankPadded];  // T = X * A_cat, bf16
-    __shared__ uint32_t lut[kNibbleLutWords];
+    __shared__ uint32_t lut_all[NW][kNibbleLutWords];  // one copy per wave: filled and used wave-synchronously
     __shared__ uint32_t slice_count[NW][kStreamRows];
 
     const int tid = threadIdx.x;
@@ -69,6 +70,7 @@ __global__ __launch_bounds__(NW * 64) void linear_stream_kernel(
     const int64_t chunks_total = (wpr + kChunkWords - 1) / kChunkWords;
     const int64_t c_begin = chunks_total * wave / NW;
     const int64_t c_end = chunks_total * (wave + 1) / NW;
+    uint32_t* lut = lut_all[wave];
     // Rows past N (last workgroup only) are computed as copies of row N-1 and dropped at the store,
     // so no load below needs a per-lane predicate: every address is clamped into range instead.
     const int64_t row_c = row_ok ? row : N - 1;
@@ -79,7 +81,7 @@ __global__ __launch_bounds__(NW * 64) void linear_stream_kernel(
 
     auto load_bitmap_chunk = [&](int64_t c) -> uint4 {
         uint4 q = make_uint4(0, 0, 0, 0);
-        if (c < c_end) {  // wave-uniform
+        if (c < c_end) {  // wave-uniform when c is
             if constexpr (kVecBitmap) {
                 q = *reinterpret_cast<const uint4*>(brow + c * kChunkWords);
             } else {
@@ -130,24 +132,58 @@ __global__ __launch_bounds__(NW * 64) void linear_stream_kernel(
         }
     }
 
-    nibble_lut_init(lut);
+    if (lane < 16) {
+        uint32_t a, b;
+        nibble_lut_entry(lane, a, b);
+        lut[2 * lane] = a;
+        lut[2 * lane + 1] = b;
+    }
+    __builtin_amdgcn_wave_barrier();
 
     // ---- pre-pass: nonzeros of this wave's slice per row.  The first S chunks are already in
     // registers (all 4 lanes of a row hold them); the 4 lanes split the rest.
+    uint32_t longest = 0;  // most nonzeros any 128-column chunk of the slice holds (per lane)
     {
         uint32_t head = 0, tail = 0;
 #pragma unroll
-        for (int i = 0; i < S; ++i) head += __popc(bmq[i].x) + __popc(bmq[i].y) + __popc(bmq[i].z) + __popc(bmq[i].w);
+        for (int i = 0; i < S; ++i) {
+            const uint32_t len = __popc(bmq[i].x) + __popc(bmq[i].y) + __popc(bmq[i].z) + __popc(bmq[i].w);
+            head += len;
+            longest = len > longest ? len : longest;
+        }
         for (int64_t c = c_begin + S + g; c < c_end; c += 4) {
             const uint4 q = load_bitmap_chunk(c);
-            tail += __popc(q.x) + __popc(q.y) + __popc(q.z) + __popc(q.w);
+            const uint32_t len = __popc(q.x) + __popc(q.y) + __popc(q.z) + __popc(q.w);
+            tail += len;
+            longest = len > longest ? len : longest;
         }
-        tail += __shfl_xor(tail, 16, 64);
-        tail += __shfl_xor(tail, 32, 64);
-        if (g == 0) slice_count[wave][n] = head + tail;
+        if constexpr (kOwnPrefix) {
+            // nonzeros left of the slice: at most 7 chunks per lane (rows of <= 32 chunks), all in flight at once
+            uint32_t before = 0;
+            uint4 left[7];  // no branches: chunks past the slice start re-read chunk 0 and are dropped
+#pragma unroll
+            for (int i = 0; i < 7; ++i) {
+                const int64_t c = g + 4 * i;
+                left[i] = *reinterpret_cast<const uint4*>(brow + (c < c_begin ? c : 0) * kChunkWords);
+            }
+#pragma unroll
+            for (int i = 0; i < 7; ++i) {
+                const uint32_t cnt = __popc(left[i].x) + __popc(left[i].y) + __popc(left[i].z) + __popc(left[i].w);
+                before += (g + 4 * i < c_begin) ? cnt : 0u;
+            }
+            before += __shfl_xor(before, 16, 64);
+            before += __shfl_xor(before, 32, 64);
+            cur += before;
+        } else {
+            tail += __shfl_xor(tail, 16, 64);
+            tail += __shfl_xor(tail, 32, 64);
+            if (g == 0) slice_count[wave][n] = head + tail;
+        }
     }
-    __syncthreads();
-    for (int w = 0; w < wave; ++w) cur += slice_count[w][n];
+    if constexpr (!kOwnPrefix) {
+        __syncthreads();
+        for (int w = 0; w < wave; ++w) cur += slice_count[w][n];
+    }
 
     const uint4* values128 = reinterpret_cast<const uint4*>(values);
     uint32_t* slot = smem + (wave * kStreamRows + n) * kSlotDwords;
@@ -156,32 +192,25 @@ __global__ __launch_bounds__(NW * 64) void linear_stream_kernel(
 #pragma unroll
     for (int i = 0; i < MT; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // Fetch everything chunk c needs; its bitmap is in ring slot `bm_slot`, which is then refilled
-    // with the bitmap of chunk c + S.
-    auto issue = [&](StreamStage<MT>& st, uint4& bm_slot, int64_t c) {
-        st.bm = bm_slot;
-        bm_slot = load_bitmap_chunk(c + S);
-        const uint32_t len = __popc(st.bm.x) + __popc(st.bm.y) + __popc(st.bm.z) + __popc(st.bm.w);
+    // A piece of up to 89 values spans at most 12 vectors (3 per lane); denser chunks need 5 per lane.
+    const bool dense_slice = __builtin_amdgcn_ballot_w64(longest > 89u) != 0;  // wave-uniform
+
+    // Fetch everything chunk c needs: NV value vectors per lane and the X operands of its 4 k-steps.
+    // Lanes whose vector lies past the piece re-read its last vector (never used); an empty piece reads
+    // the start of X instead (always mapped).  No per-lane branches: all requests go out back to back.
+    auto issue = [&](auto& st, const uint4 bm, int64_t c) {
+        constexpr int NV = sizeof(st.vq) / sizeof(uint4);
+        st.bm = bm;
+        const uint32_t len = __popc(bm.x) + __popc(bm.y) + __popc(bm.z) + __popc(bm.w);
         st.off = cur & 7u;
-        st.nv = len ? (st.off + len + 7u) >> 3 : 0u;  // nothing is fetched for an empty piece
-        const uint32_t v0 = cur >> 3;
-        cur += len;
-        // Lanes whose vector lies past the piece re-read its last vector (never used); an empty piece
-        // reads the start of X instead (always mapped).  No per-lane branches, so all requests of a
-        // stage go out back to back.
+        st.nv = len ? (st.off + len + 7u) >> 3 : 0u;
         const uint32_t last = st.nv ? st.nv - 1u : 0u;
-        const uint4* vb = st.nv ? values128 + v0 : reinterpret_cast<const uint4*>(x);
+        const uint4* vb = st.nv ? values128 + (cur >> 3) : reinterpret_cast<const uint4*>(x);
+        cur += len;
 #pragma unroll
-        for (int i = 0; i < 3; ++i) {
+        for (int i = 0; i < NV; ++i) {
             const uint32_t v = g + 4 * i;
             st.vq[i] = vb[v < last ? v : last];
-        }
-        if (__builtin_amdgcn_ballot_w64(st.nv > 12u)) {  // denser than ~70 %: rare, wave-uniform branch
-#pragma unroll
-            for (int i = 3; i < kMaxVecPerLane; ++i) {
-                const uint32_t v = g + 4 * i;
-                st.vq[i] = vb[v < last ? v : last];
-            }
         }
 #pragma unroll
         for (int s = 0; s < kChunkWords; ++s) {
@@ -196,15 +225,12 @@ __global__ __launch_bounds__(NW * 64) void linear_stream_kernel(
     };
 
     // Park the piece in LDS, expand the 4 byte masks of this lane, run the MFMAs.
-    auto consume = [&](const StreamStage<MT>& st) {
+    auto consume = [&](const auto& st) {
+        constexpr int NV = sizeof(st.vq) / sizeof(uint4);
 #pragma unroll
-        for (int i = 0; i < 3; ++i) *reinterpret_cast<uint4*>(slot + 4 * (g + 4 * i)) = st.vq[i];
-        if (__builtin_amdgcn_ballot_w64(st.nv > 12u)) {
-#pragma unroll
-            for (int i = 3; i < kMaxVecPerLane; ++i) {
-                const uint32_t v = g + 4 * i;
-                if (v < 17u) *reinterpret_cast<uint4*>(slot + 4 * v) = st.vq[i];
-            }
+        for (int i = 0; i < NV; ++i) {
+            const uint32_t v = g + 4 * i;
+            if (NV <= 4 || v < 17u) *reinterpret_cast<uint4*>(slot + 4 * v) = st.vq[i];
         }
         __builtin_amdgcn_wave_barrier();  // LDS executes a wave's accesses in order: writes above land first
         const uint32_t words[kChunkWords] = {st.bm.x, st.bm.y, st.bm.z, st.bm.w};
@@ -224,33 +250,63 @@ __global__ __launch_bounds__(NW * 64) void linear_stream_kernel(
         __builtin_amdgcn_wave_barrier();  // reads above are issued before the next chunk overwrites the slot
     };
 
-    if (c_begin < c_end) {
-        StreamStage<MT> st[S];
+    const int64_t n_chunks = c_end - c_begin;
+    if (n_chunks == S && !dense_slice) {
+        // the whole slice is in flight at once: straight-line code, each chunk waits for its own data only
+        StreamStage<MT, 3> st[S];
 #pragma unroll
-        for (int i = 0; i < S; ++i)
-            if (c_begin + i < c_end) issue(st[i], bmq[i], c_begin + i);
+        for (int i = 0; i < S; ++i) issue(st[i], bmq[i], c_begin + i);
+#pragma unroll
+        for (int i = 0; i < S; ++i) consume(st[i]);
+    } else if (n_chunks > 0 && !dense_slice) {
+        StreamStage<MT, 3> st[S];
+#pragma unroll
+        for (int i = 0; i < S; ++i) {
+            if (c_begin + i < c_end) {
+                issue(st[i], bmq[i], c_begin + i);
+                bmq[i] = load_bitmap_chunk(c_begin + i + S);
+            }
+        }
         for (int64_t c = c_begin; c < c_end; c += S) {
 #pragma unroll
             for (int i = 0; i < S; ++i) {
-                if (c + i < c_end) consume(st[i]);                       // wave-uniform conditions
-                if (c + i + S < c_end) issue(st[i], bmq[i], c + i + S);
+                if (c + i < c_end) consume(st[i]);  // wave-uniform conditions
+                if (c + i + S < c_end) {
+                    issue(st[i], bmq[i], c + i + S);
+                    bmq[i] = load_bitmap_chunk(c + i + 2 * S);
+                }
             }
         }
+    } else if (n_chunks > 0) {
+        // dense pieces (more than ~70 % nonzeros in some chunk): 5 vectors per lane, two chunks in flight
+        StreamStage<MT, kMaxVecPerLane> da, db;
+        uint4 bm_next = bmq[0];
+        auto step = [&](auto& st, int64_t c) {
+            issue(st, bm_next, c);
+            bm_next = (c + 1 - c_begin < S) ? bmq[(c + 1 - c_begin) % S] : load_bitmap_chunk(c + 1);
+        };
+        step(da, c_begin);
+        for (int64_t c = c_begin; c < c_end; c += 2) {
+            if (c + 1 < c_end) step(db, c + 1);
+            consume(da);
+            if (c + 2 < c_end) step(da, c + 2);
+            if (c + 1 < c_end) consume(db);
+        }
     }
+
+    __syncthreads();  // every wave is done with its staging slots; T in LDS is complete
 
     // ---- adapter k-step of this wave (Sec. 3.2): A operand = T rows from LDS, B operand = bq
     if (has_rank_step) {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
             const int m = 16 * mt + n;
-            uint4 aq = make_uint4(0, 0, 0, 0);
-            aq = *reinterpret_cast<const uint4*>(&t_lds[(m < M ? m : M - 1) * kMaxRankPadded + wave * 32 + 8 * g]);
+            const uint4 aq = *reinterpret_cast<const uint4*>(&t_lds[(m < M ? m : M - 1) * kMaxRankPadded + wave * 32 + 8 * g]);
             acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(aq), as_bf16x8(bq), acc[mt], 0, 0, 0);
         }
     }
 
     // ---- reduce the waves' accumulators and store
-    __syncthreads();  // every wave is done with its staging slots
     float* red = reinterpret_cast<float*>(smem);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
@@ -338,17 +394,25 @@ static void launch_stream_t(const LinearArgs& a, hipStream_t stream, const Timin
                            (int)a.M, a.K, a.a_cat, R, Rpad, kStreamTSlices, t_partial);
     // the optional events take the kernel's own begin/end timestamps (null events = plain launch)
     const unsigned grid = (unsigned)((a.N + kStreamRows - 1) / kStreamRows);
-    if ((a.K / 32) % kChunkWords == 0)  // rows of the bitmap are multiples of 16 bytes: vector loads
-        SALR_LAUNCH((linear_stream_kernel<MT, NW, S, true>), dim3(grid), dim3(NW * 64), stream, ev, a.x, (int)a.M, a.K, a.N,
-                    a.bitmap, a.values, a.row_offsets, (const float*)t_partial, a.b_cat, R, Rpad, a.y);
+    const int64_t wpr = a.K / 32;
+    if (wpr % kChunkWords != 0)  // bitmap rows are not multiples of 16 bytes: scalar bitmap loads
+        SALR_LAUNCH((linear_stream_kernel<MT, NW, S, false, false>), dim3(grid), dim3(NW * 64), stream, ev, a.x, (int)a.M, a.K,
+                    a.N, a.bitmap, a.values, a.row_offsets, (const float*)t_partial, a.b_cat, R, Rpad, a.y);
+    else if (wpr / kChunkWords <= 32)  // short rows: barrier-free start
+        SALR_LAUNCH((linear_stream_kernel<MT, NW, S, true, true>), dim3(grid), dim3(NW * 64), stream, ev, a.x, (int)a.M, a.K,
+                    a.N, a.bitmap, a.values, a.row_offsets, (const float*)t_partial, a.b_cat, R, Rpad, a.y);
     else
-        SALR_LAUNCH((linear_stream_kernel<MT, NW, S, false>), dim3(grid), dim3(NW * 64), stream, ev, a.x, (int)a.M, a.K, a.N,
-                    a.bitmap, a.values, a.row_offsets, (const float*)t_partial, a.b_cat, R, Rpad, a.y);
+        SALR_LAUNCH((linear_stream_kernel<MT, NW, S, true, false>), dim3(grid), dim3(NW * 64), stream, ev, a.x, (int)a.M, a.K,
+                    a.N, a.bitmap, a.values, a.row_offsets, (const float*)t_partial, a.b_cat, R, Rpad, a.y);
 }
 
 hipError_t launch_linear_stream(const LinearArgs& a, hipStream_t stream, const TimingEvents& ev) {
     constexpr int NW = 8;
-    if (a.M <= 16) launch_stream_t<1, NW, 4>(a, stream, ev);
+    // More row groups than two per CU: the leaner variant (2 chunks in flight, 128 registers) lets two
+    // workgroups share a CU, so one group's start-up and reduction overlap the other's stream.
+    const bool many_groups = (a.N + kStreamRows - 1) / kStreamRows >= 2 * 256;
+    if (a.M <= 16 && many_groups) launch_stream_t<1, NW, 2>(a, stream, ev);
+    else if (a.M <= 16) launch_stream_t<1, NW, 4>(a, stream, ev);
     else if (a.M <= 32) launch_stream_t<2, NW, 3>(a, stream, ev);
     else launch_stream_t<4, NW, 2>(a, stream, ev);
     return hipGetLastError();

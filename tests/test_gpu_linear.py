@@ -61,6 +61,8 @@ def test_tiny_config():
     (300, 512, 300, (16, 16)), (257, 128, 513, (7,)), (70, 384, 64, ()), (65, 1024, 1030, (40, 60)),
     # M in 17..64: the streaming path with 2 and 4 m-tiles
     (33, 640, 50, (8,)), (48, 4096, 32, (16, 16)), (64, 96, 17, ()),
+    # more than 512 row groups: the streaming variant that shares a CU between two workgroups
+    (3, 256, 8200, (8,)), (16, 1024, 8192, (16, 16)),
 ])
 def test_ragged_shapes(M, K, N, ranks):
     x, w, a_cat, b_cat = _problem(M, K, N, ranks, 31 * M + K + N, std_ab=0.05)
