@@ -9,7 +9,8 @@ All bf16 tensors are ``numpy.uint16`` arrays of raw bit patterns.  Orientation: 
 ``[N = out, K = in]`` (the transpose of the paper's ``W in R^{d_in x d_out}``), the bitmap is
 ``[N, ceil(K/32)]`` uint32 with bit t of word w = column ``32 w + t``.
 
-Pins (see tests/test_oracle_*.py): the mask against a brute-force rank count, the paper's printed
+Pins (see tests/test_oracle_*.py): the masks against a brute-force rank count (the N:M mask also against
+the row mask applied to each group), the paper's printed
 rule and Theorem 1's closed form and worked example; encode/decode against each other, the paper's
 byte-mask/LUT decoder, popcount identities and hand-worked masks; the linear against pure-Python
 loops, numpy fp64 matmul in the special cases that reduce to it, and the per-adapter sum; the SVD
@@ -50,6 +51,7 @@ def _load():
     lib.salr_oracle_words_per_row.argtypes = [_i64]
     lib.salr_oracle_mask_topk_rows.argtypes = [_u16p, _i64, _i64, _i64, _u16p]
     lib.salr_oracle_mask_threshold.argtypes = [_u16p, _i64, ctypes.c_uint16, _u16p]
+    lib.salr_oracle_mask_nm.argtypes = [_u16p, _i64, _i64, _i64, _i64, _u16p]
     lib.salr_oracle_encode.argtypes = [_u16p, _i64, _i64, _u32p, _u16p, _i64, _u32p]
     lib.salr_oracle_decode.argtypes = [_u32p, _u16p, _u32p, _i64, _i64, _u16p]
     lib.salr_oracle_decode_lut.argtypes = [_u32p, _u16p, _u32p, _i64, _i64, _u16p]
@@ -102,6 +104,18 @@ def mask_threshold(w: np.ndarray, t_mag: int) -> np.ndarray:
     rc = _load().salr_oracle_mask_threshold(_p(w, _u16p), w.size, int(t_mag), _p(out, _u16p))
     if rc:
         raise RuntimeError("mask_threshold failed")
+    return out
+
+
+def mask_nm(w: np.ndarray, n_keep: int, m_group: int) -> np.ndarray:
+    """N:M pruning (Sec. 4, the 2:4 pattern of the inference table): keep the n largest |w| of every m
+    consecutive columns, ties to the lower column."""
+    w = _c(w, np.uint16)
+    rows, cols = w.shape
+    out = np.empty_like(w)
+    rc = _load().salr_oracle_mask_nm(_p(w, _u16p), rows, cols, int(n_keep), int(m_group), _p(out, _u16p))
+    if rc:
+        raise RuntimeError(f"mask_nm failed ({rc})")
     return out
 
 

@@ -245,3 +245,27 @@ int salr_oracle_adapter_accumulate(const uint16_t* x, int64_t M, int64_t K, int6
         }
     return 0;
 }
+
+/* ------------------------------------------------------------------------------------------------
+ * N:M semi-structured pruning (the pattern the paper's inference-throughput table uses, Sec. 4: 2:4
+ * following the protocol of its baseline): in every group of m consecutive columns of a row the n
+ * entries of largest magnitude are kept, ties to the lower column, the rest become +0.0.
+ * Each group is ranked by brute force.  cols must be a multiple of m.
+ * ---------------------------------------------------------------------------------------------- */
+int salr_oracle_mask_nm(const uint16_t* w, int64_t rows, int64_t cols, int64_t n_keep, int64_t m_group,
+                        uint16_t* w_hat) {
+    if (!w || !w_hat || rows < 0 || cols < 0 || m_group <= 0 || n_keep < 0 || n_keep > m_group) return 1;
+    if (cols % m_group != 0) return 2;
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t g0 = 0; g0 < cols; g0 += m_group)
+            for (int64_t i = 0; i < m_group; ++i) {
+                const uint32_t mi = bf16_mag(w[r * cols + g0 + i]);
+                int64_t beaten_by = 0; /* entries of the group that rank before entry i */
+                for (int64_t j = 0; j < m_group; ++j) {
+                    const uint32_t mj = bf16_mag(w[r * cols + g0 + j]);
+                    if (mj > mi || (mj == mi && j < i)) ++beaten_by;
+                }
+                w_hat[r * cols + g0 + i] = (beaten_by < n_keep) ? w[r * cols + g0 + i] : (uint16_t)0;
+            }
+    return 0;
+}

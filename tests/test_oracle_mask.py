@@ -123,3 +123,26 @@ def test_mask_mse_matches_theorem1(permille):
     mse, _ = oracle.svd_residual_check(w, w_hat, 0)
     expect = oracle.pruning_mse_closed_form(permille / 1000.0, cfg.std_w)
     assert abs(mse / expect - 1.0) < 0.03, (mse, expect)
+
+
+def test_nm_mask_is_the_row_mask_applied_per_group():
+    """An N:M group is a tiny row: mask_nm(w, n, m) == mask_topk_rows on the groups laid out as rows."""
+    rng = np.random.default_rng(11)
+    vals = wl.f32_to_bf16_bits(np.array([0.5, -0.5, 0.25, 1.0, -1.0, 0.125, 0.0, -0.0], dtype=np.float32))
+    for n, m in [(2, 4), (1, 4), (4, 8), (1, 2), (4, 4), (0, 4)]:
+        w = vals[rng.integers(0, len(vals), size=(5, 8 * m))]
+        got = oracle.mask_nm(w, n, m)
+        expect = oracle.mask_topk_rows(np.ascontiguousarray(w.reshape(-1, m)), n).reshape(w.shape)
+        assert np.array_equal(got, expect), (n, m)
+    w = wl.gaussian_bf16((16, 256), 0.02, 3)
+    got = oracle.mask_nm(w, 2, 4)
+    nz = ((got & 0x7FFF) != 0).reshape(16, 64, 4)
+    assert (nz.sum(axis=2) == 2).all()          # Gaussian draws have no zeros: exactly 2 of every 4 survive
+    assert (got[(got & 0x7FFF) != 0] == w[(got & 0x7FFF) != 0]).all()
+
+
+def test_nm_mask_hand_made_group():
+    # magnitudes 1 3 3 2 -> keep both 3s ; 2 2 2 2 -> ties: the two lowest columns
+    w = wl.f32_to_bf16_bits(np.array([[1.0, -3.0, 3.0, 2.0, 2.0, -2.0, 2.0, 2.0]], dtype=np.float32))
+    got = oracle.mask_nm(w, 2, 4)
+    assert got[0].tolist() == [0, w[0, 1], w[0, 2], 0, w[0, 4], w[0, 5], 0, 0]
