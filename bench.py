@@ -12,11 +12,12 @@ Infinity Cache, so the weight stream comes from HBM, not from cache.
 Prints ONE JSON line on stdout (everything else goes to stderr):
   value     = algorithmic bytes of one call / wall-clock time per step (whole job, K steps bracketed
               by synchronize), GB/s;
-  roofline  = the fused kernel's own duration from HIP events recorded around its launch (a second
-              pass of K steps, same rotation), against the 8 TB/s HBM peak;
+  roofline  = the fused kernel's own duration from a HIP event pair attached to its launch (the
+              events take the kernel's begin and end; a second pass of K steps, same rotation),
+              against the 8 TB/s HBM peak; `traffic` = measured HBM bytes per launch;
   cpu_baseline = the CPU oracle (fp64, OpenMP) timed on this machine's host cores on the same workload.
 Extra keys report the other batch sizes, the prefill-sized gate/up layer against the bf16 MFMA peak,
-the dense bf16 GEMM (hipBLASLt via torch.matmul) under the same rotation, and encode/decode.
+the dense bf16 GEMM (hipBLASLt via torch.matmul) under the same rotation, and mask/encode/decode.
 """
 from __future__ import annotations
 
@@ -74,17 +75,6 @@ class HipEvents:
         self.pairs = []
 
 
-def magnitude_mask_rows_device(w_i16, keep):
-    """Input synthesis for the benchmark (not part of the timed path): per-row magnitude top-`keep`
-    with ties to the lower column, done with torch on the GPU."""
-    import torch
-    mag = w_i16.to(torch.int32) & 0x7FFF
-    idx = torch.sort(mag, dim=1, descending=True, stable=True).indices[:, :keep]
-    out = torch.zeros_like(w_i16)
-    out.scatter_(1, idx, w_i16.gather(1, idx))
-    return out
-
-
 class Layer:
     """Encoded weight copies + adapters of one synthetic layer on the device."""
 
@@ -96,7 +86,7 @@ class Layer:
         dev = torch.device("cuda:0")
         self.cfg, self.permille = cfg, permille
         w = torch.from_numpy(wl.dense_weight(cfg).view(np.int16)).to(dev)
-        self.w_hat = magnitude_mask_rows_device(w, cfg.keep(permille))
+        self.w_hat = salr.mask_rows(w, cfg.keep(permille))
         del w
         bitmap, values, offsets = salr.encode(self.w_hat)
         torch.cuda.synchronize()
@@ -196,8 +186,11 @@ def time_codec(layer, steps):
     bitmap, values, offsets = layer.enc[0]
     out = torch.empty((cfg.N, cfg.K), dtype=torch.int16, device=bitmap.device)
     res = {}
+    keep = cfg.keep(layer.permille)
     for name, fn in (("decode", lambda: salr.salr_decode(bitmap, values, offsets, cfg.N, cfg.K, out)),
-                     ("encode", lambda: salr.salr_encode_bitmap(layer.w_hat, bitmap, values, offsets))):
+                     ("encode", lambda: salr.salr_encode_bitmap(layer.w_hat, bitmap, values, offsets)),
+                     ("mask_rows", lambda: salr.salr_magnitude_mask_rows(layer.w_hat, keep, out)),
+                     ("mask_2of4", lambda: salr.salr_magnitude_mask_nm(layer.w_hat, 2, 4, out))):
         for _ in range(3):
             fn()
         torch.cuda.synchronize()
@@ -206,7 +199,10 @@ def time_codec(layer, steps):
             fn()
         torch.cuda.synchronize()
         ms = (time.perf_counter() - t0) * 1e3 / steps
-        nbytes = 2 * cfg.N * cfg.K + cfg.N * cfg.K // 8 + 2 * layer.nnz + 4 * (cfg.N + 1)
+        if name.startswith("mask"):
+            nbytes = 4 * cfg.N * cfg.K   # the matrix once in, once out
+        else:
+            nbytes = 2 * cfg.N * cfg.K + cfg.N * cfg.K // 8 + 2 * layer.nnz + 4 * (cfg.N + 1)
         res[name] = {"ms": round(ms, 4), "GB/s": round(nbytes / ms / 1e6, 1)}
     return res
 
@@ -237,7 +233,8 @@ def load_traffic(workload_key):
     path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     try:
         with open(path) as f:
-            return json.load(f).get(workload_key)
+            entry = json.load(f).get(workload_key)
+        return None if entry is None else entry["bytes"]
     except Exception:
         return None
 

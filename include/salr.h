@@ -58,6 +58,34 @@ const char* salr_status_string(salr_status_t status);
 int64_t salr_bitmap_words_per_row(int64_t cols);
 
 /*
+ * salr_magnitude_mask_rows -- Sec. 2, the static magnitude mask W-hat = W .* [|W| > T_p], with the
+ * threshold taken per output row so that every row keeps exactly `keep` entries (its
+ * round((1-p) * cols) largest magnitudes; among equal magnitudes the lower column wins).  Kept
+ * entries are copied bit for bit, pruned ones become +0.0.  Magnitudes compare as the 15 low bits of
+ * the bf16 pattern, so NaN/Inf rank above every finite value.
+ *
+ *   w      in   [rows, cols] bf16
+ *   keep   in   entries to keep per row, 0 <= keep <= cols
+ *   w_hat  out  [rows, cols] bf16; must not overlap w
+ *
+ * Errors: INVALID_ARG (null pointer with rows*cols > 0, negative size, keep outside [0, cols]),
+ * SHAPE (rows > 2^31 - 1 or cols > 2^31 - 32), HIP.
+ */
+salr_status_t salr_magnitude_mask_rows(const uint16_t* w, int64_t rows, int64_t cols, int64_t keep,
+                                       uint16_t* w_hat, void* stream);
+
+/*
+ * salr_magnitude_mask_nm -- the N:M pattern of the inference-throughput comparison (Sec. 4, 2:4): in
+ * every group of m_group consecutive columns of a row the n_keep largest magnitudes survive, ties to
+ * the lower column; the rest become +0.0.
+ *
+ *   w, w_hat  as above; cols % m_group == 0 (else SHAPE); 1 <= m_group <= 64 (else UNSUPPORTED);
+ *             0 <= n_keep <= m_group (else INVALID_ARG)
+ */
+salr_status_t salr_magnitude_mask_nm(const uint16_t* w, int64_t rows, int64_t cols, int64_t n_keep,
+                                     int64_t m_group, uint16_t* w_hat, void* stream);
+
+/*
  * salr_encode_bitmap -- Sec. 3.3: B[n][k] = [W-hat[n][k] != 0], v = nonzeros in row-major order.
  *
  *   w_dense          in   [rows, cols] bf16, already pruned (zeros where entries were removed)

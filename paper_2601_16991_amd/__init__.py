@@ -44,6 +44,10 @@ def lib() -> ctypes.CDLL:
         L.salr_status_string.argtypes = [ctypes.c_int]
         L.salr_bitmap_words_per_row.restype = _i64
         L.salr_bitmap_words_per_row.argtypes = [_i64]
+        L.salr_magnitude_mask_rows.restype = ctypes.c_int
+        L.salr_magnitude_mask_rows.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp]
+        L.salr_magnitude_mask_nm.restype = ctypes.c_int
+        L.salr_magnitude_mask_nm.argtypes = [_vp, _i64, _i64, _i64, _i64, _vp, _vp]
         L.salr_encode_bitmap.restype = ctypes.c_int
         L.salr_encode_bitmap.argtypes = [_vp, _i64, _i64, _vp, _vp, _i64, _vp, _vp]
         L.salr_decode.restype = ctypes.c_int
@@ -87,6 +91,26 @@ def _check(status: int, where: str) -> None:
 
 def salr_bitmap_words_per_row(cols: int) -> int:
     return int(lib().salr_bitmap_words_per_row(cols))
+
+
+def salr_magnitude_mask_rows(w: torch.Tensor, keep: int, w_hat: torch.Tensor, stream=None) -> None:
+    """Enqueue the per-row magnitude mask: w_hat = w with all but the `keep` largest |w| of each row zeroed."""
+    rows, cols = w.shape
+    if tuple(w_hat.shape) != (rows, cols):
+        raise ValueError("w_hat shape")
+    st = lib().salr_magnitude_mask_rows(_ptr(w, _BF16_TYPES, "w"), rows, cols, keep,
+                                        _ptr(w_hat, _BF16_TYPES, "w_hat"), _stream(stream))
+    _check(st, "salr_magnitude_mask_rows")
+
+
+def salr_magnitude_mask_nm(w: torch.Tensor, n_keep: int, m_group: int, w_hat: torch.Tensor, stream=None) -> None:
+    """Enqueue the N:M mask: the n_keep largest |w| of every m_group consecutive columns survive."""
+    rows, cols = w.shape
+    if tuple(w_hat.shape) != (rows, cols):
+        raise ValueError("w_hat shape")
+    st = lib().salr_magnitude_mask_nm(_ptr(w, _BF16_TYPES, "w"), rows, cols, n_keep, m_group,
+                                      _ptr(w_hat, _BF16_TYPES, "w_hat"), _stream(stream))
+    _check(st, "salr_magnitude_mask_nm")
 
 
 def salr_encode_bitmap(w_dense: torch.Tensor, bitmap: torch.Tensor, values: Optional[torch.Tensor],
@@ -174,6 +198,18 @@ def values_alloc(nnz: int, device) -> torch.Tensor:
     """A packed-values buffer of nnz elements whose storage is padded to a multiple of 16 bytes."""
     padded = (nnz + 7) // 8 * 8
     return torch.empty(max(padded, 8), dtype=torch.int16, device=device)[:nnz]
+
+
+def mask_rows(w: torch.Tensor, keep: int) -> torch.Tensor:
+    w_hat = torch.empty_like(w)
+    salr_magnitude_mask_rows(w, keep, w_hat)
+    return w_hat
+
+
+def mask_nm(w: torch.Tensor, n_keep: int, m_group: int) -> torch.Tensor:
+    w_hat = torch.empty_like(w)
+    salr_magnitude_mask_nm(w, n_keep, m_group, w_hat)
+    return w_hat
 
 
 def encode(w_dense: torch.Tensor) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:

@@ -28,6 +28,27 @@ const char* salr_status_string(salr_status_t status) {
 
 int64_t salr_bitmap_words_per_row(int64_t cols) { return cols < 0 ? -1 : (cols + 31) / 32; }
 
+salr_status_t salr_magnitude_mask_rows(const uint16_t* w, int64_t rows, int64_t cols, int64_t keep, uint16_t* w_hat,
+                                       void* stream) {
+    if (rows < 0 || cols < 0 || keep < 0 || keep > cols) return SALR_ERR_INVALID_ARG;
+    if (rows > 0 && cols > 0 && (!w || !w_hat)) return SALR_ERR_INVALID_ARG;
+    if (rows > kMaxRows || cols > kMaxCols) return SALR_ERR_SHAPE;
+    hipError_t e = salr::launch_mask_rows(w, rows, cols, keep, w_hat, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SALR_OK : SALR_ERR_HIP;
+}
+
+salr_status_t salr_magnitude_mask_nm(const uint16_t* w, int64_t rows, int64_t cols, int64_t n_keep, int64_t m_group,
+                                     uint16_t* w_hat, void* stream) {
+    if (rows < 0 || cols < 0 || m_group < 1 || n_keep < 0 || n_keep > m_group) return SALR_ERR_INVALID_ARG;
+    if (rows > 0 && cols > 0 && (!w || !w_hat)) return SALR_ERR_INVALID_ARG;
+    if (m_group > 64) return SALR_ERR_UNSUPPORTED;
+    if (rows > kMaxRows || cols > kMaxCols || cols % m_group != 0) return SALR_ERR_SHAPE;
+    if (cols > 0 && rows > (kMaxRows * 256) / (cols / m_group)) return SALR_ERR_SHAPE;  // one thread per group
+    hipError_t e = salr::launch_mask_nm(w, rows, cols, (int)n_keep, (int)m_group, w_hat,
+                                        static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SALR_OK : SALR_ERR_HIP;
+}
+
 salr_status_t salr_encode_bitmap(const uint16_t* w_dense, int64_t rows, int64_t cols, uint32_t* bitmap,
                                  uint16_t* values, int64_t values_capacity, uint32_t* row_offsets, void* stream) {
     if (rows < 0 || cols < 0) return SALR_ERR_INVALID_ARG;

@@ -12,33 +12,7 @@
 namespace salr {
 
 constexpr int kCodecThreads = 256;             // 4 waves
-constexpr int kUnit = 8;                       // columns per thread per step = one byte of bitmap
 constexpr int kChunkValuesMax = kCodecThreads * kUnit;  // packed values one step can own
-
-// Eight consecutive bf16 of a row starting at column 8u, zero-filled past the row end.
-template <bool kVec>
-__device__ __forceinline__ uint4 load_unit(const uint16_t* row, int64_t cols, int64_t u) {
-    uint4 q = make_uint4(0, 0, 0, 0);
-    const int64_t k0 = u * kUnit;
-    if (k0 >= cols) return q;
-    if constexpr (kVec) {
-        q = *reinterpret_cast<const uint4*>(row + k0);
-    } else {
-        uint32_t e[kUnit];
-#pragma unroll
-        for (int j = 0; j < kUnit; ++j) e[j] = (k0 + j < cols) ? row[k0 + j] : 0u;
-        q.x = e[0] | (e[1] << 16);
-        q.y = e[2] | (e[3] << 16);
-        q.z = e[4] | (e[5] << 16);
-        q.w = e[6] | (e[7] << 16);
-    }
-    return q;
-}
-
-__device__ __forceinline__ uint32_t unit_elem(const uint4& q, int j) {
-    const uint32_t d = (j < 2) ? q.x : (j < 4) ? q.y : (j < 6) ? q.z : q.w;
-    return (j & 1) ? (d >> 16) : (d & 0xFFFFu);
-}
 
 template <bool kVec>
 __global__ __launch_bounds__(kCodecThreads) void encode_count_kernel(const uint16_t* __restrict__ w,

@@ -14,6 +14,12 @@ hipError_t launch_encode(const uint16_t* w, int64_t rows, int64_t cols, uint32_t
 hipError_t launch_decode(const uint32_t* bitmap, const uint16_t* values, const uint32_t* row_offsets, int64_t rows,
                          int64_t cols, uint16_t* out, hipStream_t stream);
 
+hipError_t launch_mask_rows(const uint16_t* w, int64_t rows, int64_t cols, int64_t keep, uint16_t* out,
+                            hipStream_t stream);
+
+hipError_t launch_mask_nm(const uint16_t* w, int64_t rows, int64_t cols, int n_keep, int m_group, uint16_t* out,
+                          hipStream_t stream);
+
 // Columns of the bf16 workspace matrix T = X * A_cat: R rounded up to the MFMA k-step.
 inline int64_t adapter_rank_padded(int64_t R) { return (R + 31) / 32 * 32; }
 

@@ -56,9 +56,12 @@ def test_words_per_row(lib):
 def test_workspace_bytes(lib):
     assert lib.salr_linear_workspace_bytes(16, 4096, 4096, 0) == 0
     assert lib.salr_linear_workspace_bytes(0, 4096, 4096, 32) == 0
-    assert lib.salr_linear_workspace_bytes(16, 4096, 4096, 32) == 16 * 32 * 2
-    assert lib.salr_linear_workspace_bytes(16, 4096, 4096, 16) == 16 * 32 * 2   # rank padded to 32
-    assert lib.salr_linear_workspace_bytes(1, 4096, 4096, 64) == 256            # rounded to 256 B
+    # M <= 64: sixteen split-K partials of T in fp32; larger M: T in bf16.  Rank padded to 32.
+    assert lib.salr_linear_workspace_bytes(16, 4096, 4096, 32) == 16 * 16 * 32 * 4
+    assert lib.salr_linear_workspace_bytes(16, 4096, 4096, 16) == 16 * 16 * 32 * 4
+    assert lib.salr_linear_workspace_bytes(1, 4096, 4096, 64) == 16 * 64 * 4
+    assert lib.salr_linear_workspace_bytes(128, 4096, 4096, 32) == 128 * 32 * 2
+    assert lib.salr_linear_workspace_bytes(65, 4096, 4096, 1) == 4352  # 65*32*2 = 4160 rounded up to 256 B
     assert lib.salr_linear_workspace_bytes(16, 4096, 4096, 1000) == 0
 
 
@@ -91,3 +94,14 @@ def test_host_validation_rejects_before_launch(lib):
     # empty problems are no-ops
     assert lin(M=0) == salr.SALR_OK
     assert lin(N=0) == salr.SALR_OK
+    # masks: keep outside [0, cols], group sizes, null pointers, empty inputs
+    assert lib.salr_magnitude_mask_rows(fake, 4, 8, 9, fake, None) == salr.SALR_ERR_INVALID_ARG
+    assert lib.salr_magnitude_mask_rows(fake, 4, 8, -1, fake, None) == salr.SALR_ERR_INVALID_ARG
+    assert lib.salr_magnitude_mask_rows(None, 4, 8, 4, fake, None) == salr.SALR_ERR_INVALID_ARG
+    assert lib.salr_magnitude_mask_rows(fake, 0, 8, 4, fake, None) == salr.SALR_OK
+    assert lib.salr_magnitude_mask_nm(fake, 4, 8, 3, 2, fake, None) == salr.SALR_ERR_INVALID_ARG
+    assert lib.salr_magnitude_mask_nm(fake, 4, 8, 1, 0, fake, None) == salr.SALR_ERR_INVALID_ARG
+    assert lib.salr_magnitude_mask_nm(fake, 4, 10, 2, 4, fake, None) == salr.SALR_ERR_SHAPE
+    assert lib.salr_magnitude_mask_nm(fake, 4, 128, 2, 128, fake, None) == salr.SALR_ERR_UNSUPPORTED
+    assert lib.salr_magnitude_mask_nm(fake, 4, 8, 2, 4, None, None) == salr.SALR_ERR_INVALID_ARG
+    assert lib.salr_magnitude_mask_nm(fake, 0, 8, 2, 4, fake, None) == salr.SALR_OK
