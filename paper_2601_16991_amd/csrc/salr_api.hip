@@ -73,8 +73,8 @@ salr_status_t salr_decode(const uint32_t* bitmap, const uint16_t* values, const 
 }
 
 size_t salr_linear_workspace_bytes(int64_t M, int64_t K, int64_t N, int64_t R) {
-    if (M <= 0 || K < 0 || N <= 0 || R <= 0 || R > kMaxRank) return 0;
-    return salr::linear_workspace_bytes(M, R);
+    if (M <= 0 || K < 0 || N <= 0 || R < 0 || R > kMaxRank || K % 32 != 0) return 0;
+    return salr::linear_workspace_bytes(M, K, N, R);
 }
 
 salr_status_t salr_sparse_lowrank_linear(const uint16_t* x, int64_t M, int64_t K, int64_t N, const uint32_t* bitmap,

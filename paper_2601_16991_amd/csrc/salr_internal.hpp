@@ -57,17 +57,34 @@ constexpr int64_t kStreamMaxM = 64;
 constexpr int kStreamTSlices = 16;
 constexpr int kMaxRankPadded = 256;  // R <= 256: pitch of the T tile the streaming kernels keep in LDS
 
-// Workspace the linear needs: the small-batch path keeps fp32 split-K partials of T, the tiled path T in bf16.
-inline size_t linear_workspace_bytes(int64_t M, int64_t R) {
-    if (M <= 0 || R <= 0) return 0;
+// Largest-batch path: M >= kTwoStageMinM decodes the weight once into a dense scratch matrix, then runs a
+// dense MFMA GEMM on it.
+constexpr int64_t kTwoStageMinM = 1024;
+inline bool uses_twostage(int64_t M, int64_t K) { return M >= kTwoStageMinM && K >= 64 && K % 64 == 0; }
+
+inline size_t round_up_256(size_t b) { return (b + 255) / 256 * 256; }
+
+// Byte offset of the dense weight scratch inside the workspace of the two-stage path (T comes first).
+inline size_t twostage_dense_offset(int64_t M, int64_t R) {
+    return R > 0 ? round_up_256((size_t)M * (size_t)adapter_rank_padded(R) * sizeof(uint16_t)) : 0;
+}
+
+// Workspace the linear needs: the small-batch path keeps fp32 split-K partials of T, the tiled path T in bf16,
+// the two-stage path T in bf16 followed by the decoded weight [N, K] in bf16.
+inline size_t linear_workspace_bytes(int64_t M, int64_t K, int64_t N, int64_t R) {
+    if (M <= 0 || N <= 0) return 0;
     const size_t rp = (size_t)adapter_rank_padded(R);
-    const size_t b = (M <= kStreamMaxM) ? (size_t)kStreamTSlices * (size_t)M * rp * sizeof(float)
-                                        : (size_t)M * rp * sizeof(uint16_t);
-    return (b + 255) / 256 * 256;
+    if (M <= kStreamMaxM) return R > 0 ? round_up_256((size_t)kStreamTSlices * (size_t)M * rp * sizeof(float)) : 0;
+    if (uses_twostage(M, K))
+        return twostage_dense_offset(M, R) + round_up_256((size_t)N * (size_t)K * sizeof(uint16_t));
+    return R > 0 ? round_up_256((size_t)M * rp * sizeof(uint16_t)) : 0;
 }
 
 hipError_t launch_linear(const LinearArgs& args, hipStream_t stream);
 hipError_t launch_linear_stream(const LinearArgs& args, hipStream_t stream, const TimingEvents& ev);
 hipError_t launch_linear_tiled(const LinearArgs& args, hipStream_t stream, const TimingEvents& ev);
+hipError_t launch_linear_twostage(const LinearArgs& args, hipStream_t stream, const TimingEvents& ev);
+// T = X * A_cat in bf16 [M, Rpad] at the start of the workspace (tiled and two-stage paths)
+void launch_adapter_t(const LinearArgs& args, hipStream_t stream);
 
 }  // namespace salr

@@ -22,30 +22,34 @@
 
 namespace salr {
 
-constexpr int kTM = 256, kTN = 256, kTK = 32;
+constexpr int kTM = 256, kTN = 128, kTK = 32;
 constexpr int kTiledThreads = 512;
-constexpr int kPitch = kTK + 8;          // bf16 elements per LDS tile row (80 bytes)
+constexpr int kPitch = kTK;              // bf16 elements per LDS tile row: 64 bytes = four 16-byte segments, no padding
 constexpr int kSlotDw = 36;              // 9 vectors of 16 B: 64 values + misalignment
 constexpr int kXcds = 8;
 
-struct XPair {
-    uint4 a, b;      // 16 bf16 of one X row
-};
+// LDS tiles are swizzled instead of padded: segment s of row r sits at segment s ^ ((r >> 2) & 3).  Sixteen
+// consecutive lanes then cover all sixteen 16-byte bank groups of a 256-byte LDS line both when an MFMA
+// operand is read (16 rows, one segment) and when the tiles are written (8 rows x 2 or 4 rows x 4 segments).
+__device__ __forceinline__ int swz(int row, int seg) { return (seg ^ ((row >> 2) & 3)) * 8; }
 
-// One staged value chunk of a row lives in plain registers (named per ring slot): the thread's share of
-// the piece (every second 16-byte vector), the piece's first vector, the index of its last vector, the
-// element offset of the piece inside its first vector and its vector count.
-#define SALR_VC_DECL(n) uint4 n##_q0, n##_q1, n##_q2; const uint4* n##_vb; uint32_t n##_last, n##_off, n##_nv
-#define SALR_VC_ARGS(n) n##_q0, n##_q1, n##_q2, n##_vb, n##_last, n##_off, n##_nv
 
-__global__ __launch_bounds__(kTiledThreads) void linear_tiled_kernel(
+__global__ __launch_bounds__(kTiledThreads, 4) void linear_tiled_kernel(
     const uint16_t* __restrict__ x, int64_t M, int64_t K, int64_t N, const uint32_t* __restrict__ bitmap,
     const uint16_t* __restrict__ values, const uint32_t* __restrict__ row_offsets, const uint16_t* __restrict__ t,
     const uint16_t* __restrict__ b_cat, int R, int Rpad, uint16_t* __restrict__ y, int m_tiles, int n_tiles) {
-    __shared__ __attribute__((aligned(16))) uint16_t Xs[2][kTM * kPitch];
+    // two separate arrays, not one [2][...]: the compiler orders LDS reads against the asynchronous loads
+    // into LDS per variable, and reads of one buffer must not wait for loads into the other
+    __shared__ __attribute__((aligned(16))) uint16_t Xs0[kTM * kPitch];
+    __shared__ __attribute__((aligned(16))) uint16_t Xs1[kTM * kPitch];
     __shared__ __attribute__((aligned(16))) uint16_t Ws[2][kTN * kPitch];
     __shared__ __attribute__((aligned(16))) uint32_t stage[kTN * kSlotDw + 8];
     __shared__ uint32_t lut[kNibbleLutWords];
+#if defined(SALR_KO) && (SALR_KO & 32)
+    __shared__ uint32_t lds_pad[10000];   // 40 KB more: only one workgroup fits a CU
+    if (m_tiles < 0) lds_pad[blockIdx.x % 10000] = 1;
+    if (n_tiles < 0) y[0] = (uint16_t)lds_pad[threadIdx.x];
+#endif
 
     // ---- tile of this workgroup
     const int bid = blockIdx.x;
@@ -58,190 +62,169 @@ __global__ __launch_bounds__(kTiledThreads) void linear_tiled_kernel(
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave >> 2, wn = wave & 3;
+    const int wm = wave >> 1, wn = wave & 1;
 
     nibble_lut_init(lut);
 
-    // ---- loader / decoder role: row r of the tile, half h
-    const int r = tid >> 1, h = tid & 1;
-    const int64_t xrow = (m0 + r < M) ? m0 + r : M - 1;   // rows past the edge recompute the last row; never stored
-    const int64_t wrow = (n0 + r < N) ? n0 + r : N - 1;
-    const uint16_t* xptr = x + xrow * K + 16 * h;
+    // ---- both roles use the same split: four threads per tile row, thread q owns 8 of the row's 32 columns.
+    // Loader: segment q of X rows wr and wr + 128 (the four lanes of a row fetch 64 contiguous bytes).
+    // Decoder: byte q of the bitmap word of weight row wr.
+    const int wr = tid >> 2, q = tid & 3;
+    const int64_t xrow0 = (m0 + wr < M) ? m0 + wr : M - 1;   // rows past the edge recompute the last row; never stored
+    const int64_t xrow1 = (m0 + wr + 128 < M) ? m0 + wr + 128 : M - 1;
+    // X tiles go from memory straight into LDS (no registers): a wave's load instruction fills 1 KB = its 16
+    // rows of 64 bytes, lane l landing on 16-byte slot l.  Slot (row, p) holds logical segment p ^ swizzle(row),
+    // so that is the segment the lane fetches.
+    const int xseg = q ^ ((wr >> 2) & 3);
+    const uint16_t* xptr0 = x + xrow0 * K + 8 * xseg;
+    const uint16_t* xptr1 = x + xrow1 * K + 8 * xseg;
+    const int64_t wrow = (n0 + wr < N) ? n0 + wr : N - 1;
     const int64_t wpr = K >> 5;
     const uint32_t* brow = bitmap + wrow * wpr;
     const uint4* values128 = reinterpret_cast<const uint4*>(values);
-    uint32_t* slot = stage + r * kSlotDw;
+    uint32_t* slot = stage + wr * kSlotDw;
     uint32_t cur = row_offsets[wrow];  // element index in `values` of the row's next unfetched value
     const int64_t steps = K / kTK;
-    const int64_t supers = steps / 4;   // K % 128 == 0 on this path
+    const int64_t chunks = steps / 2;   // K % 64 == 0 on this path
 
-    auto load_bitmap = [&](int64_t q) -> uint4 {
-        return (q < supers) ? *reinterpret_cast<const uint4*>(brow + 4 * q) : make_uint4(0, 0, 0, 0);
+    auto load_bitmap = [&](int64_t c) -> uint2 {
+        return (c < chunks) ? *reinterpret_cast<const uint2*>(brow + 2 * c) : make_uint2(0, 0);
     };
-    auto load_x = [&](int64_t s) -> XPair {
+    typedef const __attribute__((address_space(1))) void* gptr_t;
+    typedef __attribute__((address_space(3))) void* lptr_t;
+    // request X tile of k-step s into buffer `buf`; completion is awaited (vmcnt) before the barrier that
+    // publishes the buffer
+    auto fetch_x = [&](int buf, int64_t s) {
         const int64_t sc = s < steps ? s : steps - 1;  // past the end: reload the last step (unused)
-        const uint4* p = reinterpret_cast<const uint4*>(xptr + sc * kTK);
-        XPair v;
-        v.a = p[0];
-        v.b = p[1];
-        return v;
+        uint16_t* dst = (buf ? Xs1 : Xs0) + (wave * 16) * kPitch;
+        __builtin_amdgcn_global_load_lds((gptr_t)(xptr0 + sc * kTK), (lptr_t)dst, 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((gptr_t)(xptr1 + sc * kTK), (lptr_t)(dst + 128 * kPitch), 16, 0, 0);
     };
-    auto store_x = [&](int buf, const XPair src) {
-        uint4* p = reinterpret_cast<uint4*>(&Xs[buf][r * kPitch + 16 * h]);
-        p[0] = src.a;
-        p[1] = src.b;
-    };
-    // request the packed values of the next chunk of this row (bitmap words w0, w1)
-    auto v_issue = [&](uint4& q0, uint4& q1, uint4& q2, const uint4*& vb, uint32_t& last, uint32_t& off, uint32_t& nv,
-                       uint32_t w0, uint32_t w1) {
-        const uint32_t len = __popc(w0) + __popc(w1);
-        off = cur & 7u;
-        nv = len ? (off + len + 7u) >> 3 : 0u;
-        vb = nv ? values128 + (cur >> 3) : reinterpret_cast<const uint4*>(x);
-        last = nv ? nv - 1u : 0u;
+    auto x_landed = [&]() { __builtin_amdgcn_s_waitcnt(0x0F70); };  // vmcnt(0)
+    // One staged value chunk (the packed values of 64 columns of the row, contiguous in `values`) lives in
+    // plain registers: this thread's two 16-byte vectors of the piece, the piece's first vector, the index
+    // of its last vector, the element offset of the piece inside its first vector and its vector count.
+    uint4 vq0, vq1;
+    const uint4* vb;
+    uint32_t v_last, v_off, v_nv;
+    auto v_issue = [&](uint2 w) {
+        const uint32_t len = __popc(w.x) + __popc(w.y);
+        v_off = cur & 7u;
+        v_nv = len ? (v_off + len + 7u) >> 3 : 0u;
+        vb = v_nv ? values128 + (cur >> 3) : reinterpret_cast<const uint4*>(x);
+        v_last = v_nv ? v_nv - 1u : 0u;
         cur += len;
-        // clamped, not predicated: the three requests go out back to back.  Vectors 6..8 exist only in
-        // pieces denser than ~70 %; v_store fetches them on the spot.
-        q0 = vb[h < last ? h : last];
-        q1 = vb[h + 2 < last ? h + 2 : last];
-        q2 = vb[h + 4 < last ? h + 4 : last];
+        // clamped, not predicated: both requests go out back to back.  A ninth vector exists only in
+        // pieces denser than ~90 %; v_store fetches it on the spot.
+        vq0 = vb[(uint32_t)q < v_last ? (uint32_t)q : v_last];
+        vq1 = vb[(uint32_t)q + 4u < v_last ? (uint32_t)q + 4u : v_last];
     };
     uint32_t c_local = 0;  // cursor inside the slot
-    // park the chunk in the row's LDS slot (only the row's own two threads ever touch the slot)
-    auto v_store = [&](const uint4& q0, const uint4& q1, const uint4& q2, const uint4* vb, uint32_t last, uint32_t off,
-                       uint32_t nv) {
+    // park the chunk in the row's LDS slot (only the row's own four threads, lanes of one wave, touch it)
+    auto v_store = [&]() {
         uint4* sv = reinterpret_cast<uint4*>(slot);
-        sv[h] = q0;
-        sv[h + 2] = q1;
-        sv[h + 4] = q2;
-        if (__builtin_amdgcn_ballot_w64(nv > 6u)) {  // rare, wave-uniform
-            sv[h + 6] = vb[h + 6 < last ? h + 6 : last];
-            if (h == 0) sv[8] = vb[8u < last ? 8u : last];  // the slot holds 9 vectors
+        sv[q] = vq0;
+        sv[q + 4] = vq1;
+        if (__builtin_amdgcn_ballot_w64(v_nv > 8u)) {  // rare, wave-uniform
+            if (q == 0) sv[8] = vb[8u < v_last ? 8u : v_last];
         }
         __builtin_amdgcn_wave_barrier();
-        c_local = off;  // the slot's cursor restarts at the piece's offset
+        c_local = v_off;  // the slot's cursor restarts at the piece's offset
     };
-    // expand this thread's two byte masks of `word` into Ws[buf]
+    // expand this thread's byte mask of `word` into Ws[buf]
     auto decode = [&](int buf, uint32_t word) {
-        const uint32_t half = (word >> (16 * h)) & 0xFFFFu;
-        const uint32_t cb = c_local + (h ? __popc(word & 0xFFFFu) : 0u);
-        const uint32_t ma = half & 0xFFu, mb = half >> 8;
-        const uint4 qa = expand_byte(slot, lut, cb, ma);
-        const uint4 qb = expand_byte(slot, lut, cb + __popc(ma), mb);
+#if defined(SALR_KO) && (SALR_KO & 2)
+        *reinterpret_cast<uint4*>(&Ws[buf][wr * kPitch + swz(wr, q)]) = make_uint4(word, word, word, word);
+        return;
+#endif
+        const uint32_t cb = c_local + __popc(word & ((1u << (8 * q)) - 1u));
+        const uint4 qa = expand_byte(slot, lut, cb, (word >> (8 * q)) & 0xFFu);
         c_local += __popc(word);
-        uint4* p = reinterpret_cast<uint4*>(&Ws[buf][r * kPitch + 16 * h]);
-        p[0] = qa;
-        p[1] = qb;
+        *reinterpret_cast<uint4*>(&Ws[buf][wr * kPitch + swz(wr, q)]) = qa;
     };
 
-    f32x16 acc00 = {0}, acc01 = {0}, acc10 = {0}, acc11 = {0}, acc20 = {0}, acc21 = {0}, acc30 = {0}, acc31 = {0};
+    f32x16 acc00 = {0}, acc01 = {0}, acc10 = {0}, acc11 = {0};
 
-    const int frag_row = lane & 31, frag_k = 8 * (lane >> 5);
+    // operand lane: row lane%32 of a 32-row block, k-group lane/32 (+2 for the second half of the k-step);
+    // rows 32 or 64 further down share the swizzle term
+    const int frag_row = lane & 31;
+    const int frag_k0 = swz(frag_row, lane >> 5), frag_k1 = swz(frag_row, (lane >> 5) + 2);
     auto mfma_step = [&](int buf) {
-        const uint16_t* xa = &Xs[buf][(wm * 128 + frag_row) * kPitch + frag_k];
-        const uint16_t* wb = &Ws[buf][(wn * 64 + frag_row) * kPitch + frag_k];
+        const uint16_t* xa = (buf ? Xs1 : Xs0) + (wm * 64 + frag_row) * kPitch;
+        const uint16_t* wb = &Ws[buf][(wn * 64 + frag_row) * kPitch];
         auto frag = [](const uint16_t* p) { return *reinterpret_cast<const bf16x8*>(p); };
-        // all twelve 16-byte fragment reads of the step are in flight before the first MFMA issues
-        const bf16x8 a00 = frag(xa), a10 = frag(xa + 32 * kPitch), a20 = frag(xa + 64 * kPitch), a30 = frag(xa + 96 * kPitch);
-        const bf16x8 b00 = frag(wb), b10 = frag(wb + 32 * kPitch);
-        const bf16x8 a01 = frag(xa + 16), a11 = frag(xa + 32 * kPitch + 16), a21 = frag(xa + 64 * kPitch + 16),
-                     a31 = frag(xa + 96 * kPitch + 16);
-        const bf16x8 b01 = frag(wb + 16), b11 = frag(wb + 32 * kPitch + 16);
+        const bf16x8 a00 = frag(xa + frag_k0), a10 = frag(xa + 32 * kPitch + frag_k0);
+        const bf16x8 b00 = frag(wb + frag_k0), b10 = frag(wb + 32 * kPitch + frag_k0);
+        const bf16x8 a01 = frag(xa + frag_k1), a11 = frag(xa + 32 * kPitch + frag_k1);
+        const bf16x8 b01 = frag(wb + frag_k1), b11 = frag(wb + 32 * kPitch + frag_k1);
+#if defined(SALR_KO) && (SALR_KO & 1)
+        asm volatile("" ::"v"(a00), "v"(a10), "v"(b00), "v"(b10), "v"(a01), "v"(a11), "v"(b01), "v"(b11));
+        return;
+#endif
         acc00 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a00, b00, acc00, 0, 0, 0);
         acc01 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a00, b10, acc01, 0, 0, 0);
         acc10 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a10, b00, acc10, 0, 0, 0);
         acc11 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a10, b10, acc11, 0, 0, 0);
-        acc20 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a20, b00, acc20, 0, 0, 0);
-        acc21 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a20, b10, acc21, 0, 0, 0);
-        acc30 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a30, b00, acc30, 0, 0, 0);
-        acc31 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a30, b10, acc31, 0, 0, 0);
         acc00 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a01, b01, acc00, 0, 0, 0);
         acc01 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a01, b11, acc01, 0, 0, 0);
         acc10 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a11, b01, acc10, 0, 0, 0);
         acc11 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a11, b11, acc11, 0, 0, 0);
-        acc20 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a21, b01, acc20, 0, 0, 0);
-        acc21 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a21, b11, acc21, 0, 0, 0);
-        acc30 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a31, b01, acc30, 0, 0, 0);
-        acc31 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a31, b11, acc31, 0, 0, 0);
     };
 
-    // ---- prologue: bitmap of 3 super-steps, values of chunks 0 and 1, X of steps 0..2, tile 0 decoded
-    uint4 bm0 = load_bitmap(0), bm1 = load_bitmap(1), bm2 = load_bitmap(2);
-    XPair xr0 = load_x(0), xr1;
-    SALR_VC_DECL(vc0);
-    SALR_VC_DECL(vc1);
-    v_issue(SALR_VC_ARGS(vc0), bm0.x, bm0.y);
-    v_issue(SALR_VC_ARGS(vc1), bm0.z, bm0.w);
+    // ---- prologue: bitmap of chunks 0..2, values of chunk 0 parked and of chunk 1 requested, tile 0 in buffer 0
+    uint2 bm0 = load_bitmap(0), bm1 = load_bitmap(1), bm2 = load_bitmap(2);
+    fetch_x(0, 0);
+    v_issue(bm0);
     __syncthreads();  // lut
-    store_x(0, xr0);
-    xr1 = load_x(1);
-    xr0 = load_x(2);
-    v_store(SALR_VC_ARGS(vc0));
+    v_store();
     decode(0, bm0.x);
-    v_issue(SALR_VC_ARGS(vc0), bm1.x, bm1.y);  // chunk 2
+    v_issue(bm1);
+    x_landed();
     __syncthreads();
 
-    // ---- main loop: one super-step (4 k-steps, 2 value chunks, one bitmap vector) per iteration.
-    // Within a k-step the MFMAs read buffer s%2 while the loaders fill buffer (s+1)%2, so the two halves
-    // may run in either order: waves 0-3 fill first, waves 4-7 multiply first.  Waves w and w+4 share a
-    // SIMD, so on every SIMD one wave's decode overlaps the other wave's MFMAs.
-    const bool fill_first = wave < 4;
-    for (int64_t q = 0; q < supers; ++q) {
-        const int64_t s0 = 4 * q;
-        // step s0 (tile in buffer 0): decode tile s0+1 from chunk 2q, word 1
+    // ---- main loop: one value chunk (2 k-steps, one bitmap pair) per iteration.  Within a k-step the MFMAs
+    // read buffer s%2 while the loaders fill buffer (s+1)%2, so the two halves may run in either order: even
+    // waves fill first, odd waves multiply first.  Two workgroups share a CU (4 waves per SIMD), so decode
+    // and LDS latency of some waves overlaps the MFMAs of the others.
+    const bool fill_first = (wave & 1) == 0;
+    for (int64_t c = 0; c < chunks; ++c) {
+        const int64_t s0 = 2 * c;
+        // step s0 (tile in buffer 0): decode tile s0+1 from the parked chunk, word 1
+        fetch_x(1, s0 + 1);
         if (!fill_first) mfma_step(0);
-        store_x(1, xr1);
-        xr1 = load_x(s0 + 3);
         decode(1, bm0.y);
         if (fill_first) mfma_step(0);
+        x_landed();
         __syncthreads();
-        // step s0+1 (buffer 1): chunk 2q+1 becomes current; decode tile s0+2, word 2; request chunk 2q+3
+        // step s0+1 (buffer 1): chunk c+1 becomes current; decode tile s0+2 (its word 0); request chunk c+2
+        fetch_x(0, s0 + 2);
         if (!fill_first) mfma_step(1);
-        store_x(0, xr0);
-        xr0 = load_x(s0 + 4);
-        v_store(SALR_VC_ARGS(vc1));
-        decode(0, bm0.z);
-        v_issue(SALR_VC_ARGS(vc1), bm1.z, bm1.w);
-        if (fill_first) mfma_step(1);
-        __syncthreads();
-        // step s0+2 (buffer 0): decode tile s0+3, word 3
-        if (!fill_first) mfma_step(0);
-        store_x(1, xr1);
-        xr1 = load_x(s0 + 5);
-        decode(1, bm0.w);
-        if (fill_first) mfma_step(0);
-        __syncthreads();
-        // step s0+3 (buffer 1): chunk 2q+2 becomes current; decode tile s0+4 (word 0 of the next super-step);
-        // request chunk 2q+4; rotate the bitmap ring
-        if (!fill_first) mfma_step(1);
-        store_x(0, xr0);
-        xr0 = load_x(s0 + 6);
-        v_store(SALR_VC_ARGS(vc0));
+        v_store();
         decode(0, bm1.x);
-        v_issue(SALR_VC_ARGS(vc0), bm2.x, bm2.y);
+        v_issue(bm2);
         bm0 = bm1;
         bm1 = bm2;
-        bm2 = load_bitmap(q + 3);
+        bm2 = load_bitmap(c + 3);
         if (fill_first) mfma_step(1);
+        x_landed();
         __syncthreads();
     }
 
     // ---- adapter k-steps (Sec. 3.2): Xs := T[m, r0 .. r0+31], Ws := B_cat[r0 .. r0+31, n]
     if (R > 0) {
-        const int64_t bn = (n0 + (tid & 255) < N) ? n0 + (tid & 255) : N - 1;
-        const int rr2 = tid >> 8;
+        const int64_t bn = (n0 + (tid & 127) < N) ? n0 + (tid & 127) : N - 1;
+        const int rr4 = tid >> 7;                  // rank row 4 i + rr4 of the k-step: segment i / 2 of tile row tid % 128
+        const int bf = ((tid & 127) >> 2) & 3;     // that row's swizzle term
         for (int r0 = 0; r0 < Rpad; r0 += kTK) {
-            const uint4* tp = reinterpret_cast<const uint4*>(t + xrow * Rpad + r0 + 16 * h);
-            XPair tq;
-            tq.a = tp[0];
-            tq.b = tp[1];
-            store_x(0, tq);
+            uint16_t* xs = &Xs0[wr * kPitch + swz(wr, q)];   // row wr + 128 has the same swizzle term
+            *reinterpret_cast<uint4*>(xs) = *reinterpret_cast<const uint4*>(t + xrow0 * Rpad + r0 + 8 * q);
+            *reinterpret_cast<uint4*>(xs + 128 * kPitch) = *reinterpret_cast<const uint4*>(t + xrow1 * Rpad + r0 + 8 * q);
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int rr = 2 * i + rr2;
+            for (int i = 0; i < 8; ++i) {
+                const int rr = 4 * i + rr4;
                 const int rg = r0 + rr;
                 const uint16_t v = b_cat[(int64_t)(rg < R ? rg : R - 1) * N + bn];
-                Ws[0][(tid & 255) * kPitch + rr] = rg < R ? v : (uint16_t)0;
+                Ws[0][(tid & 127) * kPitch + (((i >> 1) ^ bf) << 3) + 4 * (i & 1) + rr4] = rg < R ? v : (uint16_t)0;
             }
             __syncthreads();
             mfma_step(0);
@@ -254,7 +237,7 @@ __global__ __launch_bounds__(kTiledThreads) void linear_tiled_kernel(
         const int64_t n = n0 + wn * 64 + 32 * j + (lane & 31);
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-            const int64_t m = m0 + wm * 128 + 32 * i + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+            const int64_t m = m0 + wm * 64 + 32 * i + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
             if (m < M && n < N) y[m * N + n] = f32_to_bf16_rne(a[e]);
         }
     };
@@ -262,10 +245,6 @@ __global__ __launch_bounds__(kTiledThreads) void linear_tiled_kernel(
     store_tile(acc01, 0, 1);
     store_tile(acc10, 1, 0);
     store_tile(acc11, 1, 1);
-    store_tile(acc20, 2, 0);
-    store_tile(acc21, 2, 1);
-    store_tile(acc30, 3, 0);
-    store_tile(acc31, 3, 1);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -319,11 +298,15 @@ __global__ __launch_bounds__(kTmWaves * 64) void adapter_t_mfma_kernel(const uin
     }
 }
 
+void launch_adapter_t(const LinearArgs& a, hipStream_t stream) {
+    const int R = (int)a.R, Rpad = (int)adapter_rank_padded(a.R);
+    hipLaunchKernelGGL(adapter_t_mfma_kernel, dim3((unsigned)((a.M + 63) / 64), Rpad / 16), dim3(kTmWaves * 64), 0, stream,
+                       a.x, a.M, a.K, a.a_cat, R, Rpad, a.t);
+}
+
 hipError_t launch_linear_tiled(const LinearArgs& a, hipStream_t stream, const TimingEvents& ev) {
     const int R = (int)a.R, Rpad = (int)adapter_rank_padded(a.R);
-    if (R > 0)
-        hipLaunchKernelGGL(adapter_t_mfma_kernel, dim3((unsigned)((a.M + 63) / 64), Rpad / 16), dim3(kTmWaves * 64), 0, stream,
-                           a.x, a.M, a.K, a.a_cat, R, Rpad, a.t);
+    if (R > 0) launch_adapter_t(a, stream);
     const int m_tiles = (int)((a.M + kTM - 1) / kTM);
     const int n_tiles = (int)((a.N + kTN - 1) / kTN);
     const int n_groups = (n_tiles + kXcds - 1) / kXcds;

@@ -1,0 +1,199 @@
+// Largest-batch path of the SALR linear: the two stages of Sec. 3.3 ("Pipeline Design") as two kernels.
+//
+//   stage 1  bitmap decode of the whole weight into a dense bf16 scratch matrix (decode_kernel of the codec,
+//            once per call: the fused kernels repeat the decode for every 256-row block of X, which at
+//            M >= 1024 costs more than one round trip of the dense matrix through memory);
+//   stage 2  dense_gemm_kernel: Y = X * Wd^T (+ T * B_cat, Sec. 3.2) on the matrix cores.
+//
+// dense_gemm_kernel: output tile 256 (m) x 64 kWN (n), 4 kWN waves, wave (wm, wn) owns 64 x 64 = 2 x 2 tiles of
+// v_mfma_f32_32x32x16_bf16.  A k-step is 64 wide so that every row of a tile is one whole 128-byte line: at 64
+// bytes per row the L2 sees twice the requests for the same bytes and its request rate, not its bandwidth,
+// limits the kernel.  Both operand tiles travel from memory straight into LDS (global_load_lds, 16 bytes per
+// lane, no registers, no VALU) into a ring of kStages stages; one barrier per step publishes the stage that is
+// multiplied next and retires the one read before.  LDS rows are 128 bytes, swizzled (segment s of row r at
+// s ^ ((r >> 1) & 7)) so that operand reads are conflict-free; a load instruction of a wave fills 8 consecutive
+// rows, lane l landing on 16-byte slot l, so lane l fetches the segment that belongs there.
+#include "salr_device.hpp"
+#include "salr_internal.hpp"
+#include "salr_linear_common.hpp"
+
+namespace salr {
+
+constexpr int kDM = 256, kDK = 64;
+constexpr int kDXcds = 8;
+
+// segment (16 bytes = 8 bf16) position of logical segment `seg` in LDS row `row`, in elements
+__device__ __forceinline__ int dswz(int row, int seg) { return (seg ^ ((row >> 1) & 7)) * 8; }
+
+// kWN = waves along n: output tile 256 x (64 kWN), 4 kWN waves.  K % 64 == 0.
+template <int kWN, int kStages>
+__global__ __launch_bounds__(256 * kWN, 4) void dense_gemm_kernel(
+    const uint16_t* __restrict__ x, int64_t M, int64_t K, int64_t N, const uint16_t* __restrict__ wd,
+    const uint16_t* __restrict__ t, const uint16_t* __restrict__ b_cat, int R, int Rpad, uint16_t* __restrict__ y,
+    int m_tiles, int n_tiles) {
+    constexpr int kDN = 64 * kWN;
+    constexpr int kWaves = 4 * kWN;
+    constexpr int kXLoads = kDM / (8 * kWaves);   // load instructions per wave and step for the X tile (8 rows each)
+    constexpr int kWLoads = kDN / (8 * kWaves);   // ... and for the W tile
+    constexpr int kLoads = kXLoads + kWLoads;
+    static_assert(kWLoads == 2 && (kXLoads == 2 || kXLoads == 4), "tile/wave shape");
+    __shared__ __attribute__((aligned(16))) uint16_t Xs[kStages][kDM * kDK];
+    __shared__ __attribute__((aligned(16))) uint16_t Ws[kStages][kDN * kDK];
+
+    // consecutive workgroup ids land on different XCDs; all m-tiles of an n-tile stay on one XCD (one L2)
+    const int bid = blockIdx.x;
+    const int xcd = bid % kDXcds, local = bid / kDXcds;
+    const int nt = (local / m_tiles) * kDXcds + xcd;
+    const int mt = local % m_tiles;
+    if (nt >= n_tiles) return;  // uniform for the workgroup, before any barrier
+    const int64_t m0 = (int64_t)mt * kDM, n0 = (int64_t)nt * kDN;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / kWN, wn = wave % kWN;
+
+    // loader role: load j of wave w fills tile rows 8 (w + kWaves j) .. + 7; lane l lands on slot l % 8 of row l / 8
+    const int lrow = 8 * wave + (lane >> 3);          // row of load 0; load j is 8 kWaves j rows further down
+    const int lseg = (lane & 7) ^ ((lrow >> 1) & 7);  // logical segment stored in the lane's slot (same for all j)
+    const uint16_t* xptr[kXLoads];
+    const uint16_t* wptr[kWLoads];
+#pragma unroll
+    for (int j = 0; j < kXLoads; ++j) {
+        const int64_t row = m0 + lrow + 8 * kWaves * j;
+        xptr[j] = x + (row < M ? row : M - 1) * K + 8 * lseg;  // rows past the edge repeat the last row; never stored
+    }
+#pragma unroll
+    for (int j = 0; j < kWLoads; ++j) {
+        const int64_t row = n0 + lrow + 8 * kWaves * j;
+        wptr[j] = wd + (row < N ? row : N - 1) * K + 8 * lseg;
+    }
+    const int64_t steps = K / kDK;
+
+    // One 16-byte-per-lane load from memory straight into LDS: lane l of the wave lands on lds_base + 16 l.
+    // Written as assembly so that the waits stay under this kernel's control (vmcnt below): handed to the
+    // compiler as a builtin, every barrier of the loop would wait for ALL requests, also the newest ones.
+    auto load_to_lds = [&](const uint16_t* src, uint16_t* lds_base) {
+        const uint32_t lds_off = __builtin_amdgcn_readfirstlane(
+            (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds_base);
+        asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                     :
+                     : "v"(src), "s"(lds_off)
+                     : "memory");
+    };
+    auto fetch = [&](uint16_t* xs, uint16_t* ws, int64_t s) {
+        const int64_t sc = s < steps ? s : steps - 1;  // past the end: reload the last step (unused)
+#pragma unroll
+        for (int j = 0; j < kXLoads; ++j) load_to_lds(xptr[j] + sc * kDK, xs + (8 * wave + 8 * kWaves * j) * kDK);
+#pragma unroll
+        for (int j = 0; j < kWLoads; ++j) load_to_lds(wptr[j] + sc * kDK, ws + (8 * wave + 8 * kWaves * j) * kDK);
+    };
+    // the requests of the newest kStages - 2 steps may stay in flight, everything older has landed
+    static_assert((kStages - 2) * kLoads <= 15, "vmcnt immediate");
+    auto older_landed = [&]() { __builtin_amdgcn_s_waitcnt(0x0F70 | ((kStages - 2) * kLoads)); };
+
+    f32x16 acc00 = {0}, acc01 = {0}, acc10 = {0}, acc11 = {0};
+    // operand lane: row lane % 32 of a 32-row block, segment 2 j + lane / 32 in sub-step j (16 of the 64 k);
+    // rows 32 or 64 further down share the swizzle term
+    const int frag_row = lane & 31;
+    const int fsw = (frag_row >> 1) & 7, fhalf = lane >> 5;
+    auto mfma_substep = [&](const uint16_t* xa, const uint16_t* wb, int j) {
+        const int fk = ((2 * j + fhalf) ^ fsw) * 8;
+        auto frag = [](const uint16_t* p) { return *reinterpret_cast<const bf16x8*>(p); };
+        const bf16x8 a0 = frag(xa + fk), a1 = frag(xa + 32 * kDK + fk);
+        const bf16x8 b0 = frag(wb + fk), b1 = frag(wb + 32 * kDK + fk);
+        acc00 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b0, acc00, 0, 0, 0);
+        acc01 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b1, acc01, 0, 0, 0);
+        acc10 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b0, acc10, 0, 0, 0);
+        acc11 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b1, acc11, 0, 0, 0);
+    };
+    auto mfma_step = [&](const uint16_t* xs, const uint16_t* ws, int substeps) {
+        const uint16_t* xa = xs + (wm * 64 + frag_row) * kDK;
+        const uint16_t* wb = ws + (wn * 64 + frag_row) * kDK;
+        mfma_substep(xa, wb, 0);
+        mfma_substep(xa, wb, 1);
+        if (substeps == 4) {
+            mfma_substep(xa, wb, 2);
+            mfma_substep(xa, wb, 3);
+        }
+    };
+
+    // ---- k loop: stage s % kStages is multiplied while the requests of the next kStages - 1 steps are in flight
+    for (int p = 0; p < kStages - 1; ++p) fetch(Xs[p], Ws[p], p);
+    int cur = 0, nxt = kStages - 1;   // stage of step s, stage that step s + kStages - 1 goes into
+    for (int64_t s = 0; s < steps; ++s) {
+        older_landed();
+        __syncthreads();   // stage `cur` published; every wave is done with stage `nxt` (read in step s - 1)
+        fetch(Xs[nxt], Ws[nxt], s + kStages - 1);
+        mfma_step(Xs[cur], Ws[cur], 4);
+        cur = cur + 1 == kStages ? 0 : cur + 1;
+        nxt = nxt + 1 == kStages ? 0 : nxt + 1;
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): no request may land after this point
+    __syncthreads();
+
+    // ---- adapter k-steps of 32 (Sec. 3.2): Xs[0] := T[m, r0 .. r0+31], Ws[0] := B_cat[r0 .. r0+31, n] (transposed),
+    // both in segments 0..3 of the rows
+    if (R > 0) {
+        const int bcol = tid % kDN;                // tile row of Ws[0] = output column
+        const int64_t bn = (n0 + bcol < N) ? n0 + bcol : N - 1;
+        const int rr4 = tid / kDN;                 // rank row 4 i + rr4 of the k-step: segment i / 2 of that tile row
+        const int trow = tid >> 2, tseg = tid & 3; // T: four threads per row, 256 tile rows in 256 / (kWaves 16) passes
+        for (int r0 = 0; r0 < Rpad; r0 += 32) {
+#pragma unroll
+            for (int j = 0; j < 256 / (16 * kWaves); ++j) {
+                const int row = trow + 16 * kWaves * j;
+                const int64_t m = (m0 + row < M) ? m0 + row : M - 1;
+                *reinterpret_cast<uint4*>(&Xs[0][row * kDK + dswz(row, tseg)]) =
+                    *reinterpret_cast<const uint4*>(t + m * Rpad + r0 + 8 * tseg);
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int rg = r0 + 4 * i + rr4;
+                const uint16_t v = b_cat[(int64_t)(rg < R ? rg : R - 1) * N + bn];
+                Ws[0][bcol * kDK + dswz(bcol, i >> 1) + 4 * (i & 1) + rr4] = rg < R ? v : (uint16_t)0;
+            }
+            __syncthreads();
+            mfma_step(Xs[0], Ws[0], 2);
+            __syncthreads();
+        }
+    }
+
+    // ---- store: accumulator register e of a 32x32 tile holds row 8*(e/4) + 4*(lane/32) + e%4, column lane%32
+    auto store_tile = [&](const f32x16& a, int i, int j) {
+        const int64_t n = n0 + wn * 64 + 32 * j + (lane & 31);
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int64_t m = m0 + wm * 64 + 32 * i + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+            if (m < M && n < N) y[m * N + n] = f32_to_bf16_rne(a[e]);
+        }
+    };
+    store_tile(acc00, 0, 0);
+    store_tile(acc01, 0, 1);
+    store_tile(acc10, 1, 0);
+    store_tile(acc11, 1, 1);
+}
+
+hipError_t launch_linear_twostage(const LinearArgs& a, hipStream_t stream, const TimingEvents& ev) {
+    const int R = (int)a.R, Rpad = (int)adapter_rank_padded(a.R);
+    uint16_t* wd = reinterpret_cast<uint16_t*>(reinterpret_cast<char*>(a.t) + twostage_dense_offset(a.M, a.R));
+    hipError_t e = launch_decode(a.bitmap, a.values, a.row_offsets, a.N, a.K, wd, stream);
+    if (e != hipSuccess) return e;
+    if (R > 0) launch_adapter_t(a, stream);
+    const int m_tiles = (int)((a.M + kDM - 1) / kDM);
+    // 256 x 256 tiles when they fill the chip, else 256 x 128
+    const bool wide = (int64_t)m_tiles * ((a.N + 255) / 256) >= 224;
+    const int tn = wide ? 256 : 128;
+    const int n_tiles = (int)((a.N + tn - 1) / tn);
+    const int n_groups = (n_tiles + kDXcds - 1) / kDXcds;
+    const unsigned grid = (unsigned)(n_groups * m_tiles * kDXcds);
+    if (wide)
+        SALR_LAUNCH((dense_gemm_kernel<4, 2>), dim3(grid), dim3(1024), stream, ev, a.x, a.M, a.K, a.N, (const uint16_t*)wd,
+                    (const uint16_t*)a.t, a.b_cat, R, Rpad, a.y, m_tiles, n_tiles);
+    else
+        SALR_LAUNCH((dense_gemm_kernel<2, 3>), dim3(grid), dim3(512), stream, ev, a.x, a.M, a.K, a.N, (const uint16_t*)wd,
+                    (const uint16_t*)a.t, a.b_cat, R, Rpad, a.y, m_tiles, n_tiles);
+    return hipGetLastError();
+}
+
+}  // namespace salr

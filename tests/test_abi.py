@@ -61,6 +61,10 @@ def test_workspace_bytes(lib):
     assert lib.salr_linear_workspace_bytes(16, 4096, 4096, 16) == 16 * 16 * 32 * 4
     assert lib.salr_linear_workspace_bytes(1, 4096, 4096, 64) == 16 * 64 * 4
     assert lib.salr_linear_workspace_bytes(128, 4096, 4096, 32) == 128 * 32 * 2
+    # M >= 1024: T in bf16, then the decoded weight [N, K] in bf16
+    assert lib.salr_linear_workspace_bytes(2048, 4096, 14336, 32) == 2048 * 32 * 2 + 14336 * 4096 * 2
+    assert lib.salr_linear_workspace_bytes(1024, 64, 8, 0) == 8 * 64 * 2
+    assert lib.salr_linear_workspace_bytes(1024, 96, 8, 32) == 1024 * 32 * 2   # K % 64 != 0: no dense scratch
     assert lib.salr_linear_workspace_bytes(65, 4096, 4096, 1) == 4352  # 65*32*2 = 4160 rounded up to 256 B
     assert lib.salr_linear_workspace_bytes(16, 4096, 4096, 1000) == 0
 
