@@ -64,27 +64,31 @@ inline bool uses_twostage(int64_t M, int64_t K) { return M >= kTwoStageMinM && K
 
 inline size_t round_up_256(size_t b) { return (b + 255) / 256 * 256; }
 
-// Byte offset of the dense weight scratch inside the workspace of the two-stage path (T comes first).
-inline size_t twostage_dense_offset(int64_t M, int64_t R) {
+// Workspace layout of the large-batch paths (M > kStreamMaxM): T [M, Rpad] bf16, then the transposed padded
+// adapter a_t [Rpad, K] bf16, then (two-stage path only) the decoded weight [N, K] bf16; each 256-byte aligned.
+inline size_t adapter_t_bytes(int64_t M, int64_t R) {
     return R > 0 ? round_up_256((size_t)M * (size_t)adapter_rank_padded(R) * sizeof(uint16_t)) : 0;
 }
+inline size_t adapter_at_bytes(int64_t K, int64_t R) {
+    return R > 0 ? round_up_256((size_t)K * (size_t)adapter_rank_padded(R) * sizeof(uint16_t)) : 0;
+}
+inline size_t twostage_dense_offset(int64_t M, int64_t K, int64_t R) { return adapter_t_bytes(M, R) + adapter_at_bytes(K, R); }
 
-// Workspace the linear needs: the small-batch path keeps fp32 split-K partials of T, the tiled path T in bf16,
-// the two-stage path T in bf16 followed by the decoded weight [N, K] in bf16.
+// Workspace the linear needs: the small-batch path keeps fp32 split-K partials of T; the others see above.
 inline size_t linear_workspace_bytes(int64_t M, int64_t K, int64_t N, int64_t R) {
     if (M <= 0 || N <= 0) return 0;
-    const size_t rp = (size_t)adapter_rank_padded(R);
-    if (M <= kStreamMaxM) return R > 0 ? round_up_256((size_t)kStreamTSlices * (size_t)M * rp * sizeof(float)) : 0;
-    if (uses_twostage(M, K))
-        return twostage_dense_offset(M, R) + round_up_256((size_t)N * (size_t)K * sizeof(uint16_t));
-    return R > 0 ? round_up_256((size_t)M * rp * sizeof(uint16_t)) : 0;
+    if (M <= kStreamMaxM)
+        return R > 0 ? round_up_256((size_t)kStreamTSlices * (size_t)M * (size_t)adapter_rank_padded(R) * sizeof(float)) : 0;
+    size_t b = twostage_dense_offset(M, K, R);
+    if (uses_twostage(M, K)) b += round_up_256((size_t)N * (size_t)K * sizeof(uint16_t));
+    return b;
 }
 
 hipError_t launch_linear(const LinearArgs& args, hipStream_t stream);
 hipError_t launch_linear_stream(const LinearArgs& args, hipStream_t stream, const TimingEvents& ev);
 hipError_t launch_linear_tiled(const LinearArgs& args, hipStream_t stream, const TimingEvents& ev);
 hipError_t launch_linear_twostage(const LinearArgs& args, hipStream_t stream, const TimingEvents& ev);
-// T = X * A_cat in bf16 [M, Rpad] at the start of the workspace (tiled and two-stage paths)
+// T = X * A_cat in bf16 [M, Rpad] at the start of the workspace (every path with M > kStreamMaxM)
 void launch_adapter_t(const LinearArgs& args, hipStream_t stream);
 
 }  // namespace salr

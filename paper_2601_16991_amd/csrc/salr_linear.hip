@@ -1,7 +1,6 @@
 // The SALR linear layer  Y = X * What^T + (X * A_cat) * B_cat  (paper Sec. 3.2 and 3.3).
 //
-// Kernels in this file
-//   adapter_t_kernel        T = X * A_cat, fp32 accumulation, stored bf16 in the workspace
+// This file: the dispatch between the kernels, and
 //   linear_generic_kernel   any shape: 64 x 64 output tile per workgroup, decode of a 64 x 32 weight
 //                           tile into LDS per k-step, bf16 MFMA, adapters as extra k-steps
 #include <hip/hip_ext.h>
@@ -11,42 +10,6 @@
 #include "salr_linear_common.hpp"
 
 namespace salr {
-
-// ---------------------------------------------------------------------------------------------------
-// T[m, r] = sum_k X[m, k] * A_cat[k, r]   (Sec. 3.2: the first of the two concatenated GEMMs)
-// One workgroup per row m; thread (kslice, r) sums a slice of K, slices are reduced through LDS.
-// Columns R..Rpad-1 of T are written as zeros so the main kernel can run whole MFMA k-steps.
-// ---------------------------------------------------------------------------------------------------
-constexpr int kAdapterThreads = 256;
-
-__global__ __launch_bounds__(kAdapterThreads) void adapter_t_kernel(const uint16_t* __restrict__ x,
-                                                                    const uint16_t* __restrict__ a_cat, int64_t K,
-                                                                    int R, int Rpad, uint16_t* __restrict__ t) {
-    __shared__ float partial[kAdapterThreads];
-    const int64_t m = blockIdx.x;
-    const uint16_t* xr = x + m * K;
-    // R <= 256 columns: threads are laid out [slices][cols] with cols = power of two >= R (max 256)
-    int cols = 1;
-    while (cols < R) cols <<= 1;
-    const int slices = kAdapterThreads / cols;
-    const int r = threadIdx.x % cols;
-    const int s = threadIdx.x / cols;
-    float acc = 0.f;
-    if (r < R) {
-        for (int64_t k = s; k < K; k += slices) acc += bf16_bits_to_f32(xr[k]) * bf16_bits_to_f32(a_cat[k * R + r]);
-    }
-    partial[threadIdx.x] = acc;
-    __syncthreads();
-    if (s == 0) {
-        float sum = 0.f;
-        for (int i = 0; i < slices; ++i) sum += partial[i * cols + r];
-        if (r < Rpad) t[m * Rpad + r] = (r < R) ? f32_to_bf16_rne(sum) : (uint16_t)0;
-    }
-    // columns beyond `cols` (when Rpad > cols) are zero-filled by the threads of slice 0
-    if (s == 0) {
-        for (int c = cols + r; c < Rpad; c += cols) t[m * Rpad + c] = 0;
-    }
-}
 
 // ---------------------------------------------------------------------------------------------------
 // Generic fused kernel.  Workgroup = 4 waves, output tile 64 (m) x 64 (n), k-step 32.
@@ -198,10 +161,7 @@ hipError_t launch_linear(const LinearArgs& a, hipStream_t stream) {
     if (a.K >= 64 && a.K % 64 == 0) return launch_linear_tiled(a, stream, g_timing_events);
     const int R = (int)a.R;
     const int Rpad = (int)adapter_rank_padded(a.R);
-    if (R > 0) {
-        hipLaunchKernelGGL(adapter_t_kernel, dim3((unsigned)a.M), dim3(kAdapterThreads), 0, stream, a.x, a.a_cat, a.K, R,
-                           Rpad, a.t);
-    }
+    if (R > 0) launch_adapter_t(a, stream);
     const TimingEvents ev = g_timing_events;
     dim3 grid((unsigned)((a.N + kGenTN - 1) / kGenTN), (unsigned)((a.M + kGenTM - 1) / kGenTM));
     SALR_LAUNCH(linear_generic_kernel, grid, dim3(kGenThreads), stream, ev, a.x, a.M, a.K, a.N, a.bitmap, a.values,

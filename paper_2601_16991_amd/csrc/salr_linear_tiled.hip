@@ -1,21 +1,23 @@
-// Large-batch path of the SALR linear (M > 64): MFMA-bound, the two-stage pipeline of Sec. 3.3.
+// Medium-batch path of the SALR linear (64 < M < 1024): the two-stage pipeline of Sec. 3.3 inside one kernel.
 //
-// Workgroup = 8 waves, output tile 256 (m) x 256 (n), k-step 32, everything double-buffered in LDS:
+// Workgroup = 8 waves, output tile 256 (m) x 128 (n), k-step 32, two workgroups per CU (4 waves per SIMD), LDS
+// tiles double-buffered:
 //
+//   X tile       travels from memory straight into LDS (global_load_lds, 16 bytes per lane): the four lanes of
+//                a row fetch its 64 bytes of the k-step, no registers and no VALU involved;
 //   decode stage (all threads, for k-step s+1 while the MFMAs of step s run)
-//       thread (row = tid/2, half = tid%2) owns one weight row of the tile and two byte masks of the
-//       row's bitmap word.  Packed values arrive per 64-column chunk: each row's piece is contiguous in
-//       `values`, is fetched by the row's two threads with 16-byte loads two chunks ahead, parked in the
-//       row's LDS slot and expanded with the nibble rule (Sec. 3.3) into the dense LDS tile Ws.
-//   MFMA stage
-//       wave (wm, wn) owns 128 (m) x 64 (n): 4 x 2 tiles of v_mfma_f32_32x32x16_bf16, 128 accumulator
-//       registers; A fragments from the X tile Xs, B fragments from Ws (row pitch 80 B: conflict-free
-//       16-byte LDS reads for the 32-row operand layout).
+//       thread (row = tid/4, q = tid%4) owns byte q of the bitmap word of one weight row of the tile.  Packed
+//       values arrive per 64-column chunk: each row's piece is contiguous in `values`, is fetched by the row's
+//       four threads with 16-byte loads a chunk ahead, parked in the row's LDS slot and expanded with the
+//       nibble rule (Sec. 3.3) into the dense LDS tile Ws;
+//   MFMA stage   wave (wm, wn) owns 64 (m) x 64 (n): 2 x 2 tiles of v_mfma_f32_32x32x16_bf16;
 //   adapters (Sec. 3.2): after the K loop the same accumulators take Rpad/32 more k-steps with
-//       Xs := T (bf16, from adapter_t_mfma_kernel) and Ws := B_cat columns.
+//       Xs := T (bf16, from adapter_t_kernel) and Ws := B_cat columns.
 //
 // Consecutive workgroup ids land on different XCDs (8 of them, each with its own L2); the id -> tile
 // map keeps all m-tiles of one n-tile on the same XCD so the compressed rows are fetched into one L2.
+// Every m-tile decodes the weight tile again; from M = 1024 on, decoding once into memory is cheaper
+// (salr_linear_twostage.hip).
 #include "salr_device.hpp"
 #include "salr_internal.hpp"
 #include "salr_linear_common.hpp"
@@ -45,11 +47,6 @@ __global__ __launch_bounds__(kTiledThreads, 4) void linear_tiled_kernel(
     __shared__ __attribute__((aligned(16))) uint16_t Ws[2][kTN * kPitch];
     __shared__ __attribute__((aligned(16))) uint32_t stage[kTN * kSlotDw + 8];
     __shared__ uint32_t lut[kNibbleLutWords];
-#if defined(SALR_KO) && (SALR_KO & 32)
-    __shared__ uint32_t lds_pad[10000];   // 40 KB more: only one workgroup fits a CU
-    if (m_tiles < 0) lds_pad[blockIdx.x % 10000] = 1;
-    if (n_tiles < 0) y[0] = (uint16_t)lds_pad[threadIdx.x];
-#endif
 
     // ---- tile of this workgroup
     const int bid = blockIdx.x;
@@ -133,10 +130,6 @@ __global__ __launch_bounds__(kTiledThreads, 4) void linear_tiled_kernel(
     };
     // expand this thread's byte mask of `word` into Ws[buf]
     auto decode = [&](int buf, uint32_t word) {
-#if defined(SALR_KO) && (SALR_KO & 2)
-        *reinterpret_cast<uint4*>(&Ws[buf][wr * kPitch + swz(wr, q)]) = make_uint4(word, word, word, word);
-        return;
-#endif
         const uint32_t cb = c_local + __popc(word & ((1u << (8 * q)) - 1u));
         const uint4 qa = expand_byte(slot, lut, cb, (word >> (8 * q)) & 0xFFu);
         c_local += __popc(word);
@@ -157,10 +150,6 @@ __global__ __launch_bounds__(kTiledThreads, 4) void linear_tiled_kernel(
         const bf16x8 b00 = frag(wb + frag_k0), b10 = frag(wb + 32 * kPitch + frag_k0);
         const bf16x8 a01 = frag(xa + frag_k1), a11 = frag(xa + 32 * kPitch + frag_k1);
         const bf16x8 b01 = frag(wb + frag_k1), b11 = frag(wb + 32 * kPitch + frag_k1);
-#if defined(SALR_KO) && (SALR_KO & 1)
-        asm volatile("" ::"v"(a00), "v"(a10), "v"(b00), "v"(b10), "v"(a01), "v"(a11), "v"(b01), "v"(b11));
-        return;
-#endif
         acc00 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a00, b00, acc00, 0, 0, 0);
         acc01 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a00, b10, acc01, 0, 0, 0);
         acc10 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a10, b00, acc10, 0, 0, 0);
@@ -248,60 +237,118 @@ __global__ __launch_bounds__(kTiledThreads, 4) void linear_tiled_kernel(
 }
 
 // ---------------------------------------------------------------------------------------------------
-// T = X * A_cat for the tiled path (Sec. 3.2, first concatenated GEMM): workgroup (m-block of 64 rows,
-// rank tile of 16 columns), 4 waves split K, 16x16x32 bf16 MFMAs, LDS reduction, bf16 output
-// [M, Rpad] with zero padding columns.
+// T = X * A_cat for the large-batch paths (Sec. 3.2, first concatenated GEMM), bf16 output [M, Rpad].
+// A_cat arrives transposed and zero padded, a_t [Rpad, K] (written by the transposing pre-pass), so that
+// both MFMA operands are plain 16-byte loads along k.  Workgroup = 16 kMB rows of X, 8 waves that split K;
+// kRT rank tiles of 16 columns per pass over K (all of them in one pass up to rank 64); 16x16x32 bf16 MFMAs,
+// LDS reduction over the waves, padding columns come out as exact zeros.
 // ---------------------------------------------------------------------------------------------------
-constexpr int kTmWaves = 16;
-
-__global__ __launch_bounds__(kTmWaves * 64) void adapter_t_mfma_kernel(const uint16_t* __restrict__ x, int64_t M, int64_t K,
-                                                                       const uint16_t* __restrict__ a_cat, int R, int Rpad,
-                                                                       uint16_t* __restrict__ t) {
-    __shared__ float red[kTmWaves][4][4][64];
+template <int kMB, int kRT, int kTWaves, int kDepth>
+__global__ __launch_bounds__(kTWaves * 64) void adapter_t_kernel(const uint16_t* __restrict__ x, int64_t M, int64_t K,
+                                                                  const uint16_t* __restrict__ a_t, int Rpad,
+                                                                  uint16_t* __restrict__ t) {
+    __shared__ float red[kTWaves][kMB * kRT][4][64];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int i16 = lane & 15, g = lane >> 4;
-    const int64_t m0 = (int64_t)blockIdx.x * 64;
-    const int rt = blockIdx.y;
-    const int rc = 16 * rt + i16 < R ? 16 * rt + i16 : R - 1;
+    const int64_t m0 = (int64_t)blockIdx.x * 16 * kMB;
     const int64_t units = K >> 5;
-    f32x4 acc[4];
+    const uint16_t* xrow[kMB];
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll 4
-    for (int64_t u = wave; u < units; u += kTmWaves) {
-        const int64_t k0 = (u << 5) + 8 * g;
-        uint32_t e[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) e[j] = a_cat[(k0 + j) * R + rc];
-        const uint4 bq = make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16));
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt) {
-            const int64_t m = m0 + 16 * mt + i16;
-            const uint4 aq = *reinterpret_cast<const uint4*>(x + (m < M ? m : M - 1) * K + k0);
-            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(aq), as_bf16x8(bq), acc[mt], 0, 0, 0);
-        }
+    for (int mt = 0; mt < kMB; ++mt) {
+        const int64_t m = m0 + 16 * mt + i16;
+        xrow[mt] = x + (m < M ? m : M - 1) * K + 8 * g;
     }
+    for (int rb = 0; rb < Rpad; rb += 16 * kRT) {
+        // Rpad is a multiple of 32 and kRT of 2, so a pass never starts past the end; tiles past it are clamped
+        const uint16_t* arow[kRT];
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt)
+        for (int rt = 0; rt < kRT; ++rt) {
+            const int r = rb + 16 * rt + i16;
+            arow[rt] = a_t + (int64_t)(r < Rpad ? r : Rpad - 1) * K + 8 * g;
+        }
+        f32x4 acc[kMB][kRT];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) red[wave][mt][e][lane] = acc[mt][e];
-    __syncthreads();
-    for (int idx = threadIdx.x; idx < 1024; idx += kTmWaves * 64) {
-        const int l = idx & 63, e = (idx >> 6) & 3, mt = idx >> 8;
-        float s = 0.f;
+        for (int mt = 0; mt < kMB; ++mt)
 #pragma unroll
-        for (int w = 0; w < kTmWaves; ++w) s += red[w][mt][e][l];
-        const int64_t m = m0 + 16 * mt + 4 * (l >> 4) + e;
-        const int rr = 16 * rt + (l & 15);
-        if (m < M) t[m * Rpad + rr] = rr < R ? f32_to_bf16_rne(s) : (uint16_t)0;
+            for (int rt = 0; rt < kRT; ++rt) acc[mt][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        // kDepth k-steps per trip with every load issued before the first MFMA: the kernel lives on loads in flight
+        // each wave walks its own contiguous share of K, so that successive loads of a row are adjacent in memory
+        const int64_t per_wave = (units + kTWaves - 1) / kTWaves;
+        const int64_t u_begin = wave * per_wave < units ? wave * per_wave : units;
+        const int64_t u_end = (wave + 1) * per_wave < units ? (wave + 1) * per_wave : units;
+        const int64_t len = u_end - u_begin;
+        for (int64_t i0 = 0; i0 < len; i0 += kDepth) {
+            uint4 aq[kDepth][kMB], bq[kDepth][kRT];
+#pragma unroll
+            for (int d = 0; d < kDepth; ++d) {
+                const int64_t i = i0 + d < len ? i0 + d : len - 1;   // past the end: reload the last step, not used
+                const int64_t k0 = (u_begin + i) << 5;
+#pragma unroll
+                for (int mt = 0; mt < kMB; ++mt) aq[d][mt] = *reinterpret_cast<const uint4*>(xrow[mt] + k0);
+#pragma unroll
+                for (int rt = 0; rt < kRT; ++rt) bq[d][rt] = *reinterpret_cast<const uint4*>(arow[rt] + k0);
+            }
+#pragma unroll
+            for (int d = 0; d < kDepth; ++d) {
+                if (i0 + d < len) {   // wave-uniform
+#pragma unroll
+                    for (int mt = 0; mt < kMB; ++mt)
+#pragma unroll
+                        for (int rt = 0; rt < kRT; ++rt)
+                            acc[mt][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(aq[d][mt]), as_bf16x8(bq[d][rt]),
+                                                                                  acc[mt][rt], 0, 0, 0);
+                }
+            }
+        }
+#pragma unroll
+        for (int mt = 0; mt < kMB; ++mt)
+#pragma unroll
+            for (int rt = 0; rt < kRT; ++rt)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) red[wave][mt * kRT + rt][e][lane] = acc[mt][rt][e];
+        __syncthreads();
+        // accumulator layout of the 16x16 MFMA: lane holds column lane % 16, rows 4 (lane / 16) + e
+        for (int idx = threadIdx.x; idx < kMB * kRT * 256; idx += kTWaves * 64) {
+            const int l = idx & 63, e = (idx >> 6) & 3, tile = idx >> 8;
+            float sum = 0.f;
+#pragma unroll
+            for (int w = 0; w < kTWaves; ++w) sum += red[w][tile][e][l];
+            const int64_t m = m0 + 16 * (tile / kRT) + 4 * (l >> 4) + e;
+            const int r = rb + 16 * (tile % kRT) + (l & 15);
+            if (m < M && r < Rpad) t[m * Rpad + r] = f32_to_bf16_rne(sum);
+        }
+        __syncthreads();
+    }
+}
+
+// a_t[r][k] = A_cat[k][r] for r < R, 0 for R <= r < Rpad: one thread per k and block of 8 ranks.
+__global__ __launch_bounds__(256) void adapter_transpose_kernel(const uint16_t* __restrict__ a_cat, int64_t K, int R,
+                                                                 int Rpad, uint16_t* __restrict__ a_t) {
+    const int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (k >= K) return;
+    const int r0 = 8 * blockIdx.y;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int r = r0 + j;
+        a_t[(int64_t)r * K + k] = r < R ? a_cat[k * R + r] : (uint16_t)0;
     }
 }
 
 void launch_adapter_t(const LinearArgs& a, hipStream_t stream) {
     const int R = (int)a.R, Rpad = (int)adapter_rank_padded(a.R);
-    hipLaunchKernelGGL(adapter_t_mfma_kernel, dim3((unsigned)((a.M + 63) / 64), Rpad / 16), dim3(kTmWaves * 64), 0, stream,
-                       a.x, a.M, a.K, a.a_cat, R, Rpad, a.t);
+    uint16_t* a_t = reinterpret_cast<uint16_t*>(reinterpret_cast<char*>(a.t) + adapter_t_bytes(a.M, a.R));
+    hipLaunchKernelGGL(adapter_transpose_kernel, dim3((unsigned)((a.K + 255) / 256), Rpad / 8), dim3(256), 0, stream, a.a_cat,
+                       a.K, R, Rpad, a_t);
+    // Every workgroup reads all of a_t, so rows per workgroup trade that traffic against the number of workgroups.
+    const bool four = Rpad % 64 == 0;          // rank tiles per pass over K
+    const bool wide = a.M >= 65536;            // 32 rows and 16 waves per workgroup
+    const unsigned g16 = (unsigned)((a.M + 15) / 16), g32 = (unsigned)((a.M + 31) / 32);
+    const uint16_t* at = a_t;
+    if (wide && four) hipLaunchKernelGGL((adapter_t_kernel<2, 4, 16, 2>), dim3(g32), dim3(1024), 0, stream, a.x, a.M, a.K, at, Rpad, a.t);
+    else if (wide) hipLaunchKernelGGL((adapter_t_kernel<2, 2, 16, 4>), dim3(g32), dim3(1024), 0, stream, a.x, a.M, a.K, at, Rpad, a.t);
+    else if (four) hipLaunchKernelGGL((adapter_t_kernel<1, 4, 8, 4>), dim3(g16), dim3(512), 0, stream, a.x, a.M, a.K, at, Rpad, a.t);
+    else hipLaunchKernelGGL((adapter_t_kernel<1, 2, 8, 4>), dim3(g16), dim3(512), 0, stream, a.x, a.M, a.K, at, Rpad, a.t);
 }
 
 hipError_t launch_linear_tiled(const LinearArgs& a, hipStream_t stream, const TimingEvents& ev) {

@@ -176,7 +176,7 @@ __global__ __launch_bounds__(256 * kWN, 4) void dense_gemm_kernel(
 
 hipError_t launch_linear_twostage(const LinearArgs& a, hipStream_t stream, const TimingEvents& ev) {
     const int R = (int)a.R, Rpad = (int)adapter_rank_padded(a.R);
-    uint16_t* wd = reinterpret_cast<uint16_t*>(reinterpret_cast<char*>(a.t) + twostage_dense_offset(a.M, a.R));
+    uint16_t* wd = reinterpret_cast<uint16_t*>(reinterpret_cast<char*>(a.t) + twostage_dense_offset(a.M, a.K, a.R));
     hipError_t e = launch_decode(a.bitmap, a.values, a.row_offsets, a.N, a.K, wd, stream);
     if (e != hipSuccess) return e;
     if (R > 0) launch_adapter_t(a, stream);

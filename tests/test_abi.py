@@ -56,16 +56,18 @@ def test_words_per_row(lib):
 def test_workspace_bytes(lib):
     assert lib.salr_linear_workspace_bytes(16, 4096, 4096, 0) == 0
     assert lib.salr_linear_workspace_bytes(0, 4096, 4096, 32) == 0
-    # M <= 64: sixteen split-K partials of T in fp32; larger M: T in bf16.  Rank padded to 32.
+    # M <= 64: sixteen split-K partials of T in fp32.  Rank padded to 32.
     assert lib.salr_linear_workspace_bytes(16, 4096, 4096, 32) == 16 * 16 * 32 * 4
     assert lib.salr_linear_workspace_bytes(16, 4096, 4096, 16) == 16 * 16 * 32 * 4
     assert lib.salr_linear_workspace_bytes(1, 4096, 4096, 64) == 16 * 64 * 4
-    assert lib.salr_linear_workspace_bytes(128, 4096, 4096, 32) == 128 * 32 * 2
-    # M >= 1024: T in bf16, then the decoded weight [N, K] in bf16
-    assert lib.salr_linear_workspace_bytes(2048, 4096, 14336, 32) == 2048 * 32 * 2 + 14336 * 4096 * 2
+    # larger M: T [M, Rpad] and the transposed padded A_cat [Rpad, K] in bf16, each rounded up to 256 B
+    assert lib.salr_linear_workspace_bytes(128, 4096, 4096, 32) == 128 * 32 * 2 + 32 * 4096 * 2
+    assert lib.salr_linear_workspace_bytes(65, 4096, 4096, 1) == 4352 + 32 * 4096 * 2   # 65*32*2 = 4160 -> 4352
+    assert lib.salr_linear_workspace_bytes(128, 4096, 4096, 0) == 0
+    # M >= 1024 and K % 64 == 0: additionally the decoded weight [N, K] in bf16
+    assert lib.salr_linear_workspace_bytes(2048, 4096, 14336, 32) == 2048 * 32 * 2 + 32 * 4096 * 2 + 14336 * 4096 * 2
     assert lib.salr_linear_workspace_bytes(1024, 64, 8, 0) == 8 * 64 * 2
-    assert lib.salr_linear_workspace_bytes(1024, 96, 8, 32) == 1024 * 32 * 2   # K % 64 != 0: no dense scratch
-    assert lib.salr_linear_workspace_bytes(65, 4096, 4096, 1) == 4352  # 65*32*2 = 4160 rounded up to 256 B
+    assert lib.salr_linear_workspace_bytes(1024, 96, 8, 32) == 1024 * 32 * 2 + 32 * 96 * 2   # K % 64 != 0: no dense scratch
     assert lib.salr_linear_workspace_bytes(16, 4096, 4096, 1000) == 0
 
 
