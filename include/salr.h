@@ -122,7 +122,7 @@ salr_status_t salr_decode(const uint32_t* bitmap, const uint16_t* values, const 
 
 /*
  * Bytes of device workspace salr_sparse_lowrank_linear needs for these sizes (0 is possible).
- * It holds T = X * A_cat, for M > 64 a transposed copy of A_cat, and for M >= 1024 (where the weight
+ * It holds T = X * A_cat, for M > 64 a transposed copy of A_cat, and for M >= 256 (where the weight
  * is decoded once per call into a dense scratch matrix that the matrix-core stage then reads) N * K
  * more bf16 elements; nothing in it outlives the call.  Returns 0 for invalid sizes.
  */

@@ -57,9 +57,9 @@ constexpr int64_t kStreamMaxM = 64;
 constexpr int kStreamTSlices = 16;
 constexpr int kMaxRankPadded = 256;  // R <= 256: pitch of the T tile the streaming kernels keep in LDS
 
-// Largest-batch path: M >= kTwoStageMinM decodes the weight once into a dense scratch matrix, then runs a
+// Large-batch path: M >= kTwoStageMinM decodes the weight once into a dense scratch matrix, then runs a
 // dense MFMA GEMM on it.
-constexpr int64_t kTwoStageMinM = 1024;
+constexpr int64_t kTwoStageMinM = 256;
 inline bool uses_twostage(int64_t M, int64_t K) { return M >= kTwoStageMinM && K >= 64 && K % 64 == 0; }
 
 inline size_t round_up_256(size_t b) { return (b + 255) / 256 * 256; }

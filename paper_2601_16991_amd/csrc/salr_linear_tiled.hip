@@ -1,4 +1,4 @@
-// Medium-batch path of the SALR linear (64 < M < 1024): the two-stage pipeline of Sec. 3.3 inside one kernel.
+// Medium-batch path of the SALR linear (64 < M < 256): the two-stage pipeline of Sec. 3.3 inside one kernel.
 //
 // Workgroup = 8 waves, output tile 256 (m) x 128 (n), k-step 32, two workgroups per CU (4 waves per SIMD), LDS
 // tiles double-buffered:
@@ -16,7 +16,7 @@
 //
 // Consecutive workgroup ids land on different XCDs (8 of them, each with its own L2); the id -> tile
 // map keeps all m-tiles of one n-tile on the same XCD so the compressed rows are fetched into one L2.
-// Every m-tile decodes the weight tile again; from M = 1024 on, decoding once into memory is cheaper
+// Every m-tile decodes the weight tile again; from M = 256 on, decoding once into memory is cheaper
 // (salr_linear_twostage.hip).
 #include "salr_device.hpp"
 #include "salr_internal.hpp"

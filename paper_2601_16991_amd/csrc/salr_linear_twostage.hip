@@ -1,8 +1,8 @@
-// Largest-batch path of the SALR linear: the two stages of Sec. 3.3 ("Pipeline Design") as two kernels.
+// Large-batch path of the SALR linear (M >= 256): the two stages of Sec. 3.3 ("Pipeline Design") as two kernels.
 //
 //   stage 1  bitmap decode of the whole weight into a dense bf16 scratch matrix (decode_kernel of the codec,
 //            once per call: the fused kernels repeat the decode for every 256-row block of X, which at
-//            M >= 1024 costs more than one round trip of the dense matrix through memory);
+//            M >= 256 costs more than one round trip of the dense matrix through memory);
 //   stage 2  dense_gemm_kernel: Y = X * Wd^T (+ T * B_cat, Sec. 3.2) on the matrix cores.
 //
 // dense_gemm_kernel: output tile 256 (m) x 64 kWN (n), 4 kWN waves, wave (wm, wn) owns 64 x 64 = 2 x 2 tiles of

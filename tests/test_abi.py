@@ -64,7 +64,9 @@ def test_workspace_bytes(lib):
     assert lib.salr_linear_workspace_bytes(128, 4096, 4096, 32) == 128 * 32 * 2 + 32 * 4096 * 2
     assert lib.salr_linear_workspace_bytes(65, 4096, 4096, 1) == 4352 + 32 * 4096 * 2   # 65*32*2 = 4160 -> 4352
     assert lib.salr_linear_workspace_bytes(128, 4096, 4096, 0) == 0
-    # M >= 1024 and K % 64 == 0: additionally the decoded weight [N, K] in bf16
+    assert lib.salr_linear_workspace_bytes(255, 4096, 4096, 0) == 0
+    # M >= 256 and K % 64 == 0: additionally the decoded weight [N, K] in bf16
+    assert lib.salr_linear_workspace_bytes(256, 4096, 4096, 0) == 4096 * 4096 * 2
     assert lib.salr_linear_workspace_bytes(2048, 4096, 14336, 32) == 2048 * 32 * 2 + 32 * 4096 * 2 + 14336 * 4096 * 2
     assert lib.salr_linear_workspace_bytes(1024, 64, 8, 0) == 8 * 64 * 2
     assert lib.salr_linear_workspace_bytes(1024, 96, 8, 32) == 1024 * 32 * 2 + 32 * 96 * 2   # K % 64 != 0: no dense scratch
