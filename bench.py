@@ -81,7 +81,7 @@ class HipEvents:
 class Layer:
     """Encoded weight copies + adapters of one synthetic layer on the device."""
 
-    def __init__(self, cfg, permille, max_copies=64):
+    def __init__(self, cfg, permille, max_copies=64, nm=None):
         import numpy as np
         import torch
         import paper_2601_16991_amd as salr
@@ -89,12 +89,17 @@ class Layer:
         dev = torch.device("cuda:0")
         self.cfg, self.permille = cfg, permille
         w = torch.from_numpy(wl.dense_weight(cfg).view(np.int16)).to(dev)
-        self.w_hat = salr.mask_rows(w, cfg.keep(permille))
+        if nm is None:   # per-row top-keep (the workloads of the configs)
+            self.w_hat = salr.mask_rows(w, cfg.keep(permille))
+            expect = cfg.N * cfg.keep(permille)
+        else:            # N:M groups (the pattern of the paper's inference-throughput table)
+            self.w_hat = salr.mask_nm(w, nm[0], nm[1])
+            expect = cfg.N * cfg.K // nm[1] * nm[0]
         del w
         bitmap, values, offsets = salr.encode(self.w_hat)
         torch.cuda.synchronize()
         self.nnz = int(values.numel())
-        assert self.nnz == cfg.N * cfg.keep(permille), (self.nnz, cfg.N * cfg.keep(permille))
+        assert self.nnz == expect, (self.nnz, expect)
         enc_bytes = bitmap.numel() * 4 + self.nnz * 2 + offsets.numel() * 4
         self.ncopies = int(min(max_copies, max(2, -(-ROTATE_BYTES // enc_bytes))))
         self.enc = [(bitmap, values, offsets)]
@@ -358,6 +363,15 @@ def main():
                 "hbm_frac_kernel": round(ab / (float(np.mean(k_ms)) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                 "speedup_vs_dense_gemm": round(d_ms / w_ms, 3)}
             log(f"M={m}: {extras[f'{cfg.name}_M{m}']}")
+        # second workload: the same layer under a 2:4 mask (constant popcount per nibble)
+        layer24 = Layer(cfg, permille, nm=(2, 4))
+        w_ms, k_ms = time_linear(layer24, M, args.steps, args.warmup, events=True)
+        extras[f"{cfg.name}_M{M}_mask2of4"] = {
+            "ms_per_step": round(w_ms, 6), "GB/s": round(alg_bytes / w_ms / 1e6, 1),
+            "kernel_avg_us": round(float(np.mean(k_ms)) * 1e3, 3),
+            "hbm_frac_kernel": round(alg_bytes / (float(np.mean(k_ms)) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        log(f"2:4 mask, M={M}: {extras[f'{cfg.name}_M{M}_mask2of4']}")
+        del layer24
         extras["codec_" + cfg.name] = time_codec(layer, 20)
         log("codec:", extras["codec_" + cfg.name])
         del layer

@@ -143,6 +143,89 @@ __global__ __launch_bounds__(kCodecThreads) void decode_kernel(const uint32_t* _
     }
 }
 
+// Decoder for rows whose output can be written with 16-byte stores.  One workgroup per row, but the waves
+// work on their own: a row is cut into groups of 512 columns (one byte mask per lane), a first pass popcounts
+// the bitmap row into per-group start offsets (the only block barriers), then every wave takes groups on its
+// own -- wave scan of the byte popcounts, the group's values (one contiguous piece, at most 65 aligned 16-byte
+// vectors) copied into the wave's LDS slot, nibble expansion, one 16-byte store per lane -- with the loads of
+// its next group already in flight.
+constexpr int kDecWaves = kCodecThreads / kWave;
+constexpr int kDecMaxGroups = 1024;   // rows up to 524288 columns
+
+__global__ __launch_bounds__(kCodecThreads) void decode_rows_kernel(const uint32_t* __restrict__ bitmap,
+                                                                    const uint16_t* __restrict__ values,
+                                                                    const uint32_t* __restrict__ row_offsets, int64_t cols,
+                                                                    int64_t wpr, uint16_t* __restrict__ out) {
+    __shared__ uint32_t prefix[kDecMaxGroups + 1];
+    __shared__ __attribute__((aligned(16))) uint32_t slot[kDecWaves][65 * 4 + 8];
+    __shared__ uint32_t lut[kNibbleLutWords];
+    nibble_lut_init(lut);
+    const int lane = lane_id();
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int64_t n = blockIdx.x;
+    const uint32_t* brow = bitmap + n * wpr;
+    const int groups = (int)((wpr + 15) / 16);
+    // ---- pass 1: nonzeros per group of 16 words, then their exclusive prefix
+    for (int g = threadIdx.x >> 4; g < groups; g += kCodecThreads / 16) {
+        const int64_t w = 16 * (int64_t)g + (lane & 15);
+        uint32_t c = w < wpr ? __popc(brow[w]) : 0u;
+#pragma unroll
+        for (int d = 8; d > 0; d >>= 1) c += __shfl_xor(c, d, kWave);
+        if ((lane & 15) == 0) prefix[g + 1] = c;
+    }
+    __syncthreads();
+    if (wave == 0) {
+        uint32_t carry = 0;
+        for (int base = 0; base < groups; base += kWave) {
+            const int g = base + lane;
+            const uint32_t c = g < groups ? prefix[g + 1] : 0u;
+            const uint32_t incl = wave_inclusive_scan(c);
+            if (g < groups) prefix[g + 1] = carry + incl;
+            carry += __shfl(incl, kWave - 1, kWave);
+        }
+        if (lane == 0) prefix[0] = 0;
+    }
+    __syncthreads();
+    // ---- pass 2
+    const uint8_t* mask_bytes = reinterpret_cast<const uint8_t*>(brow);
+    const uint4* values128 = reinterpret_cast<const uint4*>(values);
+    uint16_t* row_out = out + n * cols;
+    const int64_t units = (cols + kUnit - 1) / kUnit;
+    const uint32_t row_start = row_offsets[n];
+    uint32_t* my_slot = slot[wave];
+    auto group_loads = [&](int g, uint32_t& m, uint4& v, uint32_t& off, uint32_t& nv, uint32_t& vbase) {
+        const int64_t u = 64 * (int64_t)g + lane;
+        m = (g < groups && u < units) ? mask_bytes[u] : 0u;
+        const uint32_t gi = g < groups ? g : groups - 1;
+        const uint32_t cursor = row_start + prefix[gi];
+        const uint32_t total = g < groups ? prefix[gi + 1] - prefix[gi] : 0u;
+        off = cursor & 7u;
+        nv = total ? (off + total + 7u) >> 3 : 0u;
+        // lanes past the piece repeat its last vector (clamped, not predicated); an empty piece loads nothing new
+        const uint32_t li = nv ? ((uint32_t)lane < nv ? lane : nv - 1u) : 0u;
+        vbase = cursor >> 3;
+        v = nv ? values128[vbase + li] : make_uint4(0, 0, 0, 0);
+    };
+    uint32_t m, off, nv, vbase;
+    uint4 v;
+    group_loads(wave, m, v, off, nv, vbase);
+    for (int g = wave; g < groups; g += kDecWaves) {
+        uint32_t m2, off2, nv2, vbase2;
+        uint4 v2;
+        group_loads(g + kDecWaves, m2, v2, off2, nv2, vbase2);   // next group of this wave, in flight while this one expands
+        const uint32_t incl = wave_inclusive_scan(__popc(m));
+        if ((uint32_t)lane < nv) reinterpret_cast<uint4*>(my_slot)[lane] = v;
+        // a full group that starts off a vector boundary spans 65 vectors: the last one is fetched on the spot
+        if (__builtin_amdgcn_readfirstlane(nv) > 64u && lane == 0) reinterpret_cast<uint4*>(my_slot)[64] = values128[vbase + 64];
+        __builtin_amdgcn_wave_barrier();
+        const uint4 q = expand_byte(my_slot, lut, off + incl - __popc(m), m);
+        __builtin_amdgcn_wave_barrier();
+        const int64_t u = 64 * (int64_t)g + lane;
+        if (u < units) *reinterpret_cast<uint4*>(row_out + u * kUnit) = q;
+        m = m2; v = v2; off = off2; nv = nv2; vbase = vbase2;
+    }
+}
+
 static bool vec_ok(const void* p, int64_t cols) {
     return (cols % kUnit == 0) && ((reinterpret_cast<uintptr_t>(p) & 15u) == 0);
 }
@@ -167,7 +250,9 @@ hipError_t launch_decode(const uint32_t* bitmap, const uint16_t* values, const u
                          int64_t cols, uint16_t* out, hipStream_t stream) {
     if (rows == 0 || cols == 0) return hipSuccess;
     const int64_t wpr = (cols + 31) / 32;
-    if (vec_ok(out, cols))
+    if (vec_ok(out, cols) && (wpr + 15) / 16 <= kDecMaxGroups && (reinterpret_cast<uintptr_t>(values) & 15u) == 0)
+        hipLaunchKernelGGL(decode_rows_kernel, dim3((unsigned)rows), dim3(kCodecThreads), 0, stream, bitmap, values, row_offsets, cols, wpr, out);
+    else if (vec_ok(out, cols))
         hipLaunchKernelGGL(decode_kernel<true>, dim3((unsigned)rows), dim3(kCodecThreads), 0, stream, bitmap, values, row_offsets, rows, cols, wpr, out);
     else
         hipLaunchKernelGGL(decode_kernel<false>, dim3((unsigned)rows), dim3(kCodecThreads), 0, stream, bitmap, values, row_offsets, rows, cols, wpr, out);

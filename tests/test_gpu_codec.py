@@ -59,6 +59,15 @@ def test_codec_special_patterns():
     _check_codec(w, "neg-zero / nan / inf / denormal")
 
 
+def test_codec_dense_groups_off_vector_boundaries():
+    """Fully dense 512-column groups whose values start at every offset 0..7 inside a 16-byte vector: the
+    decoder stages up to 65 vectors for such a group."""
+    w = _random_sparse(9, 1544, 1.0, 4242)          # 3 groups of 512 + a ragged fourth of 8 columns
+    for r in range(8):
+        w[r, :r] = 0                                  # row r has r zeros: row r + 1 starts at offset (...) % 8 != 0
+    _check_codec(w, "dense groups, odd starts")
+
+
 def test_codec_empty():
     salr = _salr()
     w = torch.zeros((0, 64), dtype=torch.int16, device=dev())
