@@ -1,12 +1,13 @@
 // Large-batch path of the SALR linear (M >= 256): the two stages of Sec. 3.3 ("Pipeline Design") as two kernels.
 //
-//   stage 1  bitmap decode of the whole weight into a dense bf16 scratch matrix (decode_kernel of the codec,
+//   stage 1  bitmap decode of the whole weight into a dense bf16 scratch matrix (the decode kernel of the codec,
 //            once per call: the fused kernels repeat the decode for every 256-row block of X, which at
 //            M >= 256 costs more than one round trip of the dense matrix through memory);
 //   stage 2  dense_gemm_kernel: Y = X * Wd^T (+ T * B_cat, Sec. 3.2) on the matrix cores.
 //
-// dense_gemm_kernel: output tile 256 (m) x 64 kWN (n), 4 kWN waves, wave (wm, wn) owns 64 x 64 = 2 x 2 tiles of
-// v_mfma_f32_32x32x16_bf16.  A k-step is 64 wide so that every row of a tile is one whole 128-byte line: at 64
+// dense_gemm_kernel: output tile 256 (m) x 64 kWN (n); wave (wm, wn) owns 32 kMI x 64 = kMI x 2 tiles of
+// v_mfma_f32_32x32x16_bf16 (128 x 64 per wave, 8 waves, on 256 x 256 tiles; 64 x 64 on 256 x 128 tiles when the
+// wide ones would not fill the chip).  A k-step is 64 wide so that every row of a tile is one whole 128-byte line: at 64
 // bytes per row the L2 sees twice the requests for the same bytes and its request rate, not its bandwidth,
 // limits the kernel.  Both operand tiles travel from memory straight into LDS (global_load_lds, 16 bytes per
 // lane, no registers, no VALU) into a ring of kStages stages; one barrier per step publishes the stage that is
@@ -25,18 +26,21 @@ constexpr int kDXcds = 8;
 // segment (16 bytes = 8 bf16) position of logical segment `seg` in LDS row `row`, in elements
 __device__ __forceinline__ int dswz(int row, int seg) { return (seg ^ ((row >> 1) & 7)) * 8; }
 
-// kWN = waves along n: output tile 256 x (64 kWN), 4 kWN waves.  K % 64 == 0.
-template <int kWN, int kStages>
-__global__ __launch_bounds__(256 * kWN, 4) void dense_gemm_kernel(
+// Output tile 256 x (64 kWN); wave (wm, wn) owns 32 kMI rows x 64 columns, so there are (8 / kMI) kWN waves:
+// kMI = 2: 64 x 64 wave tiles, 4 waves per SIMD at kWN = 4; kMI = 4: 128 x 64 wave tiles, 2 waves per SIMD with
+// room in the registers to fetch the operands of the next 16 k while the current ones are multiplied.
+// K % 64 == 0.
+template <int kMI, int kWN, int kStages>
+__global__ __launch_bounds__(64 * (8 / kMI) * kWN, (8 / kMI) * kWN / 4) void dense_gemm_kernel(
     const uint16_t* __restrict__ x, int64_t M, int64_t K, int64_t N, const uint16_t* __restrict__ wd,
     const uint16_t* __restrict__ t, const uint16_t* __restrict__ b_cat, int R, int Rpad, uint16_t* __restrict__ y,
     int m_tiles, int n_tiles) {
     constexpr int kDN = 64 * kWN;
-    constexpr int kWaves = 4 * kWN;
+    constexpr int kWaves = (8 / kMI) * kWN;
     constexpr int kXLoads = kDM / (8 * kWaves);   // load instructions per wave and step for the X tile (8 rows each)
     constexpr int kWLoads = kDN / (8 * kWaves);   // ... and for the W tile
     constexpr int kLoads = kXLoads + kWLoads;
-    static_assert(kWLoads == 2 && (kXLoads == 2 || kXLoads == 4), "tile/wave shape");
+    static_assert(kDM % (8 * kWaves) == 0 && kDN % (8 * kWaves) == 0, "tile/wave shape");
     __shared__ __attribute__((aligned(16))) uint16_t Xs[kStages][kDM * kDK];
     __shared__ __attribute__((aligned(16))) uint16_t Ws[kStages][kDN * kDK];
 
@@ -92,29 +96,47 @@ __global__ __launch_bounds__(256 * kWN, 4) void dense_gemm_kernel(
     static_assert((kStages - 2) * kLoads <= 15, "vmcnt immediate");
     auto older_landed = [&]() { __builtin_amdgcn_s_waitcnt(0x0F70 | ((kStages - 2) * kLoads)); };
 
-    f32x16 acc00 = {0}, acc01 = {0}, acc10 = {0}, acc11 = {0};
+    f32x16 acc[kMI][2];
+#pragma unroll
+    for (int i = 0; i < kMI; ++i) acc[i][0] = acc[i][1] = f32x16{0};
     // operand lane: row lane % 32 of a 32-row block, segment 2 j + lane / 32 in sub-step j (16 of the 64 k);
     // rows 32 or 64 further down share the swizzle term
     const int frag_row = lane & 31;
     const int fsw = (frag_row >> 1) & 7, fhalf = lane >> 5;
-    auto mfma_substep = [&](const uint16_t* xa, const uint16_t* wb, int j) {
-        const int fk = ((2 * j + fhalf) ^ fsw) * 8;
-        auto frag = [](const uint16_t* p) { return *reinterpret_cast<const bf16x8*>(p); };
-        const bf16x8 a0 = frag(xa + fk), a1 = frag(xa + 32 * kDK + fk);
-        const bf16x8 b0 = frag(wb + fk), b1 = frag(wb + 32 * kDK + fk);
-        acc00 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b0, acc00, 0, 0, 0);
-        acc01 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b1, acc01, 0, 0, 0);
-        acc10 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b0, acc10, 0, 0, 0);
-        acc11 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b1, acc11, 0, 0, 0);
+    struct Frags {
+        bf16x8 a[kMI], b[2];
     };
+    auto load_frags = [&](const uint16_t* xa, const uint16_t* wb, int j) -> Frags {
+        const int fk = ((2 * j + fhalf) ^ fsw) * 8;
+        Frags f;
+#pragma unroll
+        for (int i = 0; i < kMI; ++i) f.a[i] = *reinterpret_cast<const bf16x8*>(xa + 32 * i * kDK + fk);
+        f.b[0] = *reinterpret_cast<const bf16x8*>(wb + fk);
+        f.b[1] = *reinterpret_cast<const bf16x8*>(wb + 32 * kDK + fk);
+        return f;
+    };
+    auto multiply = [&](const Frags& f) {
+#pragma unroll
+        for (int i = 0; i < kMI; ++i) {
+            acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[0], acc[i][0], 0, 0, 0);
+            acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[1], acc[i][1], 0, 0, 0);
+        }
+    };
+    // the operands of sub-step j + 1 are requested before the MFMAs of sub-step j issue
     auto mfma_step = [&](const uint16_t* xs, const uint16_t* ws, int substeps) {
-        const uint16_t* xa = xs + (wm * 64 + frag_row) * kDK;
+        const uint16_t* xa = xs + (wm * 32 * kMI + frag_row) * kDK;
         const uint16_t* wb = ws + (wn * 64 + frag_row) * kDK;
-        mfma_substep(xa, wb, 0);
-        mfma_substep(xa, wb, 1);
+        Frags f0 = load_frags(xa, wb, 0);
+        Frags f1 = load_frags(xa, wb, 1);
+        multiply(f0);
         if (substeps == 4) {
-            mfma_substep(xa, wb, 2);
-            mfma_substep(xa, wb, 3);
+            f0 = load_frags(xa, wb, 2);
+            multiply(f1);
+            f1 = load_frags(xa, wb, 3);
+            multiply(f0);
+            multiply(f1);
+        } else {
+            multiply(f1);
         }
     };
 
@@ -135,23 +157,25 @@ __global__ __launch_bounds__(256 * kWN, 4) void dense_gemm_kernel(
     // ---- adapter k-steps of 32 (Sec. 3.2): Xs[0] := T[m, r0 .. r0+31], Ws[0] := B_cat[r0 .. r0+31, n] (transposed),
     // both in segments 0..3 of the rows
     if (R > 0) {
+        constexpr int kRowsAtOnce = 64 * kWaves / kDN;   // rank rows of the k-step written per pass (2 or 4)
         const int bcol = tid % kDN;                // tile row of Ws[0] = output column
         const int64_t bn = (n0 + bcol < N) ? n0 + bcol : N - 1;
-        const int rr4 = tid / kDN;                 // rank row 4 i + rr4 of the k-step: segment i / 2 of that tile row
+        const int rr4 = tid / kDN;                 // this thread's rank row inside a pass
         const int trow = tid >> 2, tseg = tid & 3; // T: four threads per row, 256 tile rows in 256 / (kWaves 16) passes
         for (int r0 = 0; r0 < Rpad; r0 += 32) {
 #pragma unroll
-            for (int j = 0; j < 256 / (16 * kWaves); ++j) {
+            for (int j = 0; j < kDM / (16 * kWaves); ++j) {
                 const int row = trow + 16 * kWaves * j;
                 const int64_t m = (m0 + row < M) ? m0 + row : M - 1;
                 *reinterpret_cast<uint4*>(&Xs[0][row * kDK + dswz(row, tseg)]) =
                     *reinterpret_cast<const uint4*>(t + m * Rpad + r0 + 8 * tseg);
             }
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int rg = r0 + 4 * i + rr4;
+            for (int i = 0; i < 32 / kRowsAtOnce; ++i) {
+                const int rr = kRowsAtOnce * i + rr4;      // rank row of the k-step: segment rr / 8, element rr % 8
+                const int rg = r0 + rr;
                 const uint16_t v = b_cat[(int64_t)(rg < R ? rg : R - 1) * N + bn];
-                Ws[0][bcol * kDK + dswz(bcol, i >> 1) + 4 * (i & 1) + rr4] = rg < R ? v : (uint16_t)0;
+                Ws[0][bcol * kDK + dswz(bcol, rr >> 3) + (rr & 7)] = rg < R ? v : (uint16_t)0;
             }
             __syncthreads();
             mfma_step(Xs[0], Ws[0], 2);
@@ -160,18 +184,17 @@ __global__ __launch_bounds__(256 * kWN, 4) void dense_gemm_kernel(
     }
 
     // ---- store: accumulator register e of a 32x32 tile holds row 8*(e/4) + 4*(lane/32) + e%4, column lane%32
-    auto store_tile = [&](const f32x16& a, int i, int j) {
-        const int64_t n = n0 + wn * 64 + 32 * j + (lane & 31);
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const int64_t m = m0 + wm * 64 + 32 * i + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-            if (m < M && n < N) y[m * N + n] = f32_to_bf16_rne(a[e]);
+    for (int i = 0; i < kMI; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int64_t n = n0 + wn * 64 + 32 * j + (lane & 31);
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int64_t m = m0 + wm * 32 * kMI + 32 * i + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+                if (m < M && n < N) y[m * N + n] = f32_to_bf16_rne(acc[i][j][e]);
+            }
         }
-    };
-    store_tile(acc00, 0, 0);
-    store_tile(acc01, 0, 1);
-    store_tile(acc10, 1, 0);
-    store_tile(acc11, 1, 1);
 }
 
 hipError_t launch_linear_twostage(const LinearArgs& a, hipStream_t stream, const TimingEvents& ev) {
@@ -188,10 +211,10 @@ hipError_t launch_linear_twostage(const LinearArgs& a, hipStream_t stream, const
     const int n_groups = (n_tiles + kDXcds - 1) / kDXcds;
     const unsigned grid = (unsigned)(n_groups * m_tiles * kDXcds);
     if (wide)
-        SALR_LAUNCH((dense_gemm_kernel<4, 2>), dim3(grid), dim3(1024), stream, ev, a.x, a.M, a.K, a.N, (const uint16_t*)wd,
+        SALR_LAUNCH((dense_gemm_kernel<4, 4, 2>), dim3(grid), dim3(512), stream, ev, a.x, a.M, a.K, a.N, (const uint16_t*)wd,
                     (const uint16_t*)a.t, a.b_cat, R, Rpad, a.y, m_tiles, n_tiles);
     else
-        SALR_LAUNCH((dense_gemm_kernel<2, 3>), dim3(grid), dim3(512), stream, ev, a.x, a.M, a.K, a.N, (const uint16_t*)wd,
+        SALR_LAUNCH((dense_gemm_kernel<2, 2, 3>), dim3(grid), dim3(512), stream, ev, a.x, a.M, a.K, a.N, (const uint16_t*)wd,
                     (const uint16_t*)a.t, a.b_cat, R, Rpad, a.y, m_tiles, n_tiles);
     return hipGetLastError();
 }
