@@ -74,13 +74,29 @@ inline size_t adapter_at_bytes(int64_t K, int64_t R) {
 }
 inline size_t twostage_dense_offset(int64_t M, int64_t K, int64_t R) { return adapter_t_bytes(M, R) + adapter_at_bytes(K, R); }
 
+// Split of K over workgroups in the dense stage of the two-stage path: used when the 256 x 128 output tiles are
+// too few for the 256 CUs.  Needs N % 4 == 0 (vector stores of the reducing pass) and an even split of the 64-wide
+// k-steps; the fp32 partial tiles [ksplit, M, N] follow the dense weight in the workspace.
+inline int dense_ksplit(int64_t M, int64_t K, int64_t N) {
+    const int64_t tiles = ((M + 255) / 256) * ((N + 127) / 128);
+    const int64_t steps = K / 64;
+    if (tiles >= 128 || N % 4 != 0) return 1;
+    int s = 1;
+    while (s < 8 && tiles * s * 2 <= 256 && steps % (s * 2) == 0 && steps / (s * 2) >= 4) s *= 2;
+    return s;
+}
+
 // Workspace the linear needs: the small-batch path keeps fp32 split-K partials of T; the others see above.
 inline size_t linear_workspace_bytes(int64_t M, int64_t K, int64_t N, int64_t R) {
     if (M <= 0 || N <= 0) return 0;
     if (M <= kStreamMaxM)
         return R > 0 ? round_up_256((size_t)kStreamTSlices * (size_t)M * (size_t)adapter_rank_padded(R) * sizeof(float)) : 0;
     size_t b = twostage_dense_offset(M, K, R);
-    if (uses_twostage(M, K)) b += round_up_256((size_t)N * (size_t)K * sizeof(uint16_t));
+    if (uses_twostage(M, K)) {
+        b += round_up_256((size_t)N * (size_t)K * sizeof(uint16_t));
+        const int ks = dense_ksplit(M, K, N);
+        if (ks > 1) b += round_up_256((size_t)ks * (size_t)M * (size_t)N * sizeof(float));
+    }
     return b;
 }
 

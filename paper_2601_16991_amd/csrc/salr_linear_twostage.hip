@@ -34,7 +34,7 @@ template <int kMI, int kWN, int kStages>
 __global__ __launch_bounds__(64 * (8 / kMI) * kWN, (8 / kMI) * kWN / 4) void dense_gemm_kernel(
     const uint16_t* __restrict__ x, int64_t M, int64_t K, int64_t N, const uint16_t* __restrict__ wd,
     const uint16_t* __restrict__ t, const uint16_t* __restrict__ b_cat, int R, int Rpad, uint16_t* __restrict__ y,
-    int m_tiles, int n_tiles) {
+    int m_tiles, int n_tiles, int ksplit, float* __restrict__ partial) {
     constexpr int kDN = 64 * kWN;
     constexpr int kWaves = (8 / kMI) * kWN;
     constexpr int kXLoads = kDM / (8 * kWaves);   // load instructions per wave and step for the X tile (8 rows each)
@@ -57,6 +57,12 @@ __global__ __launch_bounds__(64 * (8 / kMI) * kWN, (8 / kMI) * kWN / 4) void den
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / kWN, wn = wave % kWN;
 
+    // split K: workgroup z = blockIdx.y multiplies k-steps [z, z + 1) * steps of its tile and leaves an fp32
+    // partial tile in partial[z]; dense_splitk_reduce_kernel adds them up.  The adapters ride with z = 0.
+    const int kz = blockIdx.y;
+    const int64_t steps = K / kDK / ksplit;
+    const int64_t k_first = kz * steps * kDK;
+
     // loader role: load j of wave w fills tile rows 8 (w + kWaves j) .. + 7; lane l lands on slot l % 8 of row l / 8
     const int lrow = 8 * wave + (lane >> 3);          // row of load 0; load j is 8 kWaves j rows further down
     const int lseg = (lane & 7) ^ ((lrow >> 1) & 7);  // logical segment stored in the lane's slot (same for all j)
@@ -65,14 +71,13 @@ __global__ __launch_bounds__(64 * (8 / kMI) * kWN, (8 / kMI) * kWN / 4) void den
 #pragma unroll
     for (int j = 0; j < kXLoads; ++j) {
         const int64_t row = m0 + lrow + 8 * kWaves * j;
-        xptr[j] = x + (row < M ? row : M - 1) * K + 8 * lseg;  // rows past the edge repeat the last row; never stored
+        xptr[j] = x + (row < M ? row : M - 1) * K + k_first + 8 * lseg;  // rows past the edge repeat the last row; never stored
     }
 #pragma unroll
     for (int j = 0; j < kWLoads; ++j) {
         const int64_t row = n0 + lrow + 8 * kWaves * j;
-        wptr[j] = wd + (row < N ? row : N - 1) * K + 8 * lseg;
+        wptr[j] = wd + (row < N ? row : N - 1) * K + k_first + 8 * lseg;
     }
-    const int64_t steps = K / kDK;
 
     // One 16-byte-per-lane load from memory straight into LDS: lane l of the wave lands on lds_base + 16 l.
     // Written as assembly so that the waits stay under this kernel's control (vmcnt below): handed to the
@@ -156,7 +161,7 @@ __global__ __launch_bounds__(64 * (8 / kMI) * kWN, (8 / kMI) * kWN / 4) void den
 
     // ---- adapter k-steps of 32 (Sec. 3.2): Xs[0] := T[m, r0 .. r0+31], Ws[0] := B_cat[r0 .. r0+31, n] (transposed),
     // both in segments 0..3 of the rows
-    if (R > 0) {
+    if (R > 0 && kz == 0) {
         constexpr int kRowsAtOnce = 64 * kWaves / kDN;   // rank rows of the k-step written per pass (2 or 4)
         const int bcol = tid % kDN;                // tile row of Ws[0] = output column
         const int64_t bn = (n0 + bcol < N) ? n0 + bcol : N - 1;
@@ -192,9 +197,28 @@ __global__ __launch_bounds__(64 * (8 / kMI) * kWN, (8 / kMI) * kWN / 4) void den
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const int64_t m = m0 + wm * 32 * kMI + 32 * i + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-                if (m < M && n < N) y[m * N + n] = f32_to_bf16_rne(acc[i][j][e]);
+                if (m < M && n < N) {
+                    if (ksplit == 1) y[m * N + n] = f32_to_bf16_rne(acc[i][j][e]);
+                    else partial[((int64_t)kz * M + m) * N + n] = acc[i][j][e];
+                }
             }
         }
+}
+
+// y = bf16(sum over z of partial[z]), four columns per thread (N % 4 == 0 on this path).
+__global__ __launch_bounds__(256) void dense_splitk_reduce_kernel(const float* __restrict__ partial, int64_t MN, int ksplit,
+                                                                  uint16_t* __restrict__ y) {
+    const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (i >= MN) return;
+    float4 s = *reinterpret_cast<const float4*>(partial + i);
+    for (int z = 1; z < ksplit; ++z) {
+        const float4 p = *reinterpret_cast<const float4*>(partial + (int64_t)z * MN + i);
+        s.x += p.x; s.y += p.y; s.z += p.z; s.w += p.w;
+    }
+    uint2 o;
+    o.x = (uint32_t)f32_to_bf16_rne(s.x) | ((uint32_t)f32_to_bf16_rne(s.y) << 16);
+    o.y = (uint32_t)f32_to_bf16_rne(s.z) | ((uint32_t)f32_to_bf16_rne(s.w) << 16);
+    *reinterpret_cast<uint2*>(y + i) = o;
 }
 
 hipError_t launch_linear_twostage(const LinearArgs& a, hipStream_t stream, const TimingEvents& ev) {
@@ -209,13 +233,20 @@ hipError_t launch_linear_twostage(const LinearArgs& a, hipStream_t stream, const
     const int tn = wide ? 256 : 128;
     const int n_tiles = (int)((a.N + tn - 1) / tn);
     const int n_groups = (n_tiles + kDXcds - 1) / kDXcds;
-    const unsigned grid = (unsigned)(n_groups * m_tiles * kDXcds);
+    const int ksplit = dense_ksplit(a.M, a.K, a.N);
+    float* partial = reinterpret_cast<float*>(reinterpret_cast<char*>(wd) + round_up_256((size_t)a.N * (size_t)a.K * sizeof(uint16_t)));
+    const dim3 grid((unsigned)(n_groups * m_tiles * kDXcds), (unsigned)ksplit);
     if (wide)
-        SALR_LAUNCH((dense_gemm_kernel<4, 4, 2>), dim3(grid), dim3(512), stream, ev, a.x, a.M, a.K, a.N, (const uint16_t*)wd,
-                    (const uint16_t*)a.t, a.b_cat, R, Rpad, a.y, m_tiles, n_tiles);
+        SALR_LAUNCH((dense_gemm_kernel<4, 4, 2>), grid, dim3(512), stream, ev, a.x, a.M, a.K, a.N, (const uint16_t*)wd,
+                    (const uint16_t*)a.t, a.b_cat, R, Rpad, a.y, m_tiles, n_tiles, ksplit, partial);
     else
-        SALR_LAUNCH((dense_gemm_kernel<2, 2, 3>), dim3(grid), dim3(512), stream, ev, a.x, a.M, a.K, a.N, (const uint16_t*)wd,
-                    (const uint16_t*)a.t, a.b_cat, R, Rpad, a.y, m_tiles, n_tiles);
+        SALR_LAUNCH((dense_gemm_kernel<2, 2, 3>), grid, dim3(512), stream, ev, a.x, a.M, a.K, a.N, (const uint16_t*)wd,
+                    (const uint16_t*)a.t, a.b_cat, R, Rpad, a.y, m_tiles, n_tiles, ksplit, partial);
+    if (ksplit > 1) {
+        const int64_t MN = a.M * a.N;
+        hipLaunchKernelGGL(dense_splitk_reduce_kernel, dim3((unsigned)((MN / 4 + 255) / 256)), dim3(256), 0, stream,
+                           (const float*)partial, MN, ksplit, a.y);
+    }
     return hipGetLastError();
 }
 

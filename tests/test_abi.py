@@ -66,7 +66,10 @@ def test_workspace_bytes(lib):
     assert lib.salr_linear_workspace_bytes(128, 4096, 4096, 0) == 0
     assert lib.salr_linear_workspace_bytes(255, 4096, 4096, 0) == 0
     # M >= 256 and K % 64 == 0: additionally the decoded weight [N, K] in bf16
-    assert lib.salr_linear_workspace_bytes(256, 4096, 4096, 0) == 4096 * 4096 * 2
+    assert lib.salr_linear_workspace_bytes(2048, 4096, 4096, 0) == 4096 * 4096 * 2
+    # ... and, when the output has fewer than 128 tiles of 256 x 128, fp32 partials of a K split over 2..8 workgroups
+    assert lib.salr_linear_workspace_bytes(256, 4096, 4096, 0) == 4096 * 4096 * 2 + 8 * 256 * 4096 * 4
+    assert lib.salr_linear_workspace_bytes(512, 14336, 4096, 0) == 4096 * 14336 * 2 + 4 * 512 * 4096 * 4
     assert lib.salr_linear_workspace_bytes(2048, 4096, 14336, 32) == 2048 * 32 * 2 + 32 * 4096 * 2 + 14336 * 4096 * 2
     assert lib.salr_linear_workspace_bytes(1024, 64, 8, 0) == 8 * 64 * 2
     assert lib.salr_linear_workspace_bytes(1024, 96, 8, 32) == 1024 * 32 * 2 + 32 * 96 * 2   # K % 64 != 0: no dense scratch

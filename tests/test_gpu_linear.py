@@ -65,6 +65,8 @@ def test_tiny_config():
     (300, 512, 300, (16, 16)), (257, 128, 513, (7,)), (600, 192, 260, (16,)), (256, 64, 129, (3,)),
     (1030, 64, 100, ()), (1100, 128, 257, (16, 16)), (1025, 192, 140, (33,)), (1024, 320, 130, (5,)),
     (1024, 32, 130, (5,)), (1100, 96, 70, (16,)),
+    # few output tiles and a long K: the dense stage splits K over 2, 4 or 8 workgroups per tile (fp32 partials)
+    (300, 1024, 260, (16,)), (256, 2048, 128, (8, 8)), (512, 512, 100, ()), (257, 4096, 36, (3,)),
     # M in 17..64: the streaming path with 2 and 4 m-tiles
     (33, 640, 50, (8,)), (48, 4096, 32, (16, 16)), (64, 96, 17, ()),
     # more than 512 row groups: the streaming variant that shares a CU between two workgroups
