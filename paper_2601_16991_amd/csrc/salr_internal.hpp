@@ -64,15 +64,31 @@ inline bool uses_twostage(int64_t M, int64_t K) { return M >= kTwoStageMinM && K
 
 inline size_t round_up_256(size_t b) { return (b + 255) / 256 * 256; }
 
-// Workspace layout of the large-batch paths (M > kStreamMaxM): T [M, Rpad] bf16, then the transposed padded
-// adapter a_t [Rpad, K] bf16, then (two-stage path only) the decoded weight [N, K] bf16; each 256-byte aligned.
+// Workspace layout of the large-batch paths (M > kStreamMaxM): T [M, Rpad] bf16, the transposed padded adapter
+// a_t [Rpad, K] bf16, the split-K partials of T, then (two-stage path only) the decoded weight [N, K] bf16 and the
+// split-K partials of Y; each 256-byte aligned.
 inline size_t adapter_t_bytes(int64_t M, int64_t R) {
     return R > 0 ? round_up_256((size_t)M * (size_t)adapter_rank_padded(R) * sizeof(uint16_t)) : 0;
 }
 inline size_t adapter_at_bytes(int64_t K, int64_t R) {
     return R > 0 ? round_up_256((size_t)K * (size_t)adapter_rank_padded(R) * sizeof(uint16_t)) : 0;
 }
-inline size_t twostage_dense_offset(int64_t M, int64_t K, int64_t R) { return adapter_t_bytes(M, R) + adapter_at_bytes(K, R); }
+// T = X * A_cat splits K over workgroups (fp32 partials [ksplit, M, Rpad], added up in a fixed order).
+inline int adapter_rows_per_block(int64_t M) { return M >= 4096 ? 256 : 64; }
+inline int adapter_ksplit(int64_t M, int64_t K) {
+    const int64_t rows = adapter_rows_per_block(M);
+    const int64_t blocks = (M + rows - 1) / rows, units = K / 32;
+    int s = 1;
+    while (s < 64 && blocks * s * 2 <= 1024 && units / (s * 2) >= 8) s *= 2;
+    return s;
+}
+inline size_t adapter_partial_bytes(int64_t M, int64_t K, int64_t R) {
+    const int s = adapter_ksplit(M, K);
+    return (R > 0 && s > 1) ? round_up_256((size_t)s * (size_t)M * (size_t)adapter_rank_padded(R) * sizeof(float)) : 0;
+}
+inline size_t twostage_dense_offset(int64_t M, int64_t K, int64_t R) {
+    return adapter_t_bytes(M, R) + adapter_at_bytes(K, R) + adapter_partial_bytes(M, K, R);
+}
 
 // Split of K over workgroups in the dense stage of the two-stage path: used when the 256 x 128 output tiles are
 // too few for the 256 CUs.  Needs N % 4 == 0 (vector stores of the reducing pass) and an even split of the 64-wide
@@ -106,5 +122,7 @@ hipError_t launch_linear_tiled(const LinearArgs& args, hipStream_t stream, const
 hipError_t launch_linear_twostage(const LinearArgs& args, hipStream_t stream, const TimingEvents& ev);
 // T = X * A_cat in bf16 [M, Rpad] at the start of the workspace (every path with M > kStreamMaxM)
 void launch_adapter_t(const LinearArgs& args, hipStream_t stream);
+// out[i] = bf16(sum over z < ksplit of partial[z * count + i]); count % 4 == 0
+void launch_splitk_reduce(const float* partial, int64_t count, int ksplit, uint16_t* out, hipStream_t stream);
 
 }  // namespace salr

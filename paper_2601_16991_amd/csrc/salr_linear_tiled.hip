@@ -239,25 +239,34 @@ __global__ __launch_bounds__(kTiledThreads, 4) void linear_tiled_kernel(
 // ---------------------------------------------------------------------------------------------------
 // T = X * A_cat for the large-batch paths (Sec. 3.2, first concatenated GEMM), bf16 output [M, Rpad].
 // A_cat arrives transposed and zero padded, a_t [Rpad, K] (written by the transposing pre-pass), so that
-// both MFMA operands are plain 16-byte loads along k.  Workgroup = 16 kMB rows of X, 8 waves that split K;
-// kRT rank tiles of 16 columns per pass over K (all of them in one pass up to rank 64); 16x16x32 bf16 MFMAs,
-// LDS reduction over the waves, padding columns come out as exact zeros.
+// both MFMA operands are plain 16-byte loads along k.  The product is a stream over X (it is read once, nothing
+// else is large), so the grid is made wide: workgroup (b, z) = 64 kMB rows of X times slice z of K, wave w owns
+// 16 kMB of the rows (each a_t operand it loads is used for kMB row blocks: at kMB = 1 the a_t requests are kRT
+// times the X requests and their L2 traffic, not X, sets the pace), the four waves walk the slice in step.
+// kRT rank tiles of 16 columns per pass over the slice (all of them in one pass up to rank 64); 16x16x32 bf16
+// MFMAs; with more than one slice the fp32 partial results go to partial[z] and splitk_reduce_kernel adds
+// them in a fixed order.  Padding columns come out as exact zeros.
 // ---------------------------------------------------------------------------------------------------
-template <int kMB, int kRT, int kTWaves, int kDepth>
-__global__ __launch_bounds__(kTWaves * 64) void adapter_t_kernel(const uint16_t* __restrict__ x, int64_t M, int64_t K,
-                                                                  const uint16_t* __restrict__ a_t, int Rpad,
-                                                                  uint16_t* __restrict__ t) {
-    __shared__ float red[kTWaves][kMB * kRT][4][64];
+template <int kMB, int kRT, int kDepth>
+__global__ __launch_bounds__(256) void adapter_t_kernel(const uint16_t* __restrict__ x, int64_t M, int64_t K,
+                                                        const uint16_t* __restrict__ a_t, int Rpad, int ksplit,
+                                                        uint16_t* __restrict__ t, float* __restrict__ partial) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int i16 = lane & 15, g = lane >> 4;
-    const int64_t m0 = (int64_t)blockIdx.x * 16 * kMB;
+    const int64_t m0 = ((int64_t)blockIdx.x * 4 + wave) * 16 * kMB;
+    if (m0 >= M) return;   // wave-uniform; the kernel has no barrier
+    const int z = blockIdx.y;
     const int64_t units = K >> 5;
+    const int64_t per_slice = (units + ksplit - 1) / ksplit;
+    const int64_t u_begin = z * per_slice < units ? z * per_slice : units;
+    const int64_t u_end = (z + 1) * per_slice < units ? (z + 1) * per_slice : units;
+    const int64_t len = u_end - u_begin;
     const uint16_t* xrow[kMB];
 #pragma unroll
-    for (int mt = 0; mt < kMB; ++mt) {
-        const int64_t m = m0 + 16 * mt + i16;
-        xrow[mt] = x + (m < M ? m : M - 1) * K + 8 * g;
+    for (int mb = 0; mb < kMB; ++mb) {
+        const int64_t mrow = m0 + 16 * mb + i16;
+        xrow[mb] = x + (mrow < M ? mrow : M - 1) * K + 8 * g;
     }
     for (int rb = 0; rb < Rpad; rb += 16 * kRT) {
         // Rpad is a multiple of 32 and kRT of 2, so a pass never starts past the end; tiles past it are clamped
@@ -269,15 +278,10 @@ __global__ __launch_bounds__(kTWaves * 64) void adapter_t_kernel(const uint16_t*
         }
         f32x4 acc[kMB][kRT];
 #pragma unroll
-        for (int mt = 0; mt < kMB; ++mt)
+        for (int mb = 0; mb < kMB; ++mb)
 #pragma unroll
-            for (int rt = 0; rt < kRT; ++rt) acc[mt][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int rt = 0; rt < kRT; ++rt) acc[mb][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
         // kDepth k-steps per trip with every load issued before the first MFMA: the kernel lives on loads in flight
-        // each wave walks its own contiguous share of K, so that successive loads of a row are adjacent in memory
-        const int64_t per_wave = (units + kTWaves - 1) / kTWaves;
-        const int64_t u_begin = wave * per_wave < units ? wave * per_wave : units;
-        const int64_t u_end = (wave + 1) * per_wave < units ? (wave + 1) * per_wave : units;
-        const int64_t len = u_end - u_begin;
         for (int64_t i0 = 0; i0 < len; i0 += kDepth) {
             uint4 aq[kDepth][kMB], bq[kDepth][kRT];
 #pragma unroll
@@ -285,7 +289,7 @@ __global__ __launch_bounds__(kTWaves * 64) void adapter_t_kernel(const uint16_t*
                 const int64_t i = i0 + d < len ? i0 + d : len - 1;   // past the end: reload the last step, not used
                 const int64_t k0 = (u_begin + i) << 5;
 #pragma unroll
-                for (int mt = 0; mt < kMB; ++mt) aq[d][mt] = *reinterpret_cast<const uint4*>(xrow[mt] + k0);
+                for (int mb = 0; mb < kMB; ++mb) aq[d][mb] = *reinterpret_cast<const uint4*>(xrow[mb] + k0);
 #pragma unroll
                 for (int rt = 0; rt < kRT; ++rt) bq[d][rt] = *reinterpret_cast<const uint4*>(arow[rt] + k0);
             }
@@ -293,33 +297,51 @@ __global__ __launch_bounds__(kTWaves * 64) void adapter_t_kernel(const uint16_t*
             for (int d = 0; d < kDepth; ++d) {
                 if (i0 + d < len) {   // wave-uniform
 #pragma unroll
-                    for (int mt = 0; mt < kMB; ++mt)
+                    for (int mb = 0; mb < kMB; ++mb)
 #pragma unroll
                         for (int rt = 0; rt < kRT; ++rt)
-                            acc[mt][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(aq[d][mt]), as_bf16x8(bq[d][rt]),
-                                                                                  acc[mt][rt], 0, 0, 0);
+                            acc[mb][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(aq[d][mb]), as_bf16x8(bq[d][rt]),
+                                                                                  acc[mb][rt], 0, 0, 0);
                 }
             }
         }
-#pragma unroll
-        for (int mt = 0; mt < kMB; ++mt)
-#pragma unroll
-            for (int rt = 0; rt < kRT; ++rt)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) red[wave][mt * kRT + rt][e][lane] = acc[mt][rt][e];
-        __syncthreads();
         // accumulator layout of the 16x16 MFMA: lane holds column lane % 16, rows 4 (lane / 16) + e
-        for (int idx = threadIdx.x; idx < kMB * kRT * 256; idx += kTWaves * 64) {
-            const int l = idx & 63, e = (idx >> 6) & 3, tile = idx >> 8;
-            float sum = 0.f;
 #pragma unroll
-            for (int w = 0; w < kTWaves; ++w) sum += red[w][tile][e][l];
-            const int64_t m = m0 + 16 * (tile / kRT) + 4 * (l >> 4) + e;
-            const int r = rb + 16 * (tile % kRT) + (l & 15);
-            if (m < M && r < Rpad) t[m * Rpad + r] = f32_to_bf16_rne(sum);
-        }
-        __syncthreads();
+        for (int mb = 0; mb < kMB; ++mb)
+#pragma unroll
+            for (int rt = 0; rt < kRT; ++rt) {
+                const int r = rb + 16 * rt + i16;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int64_t m = m0 + 16 * mb + 4 * g + e;
+                    if (m < M && r < Rpad) {
+                        if (ksplit == 1) t[m * Rpad + r] = f32_to_bf16_rne(acc[mb][rt][e]);
+                        else partial[((int64_t)z * M + m) * Rpad + r] = acc[mb][rt][e];
+                    }
+                }
+            }
     }
+}
+
+// out = bf16(sum over z of partial[z]), four elements per thread (count % 4 == 0), z in ascending order.
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ partial, int64_t count, int ksplit,
+                                                            uint16_t* __restrict__ out) {
+    const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (i >= count) return;
+    float4 s = *reinterpret_cast<const float4*>(partial + i);
+    for (int z = 1; z < ksplit; ++z) {
+        const float4 p = *reinterpret_cast<const float4*>(partial + (int64_t)z * count + i);
+        s.x += p.x; s.y += p.y; s.z += p.z; s.w += p.w;
+    }
+    uint2 o;
+    o.x = (uint32_t)f32_to_bf16_rne(s.x) | ((uint32_t)f32_to_bf16_rne(s.y) << 16);
+    o.y = (uint32_t)f32_to_bf16_rne(s.z) | ((uint32_t)f32_to_bf16_rne(s.w) << 16);
+    *reinterpret_cast<uint2*>(out + i) = o;
+}
+
+void launch_splitk_reduce(const float* partial, int64_t count, int ksplit, uint16_t* out, hipStream_t stream) {
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((count / 4 + 255) / 256)), dim3(256), 0, stream, partial, count,
+                       ksplit, out);
 }
 
 // a_t[r][k] = A_cat[k][r] for r < R, 0 for R <= r < Rpad: one thread per k and block of 8 ranks.
@@ -337,18 +359,25 @@ __global__ __launch_bounds__(256) void adapter_transpose_kernel(const uint16_t* 
 
 void launch_adapter_t(const LinearArgs& a, hipStream_t stream) {
     const int R = (int)a.R, Rpad = (int)adapter_rank_padded(a.R);
-    uint16_t* a_t = reinterpret_cast<uint16_t*>(reinterpret_cast<char*>(a.t) + adapter_t_bytes(a.M, a.R));
+    char* base = reinterpret_cast<char*>(a.t);
+    uint16_t* a_t = reinterpret_cast<uint16_t*>(base + adapter_t_bytes(a.M, a.R));
+    float* partial = reinterpret_cast<float*>(base + adapter_t_bytes(a.M, a.R) + adapter_at_bytes(a.K, a.R));
     hipLaunchKernelGGL(adapter_transpose_kernel, dim3((unsigned)((a.K + 255) / 256), Rpad / 8), dim3(256), 0, stream, a.a_cat,
                        a.K, R, Rpad, a_t);
-    // Every workgroup reads all of a_t, so rows per workgroup trade that traffic against the number of workgroups.
-    const bool four = Rpad % 64 == 0;          // rank tiles per pass over K
-    const bool wide = a.M >= 65536;            // 32 rows and 16 waves per workgroup
-    const unsigned g16 = (unsigned)((a.M + 15) / 16), g32 = (unsigned)((a.M + 31) / 32);
+    const int ksplit = adapter_ksplit(a.M, a.K);
+    const int rows = adapter_rows_per_block(a.M);
+    const dim3 grid((unsigned)((a.M + rows - 1) / rows), (unsigned)ksplit);
     const uint16_t* at = a_t;
-    if (wide && four) hipLaunchKernelGGL((adapter_t_kernel<2, 4, 16, 2>), dim3(g32), dim3(1024), 0, stream, a.x, a.M, a.K, at, Rpad, a.t);
-    else if (wide) hipLaunchKernelGGL((adapter_t_kernel<2, 2, 16, 4>), dim3(g32), dim3(1024), 0, stream, a.x, a.M, a.K, at, Rpad, a.t);
-    else if (four) hipLaunchKernelGGL((adapter_t_kernel<1, 4, 8, 4>), dim3(g16), dim3(512), 0, stream, a.x, a.M, a.K, at, Rpad, a.t);
-    else hipLaunchKernelGGL((adapter_t_kernel<1, 2, 8, 4>), dim3(g16), dim3(512), 0, stream, a.x, a.M, a.K, at, Rpad, a.t);
+    const bool four = Rpad % 64 == 0;   // rank tiles per pass over the slice
+    if (rows == 256 && four)
+        hipLaunchKernelGGL((adapter_t_kernel<4, 4, 2>), grid, dim3(256), 0, stream, a.x, a.M, a.K, at, Rpad, ksplit, a.t, partial);
+    else if (rows == 256)
+        hipLaunchKernelGGL((adapter_t_kernel<4, 2, 2>), grid, dim3(256), 0, stream, a.x, a.M, a.K, at, Rpad, ksplit, a.t, partial);
+    else if (four)
+        hipLaunchKernelGGL((adapter_t_kernel<1, 4, 4>), grid, dim3(256), 0, stream, a.x, a.M, a.K, at, Rpad, ksplit, a.t, partial);
+    else
+        hipLaunchKernelGGL((adapter_t_kernel<1, 2, 4>), grid, dim3(256), 0, stream, a.x, a.M, a.K, at, Rpad, ksplit, a.t, partial);
+    if (ksplit > 1) launch_splitk_reduce(partial, a.M * Rpad, ksplit, a.t, stream);
 }
 
 hipError_t launch_linear_tiled(const LinearArgs& a, hipStream_t stream, const TimingEvents& ev) {

@@ -58,7 +58,7 @@ __global__ __launch_bounds__(64 * (8 / kMI) * kWN, (8 / kMI) * kWN / 4) void den
     const int wm = wave / kWN, wn = wave % kWN;
 
     // split K: workgroup z = blockIdx.y multiplies k-steps [z, z + 1) * steps of its tile and leaves an fp32
-    // partial tile in partial[z]; dense_splitk_reduce_kernel adds them up.  The adapters ride with z = 0.
+    // partial tile in partial[z]; splitk_reduce_kernel adds them up.  The adapters ride with z = 0.
     const int kz = blockIdx.y;
     const int64_t steps = K / kDK / ksplit;
     const int64_t k_first = kz * steps * kDK;
@@ -205,22 +205,6 @@ __global__ __launch_bounds__(64 * (8 / kMI) * kWN, (8 / kMI) * kWN / 4) void den
         }
 }
 
-// y = bf16(sum over z of partial[z]), four columns per thread (N % 4 == 0 on this path).
-__global__ __launch_bounds__(256) void dense_splitk_reduce_kernel(const float* __restrict__ partial, int64_t MN, int ksplit,
-                                                                  uint16_t* __restrict__ y) {
-    const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
-    if (i >= MN) return;
-    float4 s = *reinterpret_cast<const float4*>(partial + i);
-    for (int z = 1; z < ksplit; ++z) {
-        const float4 p = *reinterpret_cast<const float4*>(partial + (int64_t)z * MN + i);
-        s.x += p.x; s.y += p.y; s.z += p.z; s.w += p.w;
-    }
-    uint2 o;
-    o.x = (uint32_t)f32_to_bf16_rne(s.x) | ((uint32_t)f32_to_bf16_rne(s.y) << 16);
-    o.y = (uint32_t)f32_to_bf16_rne(s.z) | ((uint32_t)f32_to_bf16_rne(s.w) << 16);
-    *reinterpret_cast<uint2*>(y + i) = o;
-}
-
 hipError_t launch_linear_twostage(const LinearArgs& a, hipStream_t stream, const TimingEvents& ev) {
     const int R = (int)a.R, Rpad = (int)adapter_rank_padded(a.R);
     uint16_t* wd = reinterpret_cast<uint16_t*>(reinterpret_cast<char*>(a.t) + twostage_dense_offset(a.M, a.K, a.R));
@@ -243,9 +227,7 @@ hipError_t launch_linear_twostage(const LinearArgs& a, hipStream_t stream, const
         SALR_LAUNCH((dense_gemm_kernel<2, 2, 3>), grid, dim3(512), stream, ev, a.x, a.M, a.K, a.N, (const uint16_t*)wd,
                     (const uint16_t*)a.t, a.b_cat, R, Rpad, a.y, m_tiles, n_tiles, ksplit, partial);
     if (ksplit > 1) {
-        const int64_t MN = a.M * a.N;
-        hipLaunchKernelGGL(dense_splitk_reduce_kernel, dim3((unsigned)((MN / 4 + 255) / 256)), dim3(256), 0, stream,
-                           (const float*)partial, MN, ksplit, a.y);
+        launch_splitk_reduce(partial, a.M * a.N, ksplit, a.y, stream);
     }
     return hipGetLastError();
 }

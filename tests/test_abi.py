@@ -53,27 +53,61 @@ def test_words_per_row(lib):
     assert lib.salr_bitmap_words_per_row(-1) == -1
 
 
+def _r256(b):
+    return (b + 255) // 256 * 256
+
+
+def _t_ksplit(M, K):
+    rows = 256 if M >= 4096 else 64
+    blocks, units, s = (M + rows - 1) // rows, K // 32, 1
+    while s < 64 and blocks * s * 2 <= 1024 and units // (s * 2) >= 8:
+        s *= 2
+    return s
+
+
+def _y_ksplit(M, K, N):
+    tiles, steps, s = ((M + 255) // 256) * ((N + 127) // 128), K // 64, 1
+    if tiles >= 128 or N % 4:
+        return 1
+    while s < 8 and tiles * s * 2 <= 256 and steps % (s * 2) == 0 and steps // (s * 2) >= 4:
+        s *= 2
+    return s
+
+
+def _expected_workspace(M, K, N, R):
+    """The documented layout, restated: M <= 64: sixteen fp32 split-K partials of T.  Larger M: T [M, Rpad] bf16,
+    transposed padded A_cat [Rpad, K] bf16, fp32 split-K partials of T; for M >= 256 and K % 64 == 0 also the decoded
+    weight [N, K] bf16 and, when the output has few tiles, fp32 split-K partials of Y.  Each part rounded to 256 B."""
+    rp = (R + 31) // 32 * 32
+    if M <= 64:
+        return _r256(16 * M * rp * 4) if R else 0
+    b = 0
+    if R:
+        b += _r256(M * rp * 2) + _r256(K * rp * 2)
+        ks = _t_ksplit(M, K)
+        if ks > 1:
+            b += _r256(ks * M * rp * 4)
+    if M >= 256 and K >= 64 and K % 64 == 0:
+        b += _r256(N * K * 2)
+        ks = _y_ksplit(M, K, N)
+        if ks > 1:
+            b += _r256(ks * M * N * 4)
+    return b
+
+
 def test_workspace_bytes(lib):
     assert lib.salr_linear_workspace_bytes(16, 4096, 4096, 0) == 0
     assert lib.salr_linear_workspace_bytes(0, 4096, 4096, 32) == 0
-    # M <= 64: sixteen split-K partials of T in fp32.  Rank padded to 32.
     assert lib.salr_linear_workspace_bytes(16, 4096, 4096, 32) == 16 * 16 * 32 * 4
-    assert lib.salr_linear_workspace_bytes(16, 4096, 4096, 16) == 16 * 16 * 32 * 4
     assert lib.salr_linear_workspace_bytes(1, 4096, 4096, 64) == 16 * 64 * 4
-    # larger M: T [M, Rpad] and the transposed padded A_cat [Rpad, K] in bf16, each rounded up to 256 B
-    assert lib.salr_linear_workspace_bytes(128, 4096, 4096, 32) == 128 * 32 * 2 + 32 * 4096 * 2
-    assert lib.salr_linear_workspace_bytes(65, 4096, 4096, 1) == 4352 + 32 * 4096 * 2   # 65*32*2 = 4160 -> 4352
     assert lib.salr_linear_workspace_bytes(128, 4096, 4096, 0) == 0
-    assert lib.salr_linear_workspace_bytes(255, 4096, 4096, 0) == 0
-    # M >= 256 and K % 64 == 0: additionally the decoded weight [N, K] in bf16
-    assert lib.salr_linear_workspace_bytes(2048, 4096, 4096, 0) == 4096 * 4096 * 2
-    # ... and, when the output has fewer than 128 tiles of 256 x 128, fp32 partials of a K split over 2..8 workgroups
-    assert lib.salr_linear_workspace_bytes(256, 4096, 4096, 0) == 4096 * 4096 * 2 + 8 * 256 * 4096 * 4
-    assert lib.salr_linear_workspace_bytes(512, 14336, 4096, 0) == 4096 * 14336 * 2 + 4 * 512 * 4096 * 4
-    assert lib.salr_linear_workspace_bytes(2048, 4096, 14336, 32) == 2048 * 32 * 2 + 32 * 4096 * 2 + 14336 * 4096 * 2
-    assert lib.salr_linear_workspace_bytes(1024, 64, 8, 0) == 8 * 64 * 2
-    assert lib.salr_linear_workspace_bytes(1024, 96, 8, 32) == 1024 * 32 * 2 + 32 * 96 * 2   # K % 64 != 0: no dense scratch
-    assert lib.salr_linear_workspace_bytes(16, 4096, 4096, 1000) == 0
+    assert lib.salr_linear_workspace_bytes(16, 4096, 4096, 1000) == 0          # rank not supported
+    assert lib.salr_linear_workspace_bytes(2048, 4096, 14336, 0) == 14336 * 4096 * 2
+    assert _t_ksplit(4096, 14336) == 32 and _t_ksplit(2048, 4096) == 16 and _y_ksplit(512, 14336, 4096) == 4
+    for (M, K, N, R) in [(16, 4096, 4096, 16), (65, 4096, 4096, 1), (128, 4096, 4096, 32), (255, 64, 8, 7),
+                         (256, 4096, 4096, 0), (256, 4096, 4096, 32), (512, 14336, 4096, 64), (2048, 4096, 14336, 32),
+                         (4096, 14336, 4096, 64), (1024, 96, 8, 32), (1024, 64, 8, 0), (300, 1024, 262, 5)]:
+        assert lib.salr_linear_workspace_bytes(M, K, N, R) == _expected_workspace(M, K, N, R), (M, K, N, R)
 
 
 def test_host_validation_rejects_before_launch(lib):
