@@ -26,21 +26,25 @@ constexpr int kDXcds = 8;
 // segment (16 bytes = 8 bf16) position of logical segment `seg` in LDS row `row`, in elements
 __device__ __forceinline__ int dswz(int row, int seg) { return (seg ^ ((row >> 1) & 7)) * 8; }
 
-// Output tile 256 x (64 kWN); wave (wm, wn) owns 32 kMI rows x 64 columns, so there are (8 / kMI) kWN waves:
-// kMI = 2: 64 x 64 wave tiles, 4 waves per SIMD at kWN = 4; kMI = 4: 128 x 64 wave tiles, 2 waves per SIMD with
-// room in the registers to fetch the operands of the next 16 k while the current ones are multiplied.
+// Output tile 256 x (32 kNI kWN); wave (wm, wn) owns 32 kMI rows x 32 kNI columns, so there are (8 / kMI) kWN
+// waves, always 8 here (2 per SIMD, which leaves room in the registers to fetch the operands of the next 16 k
+// while the current ones are multiplied):
+//   <4, 2, 4>  256 x 256 tile, 128 x 64 per wave;   <1, 7, 1>  256 x 224 tile, 32 x 224 per wave (for N where
+//   224-wide tiles fill whole rounds of the 256 CUs and 256-wide ones do not);   <2, 2, 2>  256 x 128 tile.
 // K % 64 == 0.
-template <int kMI, int kWN, int kStages>
+template <int kMI, int kNI, int kWN, int kStages>
 __global__ __launch_bounds__(64 * (8 / kMI) * kWN, (8 / kMI) * kWN / 4) void dense_gemm_kernel(
     const uint16_t* __restrict__ x, int64_t M, int64_t K, int64_t N, const uint16_t* __restrict__ wd,
     const uint16_t* __restrict__ t, const uint16_t* __restrict__ b_cat, int R, int Rpad, uint16_t* __restrict__ y,
     int m_tiles, int n_tiles, int ksplit, float* __restrict__ partial) {
-    constexpr int kDN = 64 * kWN;
+    constexpr int kDN = 32 * kNI * kWN;
     constexpr int kWaves = (8 / kMI) * kWN;
-    constexpr int kXLoads = kDM / (8 * kWaves);   // load instructions per wave and step for the X tile (8 rows each)
-    constexpr int kWLoads = kDN / (8 * kWaves);   // ... and for the W tile
+    constexpr int kXLoads = kDM / (8 * kWaves);                 // load instructions per wave and step for the X tile (8 rows each)
+    constexpr int kWLoads = (kDN + 8 * kWaves - 1) / (8 * kWaves);   // ... and for the W tile; the last one may be partial
+    constexpr bool kWRagged = kDN % (8 * kWaves) != 0;          // only the first waves take part in the last W load
     constexpr int kLoads = kXLoads + kWLoads;
-    static_assert(kDM % (8 * kWaves) == 0 && kDN % (8 * kWaves) == 0, "tile/wave shape");
+    static_assert(kDM % (8 * kWaves) == 0 && kDN % 8 == 0, "tile/wave shape");
+    static_assert(!kWRagged || kStages == 2, "a partial load makes the in-flight count differ between waves: wait for all");
     __shared__ __attribute__((aligned(16))) uint16_t Xs[kStages][kDM * kDK];
     __shared__ __attribute__((aligned(16))) uint16_t Ws[kStages][kDN * kDK];
 
@@ -95,42 +99,47 @@ __global__ __launch_bounds__(64 * (8 / kMI) * kWN, (8 / kMI) * kWN / 4) void den
 #pragma unroll
         for (int j = 0; j < kXLoads; ++j) load_to_lds(xptr[j] + sc * kDK, xs + (8 * wave + 8 * kWaves * j) * kDK);
 #pragma unroll
-        for (int j = 0; j < kWLoads; ++j) load_to_lds(wptr[j] + sc * kDK, ws + (8 * wave + 8 * kWaves * j) * kDK);
+        for (int j = 0; j < kWLoads; ++j) {
+            if (!kWRagged || j + 1 < kWLoads || 8 * (wave + kWaves * j) < kDN)   // wave-uniform
+                load_to_lds(wptr[j] + sc * kDK, ws + (8 * wave + 8 * kWaves * j) * kDK);
+        }
     };
     // the requests of the newest kStages - 2 steps may stay in flight, everything older has landed
     static_assert((kStages - 2) * kLoads <= 15, "vmcnt immediate");
     auto older_landed = [&]() { __builtin_amdgcn_s_waitcnt(0x0F70 | ((kStages - 2) * kLoads)); };
 
-    f32x16 acc[kMI][2];
+    f32x16 acc[kMI][kNI];
 #pragma unroll
-    for (int i = 0; i < kMI; ++i) acc[i][0] = acc[i][1] = f32x16{0};
+    for (int i = 0; i < kMI; ++i)
+#pragma unroll
+        for (int j = 0; j < kNI; ++j) acc[i][j] = f32x16{0};
     // operand lane: row lane % 32 of a 32-row block, segment 2 j + lane / 32 in sub-step j (16 of the 64 k);
     // rows 32 or 64 further down share the swizzle term
     const int frag_row = lane & 31;
     const int fsw = (frag_row >> 1) & 7, fhalf = lane >> 5;
     struct Frags {
-        bf16x8 a[kMI], b[2];
+        bf16x8 a[kMI], b[kNI];
     };
     auto load_frags = [&](const uint16_t* xa, const uint16_t* wb, int j) -> Frags {
         const int fk = ((2 * j + fhalf) ^ fsw) * 8;
         Frags f;
 #pragma unroll
         for (int i = 0; i < kMI; ++i) f.a[i] = *reinterpret_cast<const bf16x8*>(xa + 32 * i * kDK + fk);
-        f.b[0] = *reinterpret_cast<const bf16x8*>(wb + fk);
-        f.b[1] = *reinterpret_cast<const bf16x8*>(wb + 32 * kDK + fk);
+#pragma unroll
+        for (int j = 0; j < kNI; ++j) f.b[j] = *reinterpret_cast<const bf16x8*>(wb + 32 * j * kDK + fk);
         return f;
     };
     auto multiply = [&](const Frags& f) {
 #pragma unroll
-        for (int i = 0; i < kMI; ++i) {
-            acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[0], acc[i][0], 0, 0, 0);
-            acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[1], acc[i][1], 0, 0, 0);
-        }
+        for (int i = 0; i < kMI; ++i)
+#pragma unroll
+            for (int j = 0; j < kNI; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
     };
     // the operands of sub-step j + 1 are requested before the MFMAs of sub-step j issue
     auto mfma_step = [&](const uint16_t* xs, const uint16_t* ws, int substeps) {
         const uint16_t* xa = xs + (wm * 32 * kMI + frag_row) * kDK;
-        const uint16_t* wb = ws + (wn * 64 + frag_row) * kDK;
+        const uint16_t* wb = ws + (wn * 32 * kNI + frag_row) * kDK;
         Frags f0 = load_frags(xa, wb, 0);
         Frags f1 = load_frags(xa, wb, 1);
         multiply(f0);
@@ -162,10 +171,6 @@ __global__ __launch_bounds__(64 * (8 / kMI) * kWN, (8 / kMI) * kWN / 4) void den
     // ---- adapter k-steps of 32 (Sec. 3.2): Xs[0] := T[m, r0 .. r0+31], Ws[0] := B_cat[r0 .. r0+31, n] (transposed),
     // both in segments 0..3 of the rows
     if (R > 0 && kz == 0) {
-        constexpr int kRowsAtOnce = 64 * kWaves / kDN;   // rank rows of the k-step written per pass (2 or 4)
-        const int bcol = tid % kDN;                // tile row of Ws[0] = output column
-        const int64_t bn = (n0 + bcol < N) ? n0 + bcol : N - 1;
-        const int rr4 = tid / kDN;                 // this thread's rank row inside a pass
         const int trow = tid >> 2, tseg = tid & 3; // T: four threads per row, 256 tile rows in 256 / (kWaves 16) passes
         for (int r0 = 0; r0 < Rpad; r0 += 32) {
 #pragma unroll
@@ -175,10 +180,11 @@ __global__ __launch_bounds__(64 * (8 / kMI) * kWN, (8 / kMI) * kWN / 4) void den
                 *reinterpret_cast<uint4*>(&Xs[0][row * kDK + dswz(row, tseg)]) =
                     *reinterpret_cast<const uint4*>(t + m * Rpad + r0 + 8 * tseg);
             }
-#pragma unroll
-            for (int i = 0; i < 32 / kRowsAtOnce; ++i) {
-                const int rr = kRowsAtOnce * i + rr4;      // rank row of the k-step: segment rr / 8, element rr % 8
+            // element (rank row rr, output column bcol) of the 32 x kDN block: consecutive threads take consecutive columns
+            for (int idx = tid; idx < 32 * kDN; idx += 64 * kWaves) {
+                const int rr = idx / kDN, bcol = idx % kDN;   // segment rr / 8, element rr % 8 of tile row bcol
                 const int rg = r0 + rr;
+                const int64_t bn = (n0 + bcol < N) ? n0 + bcol : N - 1;
                 const uint16_t v = b_cat[(int64_t)(rg < R ? rg : R - 1) * N + bn];
                 Ws[0][bcol * kDK + dswz(bcol, rr >> 3) + (rr & 7)] = rg < R ? v : (uint16_t)0;
             }
@@ -192,8 +198,8 @@ __global__ __launch_bounds__(64 * (8 / kMI) * kWN, (8 / kMI) * kWN / 4) void den
 #pragma unroll
     for (int i = 0; i < kMI; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int64_t n = n0 + wn * 64 + 32 * j + (lane & 31);
+        for (int j = 0; j < kNI; ++j) {
+            const int64_t n = n0 + wn * 32 * kNI + 32 * j + (lane & 31);
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const int64_t m = m0 + wm * 32 * kMI + 32 * i + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
@@ -212,20 +218,27 @@ hipError_t launch_linear_twostage(const LinearArgs& a, hipStream_t stream, const
     if (e != hipSuccess) return e;
     if (R > 0) launch_adapter_t(a, stream);
     const int m_tiles = (int)((a.M + kDM - 1) / kDM);
-    // 256 x 256 tiles when they fill the chip, else 256 x 128
-    const bool wide = (int64_t)m_tiles * ((a.N + 255) / 256) >= 224;
-    const int tn = wide ? 256 : 128;
+    // Tile width: 256 or 224 columns, whichever needs less time in whole rounds of the 256 CUs (one workgroup per
+    // CU, so a round costs its tile width); 128, with K split over workgroups if need be, when neither fills the chip.
+    const int64_t t256 = (int64_t)m_tiles * ((a.N + 255) / 256), t224 = (int64_t)m_tiles * ((a.N + 223) / 224);
+    const int64_t cost256 = (t256 + 255) / 256 * 256, cost224 = (t224 + 255) / 256 * 224;
+    const int tn = t256 < 224 ? 128 : (cost224 < cost256 ? 224 : 256);
     const int n_tiles = (int)((a.N + tn - 1) / tn);
     const int n_groups = (n_tiles + kDXcds - 1) / kDXcds;
-    const int ksplit = dense_ksplit(a.M, a.K, a.N);
+    const int ksplit = tn == 128 ? dense_ksplit(a.M, a.K, a.N) : 1;
     float* partial = reinterpret_cast<float*>(reinterpret_cast<char*>(wd) + round_up_256((size_t)a.N * (size_t)a.K * sizeof(uint16_t)));
     const dim3 grid((unsigned)(n_groups * m_tiles * kDXcds), (unsigned)ksplit);
-    if (wide)
-        SALR_LAUNCH((dense_gemm_kernel<4, 4, 2>), grid, dim3(512), stream, ev, a.x, a.M, a.K, a.N, (const uint16_t*)wd,
-                    (const uint16_t*)a.t, a.b_cat, R, Rpad, a.y, m_tiles, n_tiles, ksplit, partial);
+    const uint16_t* wdc = wd;
+    const uint16_t* tc = a.t;
+    if (tn == 256)
+        SALR_LAUNCH((dense_gemm_kernel<4, 2, 4, 2>), grid, dim3(512), stream, ev, a.x, a.M, a.K, a.N, wdc, tc, a.b_cat, R, Rpad,
+                    a.y, m_tiles, n_tiles, ksplit, partial);
+    else if (tn == 224)
+        SALR_LAUNCH((dense_gemm_kernel<1, 7, 1, 2>), grid, dim3(512), stream, ev, a.x, a.M, a.K, a.N, wdc, tc, a.b_cat, R, Rpad,
+                    a.y, m_tiles, n_tiles, ksplit, partial);
     else
-        SALR_LAUNCH((dense_gemm_kernel<2, 2, 3>), grid, dim3(512), stream, ev, a.x, a.M, a.K, a.N, (const uint16_t*)wd,
-                    (const uint16_t*)a.t, a.b_cat, R, Rpad, a.y, m_tiles, n_tiles, ksplit, partial);
+        SALR_LAUNCH((dense_gemm_kernel<2, 2, 2, 3>), grid, dim3(512), stream, ev, a.x, a.M, a.K, a.N, wdc, tc, a.b_cat, R, Rpad,
+                    a.y, m_tiles, n_tiles, ksplit, partial);
     if (ksplit > 1) {
         launch_splitk_reduce(partial, a.M * a.N, ksplit, a.y, stream);
     }

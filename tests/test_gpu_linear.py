@@ -77,6 +77,14 @@ def test_ragged_shapes(M, K, N, ranks):
     _assert_close(_run(x, w, a_cat, b_cat), oracle.linear(x, w, a_cat, b_cat), f"M{M} K{K} N{N} R{sum(ranks)}")
 
 
+@pytest.mark.parametrize("M,N", [(4096, 3584), (4090, 3580)])
+def test_many_tiles_224_wide(M, N):
+    """16 row blocks x 14 column blocks of 256 x 256 would leave the second round of the 256 CUs mostly empty;
+    the dense stage then takes 256 x 224 tiles (16 x 16 of them).  Short K keeps the oracle cheap."""
+    x, w, a_cat, b_cat = _problem(M, 128, N, (8, 8), 5 * M + N, std_ab=0.05)
+    _assert_close(_run(x, w, a_cat, b_cat), oracle.linear(x, w, a_cat, b_cat), f"M{M} N{N} 224-wide tiles")
+
+
 def test_adapter_term_alone():
     """What = 0 isolates (X A_cat) B_cat: the tolerance is then relative to the adapter term itself."""
     x, w, a_cat, b_cat = _problem(16, 512, 256, (16, 16), 5)
