@@ -8,7 +8,7 @@ namespace {
 constexpr int64_t kMaxRows = 2147483647LL;        // gridDim.x
 constexpr int64_t kMaxCols = 2147483647LL - 31;   // so that ceil(cols/32)*32 stays in int32 range
 constexpr int64_t kMaxRank = 256;
-constexpr int64_t kMaxM = 65535LL * 64;           // gridDim.y of the tiled kernels
+constexpr int64_t kMaxM = 65535LL * 64;           // gridDim.y of the generic kernel
 
 }  // namespace
 

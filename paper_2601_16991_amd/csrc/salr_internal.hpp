@@ -57,10 +57,9 @@ constexpr int64_t kStreamMaxM = 64;
 constexpr int kStreamTSlices = 16;
 constexpr int kMaxRankPadded = 256;  // R <= 256: pitch of the T tile the streaming kernels keep in LDS
 
-// Large-batch path: M >= kTwoStageMinM decodes the weight once into a dense scratch matrix, then runs a
-// dense MFMA GEMM on it.
-constexpr int64_t kTwoStageMinM = 256;
-inline bool uses_twostage(int64_t M, int64_t K) { return M >= kTwoStageMinM && K >= 64 && K % 64 == 0; }
+// Large-batch path: M > kStreamMaxM decodes the weight once into a dense scratch matrix, then runs a dense MFMA
+// GEMM on it (k-steps of 64).
+inline bool uses_twostage(int64_t M, int64_t K) { return M > kStreamMaxM && K >= 64 && K % 64 == 0; }
 
 inline size_t round_up_256(size_t b) { return (b + 255) / 256 * 256; }
 
@@ -118,7 +117,6 @@ inline size_t linear_workspace_bytes(int64_t M, int64_t K, int64_t N, int64_t R)
 
 hipError_t launch_linear(const LinearArgs& args, hipStream_t stream);
 hipError_t launch_linear_stream(const LinearArgs& args, hipStream_t stream, const TimingEvents& ev);
-hipError_t launch_linear_tiled(const LinearArgs& args, hipStream_t stream, const TimingEvents& ev);
 hipError_t launch_linear_twostage(const LinearArgs& args, hipStream_t stream, const TimingEvents& ev);
 // T = X * A_cat in bf16 [M, Rpad] at the start of the workspace (every path with M > kStreamMaxM)
 void launch_adapter_t(const LinearArgs& args, hipStream_t stream);

@@ -158,7 +158,6 @@ hipError_t launch_linear(const LinearArgs& a, hipStream_t stream) {
     if (a.M == 0 || a.N == 0) return hipSuccess;
     if (a.M <= kStreamMaxM) return launch_linear_stream(a, stream, g_timing_events);
     if (uses_twostage(a.M, a.K)) return launch_linear_twostage(a, stream, g_timing_events);
-    if (a.K >= 64 && a.K % 64 == 0) return launch_linear_tiled(a, stream, g_timing_events);
     const int R = (int)a.R;
     const int Rpad = (int)adapter_rank_padded(a.R);
     if (R > 0) launch_adapter_t(a, stream);

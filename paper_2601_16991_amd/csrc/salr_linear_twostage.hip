@@ -1,8 +1,8 @@
-// Large-batch path of the SALR linear (M >= 256): the two stages of Sec. 3.3 ("Pipeline Design") as two kernels.
+// Large-batch path of the SALR linear (M > 64): the two stages of Sec. 3.3 ("Pipeline Design") as two kernels.
 //
 //   stage 1  bitmap decode of the whole weight into a dense bf16 scratch matrix (the decode kernel of the codec,
-//            once per call: the fused kernels repeat the decode for every 256-row block of X, which at
-//            M >= 256 costs more than one round trip of the dense matrix through memory);
+//            once per call: a kernel that decodes into LDS tiles next to its MFMAs repeats the decode for every
+//            256-row block of X and was slower at every M > 64, see below);
 //   stage 2  dense_gemm_kernel: Y = X * Wd^T (+ T * B_cat, Sec. 3.2) on the matrix cores.
 //
 // dense_gemm_kernel: output tile 256 (m) x 64 kWN (n); wave (wm, wn) owns 32 kMI x 64 = kMI x 2 tiles of

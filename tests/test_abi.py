@@ -76,8 +76,8 @@ def _y_ksplit(M, K, N):
 
 def _expected_workspace(M, K, N, R):
     """The documented layout, restated: M <= 64: sixteen fp32 split-K partials of T.  Larger M: T [M, Rpad] bf16,
-    transposed padded A_cat [Rpad, K] bf16, fp32 split-K partials of T; for M >= 256 and K % 64 == 0 also the decoded
-    weight [N, K] bf16 and, when the output has few tiles, fp32 split-K partials of Y.  Each part rounded to 256 B."""
+    transposed padded A_cat [Rpad, K] bf16, fp32 split-K partials of T; for K % 64 == 0 also the decoded weight [N, K]
+    bf16 and, when the output has few tiles, fp32 split-K partials of Y.  Each part rounded to 256 B."""
     rp = (R + 31) // 32 * 32
     if M <= 64:
         return _r256(16 * M * rp * 4) if R else 0
@@ -87,7 +87,7 @@ def _expected_workspace(M, K, N, R):
         ks = _t_ksplit(M, K)
         if ks > 1:
             b += _r256(ks * M * rp * 4)
-    if M >= 256 and K >= 64 and K % 64 == 0:
+    if K >= 64 and K % 64 == 0:
         b += _r256(N * K * 2)
         ks = _y_ksplit(M, K, N)
         if ks > 1:
@@ -100,7 +100,8 @@ def test_workspace_bytes(lib):
     assert lib.salr_linear_workspace_bytes(0, 4096, 4096, 32) == 0
     assert lib.salr_linear_workspace_bytes(16, 4096, 4096, 32) == 16 * 16 * 32 * 4
     assert lib.salr_linear_workspace_bytes(1, 4096, 4096, 64) == 16 * 64 * 4
-    assert lib.salr_linear_workspace_bytes(128, 4096, 4096, 0) == 0
+    assert lib.salr_linear_workspace_bytes(64, 4096, 4096, 0) == 0
+    assert lib.salr_linear_workspace_bytes(128, 4000, 4096, 0) == 0            # K % 64 != 0: no dense scratch
     assert lib.salr_linear_workspace_bytes(16, 4096, 4096, 1000) == 0          # rank not supported
     assert lib.salr_linear_workspace_bytes(2048, 4096, 14336, 0) == 14336 * 4096 * 2
     assert _t_ksplit(4096, 14336) == 32 and _t_ksplit(2048, 4096) == 16 and _y_ksplit(512, 14336, 4096) == 4

@@ -57,11 +57,10 @@ def test_tiny_config():
 @pytest.mark.parametrize("M,K,N,ranks", [
     (1, 64, 16, (8,)), (3, 96, 40, (4, 4)), (17, 128, 100, (16, 16)), (65, 256, 130, (5,)), (100, 32, 64, (33,)),
     (16, 512, 64, ()), (130, 160, 70, (64, 64, 64, 64)), (2, 2048, 48, (1,)), (64, 64, 64, (32,)),
-    # 64 < M < 256 with K % 64 == 0: the fused tiled MFMA path, ragged in both tile dimensions
+    # M > 64 with K % 64 == 0: decode once into dense scratch, then the dense MFMA kernel (1, 2, 3, 5 k-steps;
+    # ragged in both tile dimensions); other K at such M fall back to the generic kernel
     (200, 512, 300, (16, 16)), (255, 128, 513, (7,)), (70, 384, 64, ()), (65, 1024, 1030, (40, 60)),
     (129, 64, 129, (3,)), (160, 192, 260, (16,)),
-    # M >= 256 with K % 64 == 0: decode once into dense scratch, then the dense MFMA kernel (1, 2, 3, 5 k-steps;
-    # ragged in both tile dimensions); other K at such M fall back to the generic kernel
     (300, 512, 300, (16, 16)), (257, 128, 513, (7,)), (600, 192, 260, (16,)), (256, 64, 129, (3,)),
     (1030, 64, 100, ()), (1100, 128, 257, (16, 16)), (1025, 192, 140, (33,)), (1024, 320, 130, (5,)),
     (1024, 32, 130, (5,)), (1100, 96, 70, (16,)),
