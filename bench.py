@@ -340,7 +340,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{cfg.name} W[{cfg.N},{cfg.K}] p=0.{permille // 100} R={layer.R} M={M}",
                    "weight_copies_rotated": layer.ncopies, "algorithmic_bytes": alg_bytes,
-                   "algorithmic_flops": alg_flops},
+                   "algorithmic_flops": alg_flops,   # executed: the method multiplies the decoded zeros too
+                   "useful_flops": 2 * M * layer.nnz + 2 * M * layer.R * (cfg.K + cfg.N)},
         "tflops": round(alg_flops / (ms_wall * 1e-3) / 1e12, 3),
         "speedup_vs_dense_gemm": round(dense_ms / ms_wall, 3),
         "speedup_vs_dense_gemm_plus_lora": round(dense_lora_ms / ms_wall, 3),
@@ -348,7 +349,9 @@ def main():
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": load_traffic(f"{cfg.name}_M{M}"),
                      "kernel": "fused decode+GEMM kernel of salr_sparse_lowrank_linear",
-                     "kernel_avg_us": round(k_avg * 1e3, 3), "kernel_median_us": round(k_med * 1e3, 3)},
+                     "kernel_avg_us": round(k_avg * 1e3, 3), "kernel_median_us": round(k_med * 1e3, 3),
+                     "kernel_p10_us": round(float(np.percentile(kernel_ms, 10)) * 1e3, 3),
+                     "kernel_p90_us": round(float(np.percentile(kernel_ms, 90)) * 1e3, 3)},
     }
 
     if not args.no_extras:
