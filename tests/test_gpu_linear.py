@@ -165,3 +165,21 @@ def test_gate_up_prefill_sampled_rows():
     y_ref = oracle.linear(np.ascontiguousarray(x[rows]), w_hat, a_cat, b_cat)
     _assert_close(y[rows], y_ref, "gate/up M=2048 (8 sampled rows)")
     assert np.isfinite(y).all()
+
+
+@pytest.mark.parametrize("name,permille,M", [
+    ("llama3_8b_down_proj", 700, 512),     # split-K dense stage, odd keep (4301 per row), R = 64
+    ("llama3_8b_down_proj", 500, 4096),    # 256 x 256 tiles, T with four row blocks per adapter operand
+    ("llama3_70b_attn", 500, 4096),        # K = N = 8192
+])
+def test_large_batch_full_size_sampled_rows(name, permille, M):
+    """Full-size launches of the large-batch path; the oracle checks a fixed sample of 6 rows of X across all N."""
+    cfg = wl.CONFIGS[name]
+    w_hat = oracle.mask_topk_rows(wl.dense_weight(cfg), cfg.keep(permille))
+    a_cat, b_cat = wl.concat_adapters(*wl.adapters(cfg))
+    x = wl.activations(cfg, M)
+    y = _run(x, w_hat, a_cat, b_cat)
+    rows = np.array([0, 15, 16, 255, M // 2 + 1, M - 1])
+    y_ref = oracle.linear(np.ascontiguousarray(x[rows]), w_hat, a_cat, b_cat)
+    _assert_close(y[rows], y_ref, f"{name} p={permille} M={M} (6 sampled rows)")
+    assert np.isfinite(y).all()
