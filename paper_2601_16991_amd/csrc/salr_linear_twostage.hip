@@ -10,8 +10,8 @@
 // wide ones would not fill the chip).  A k-step is 64 wide so that every row of a tile is one whole 128-byte line: at 64
 // bytes per row the L2 sees twice the requests for the same bytes and its request rate, not its bandwidth,
 // limits the kernel.  Both operand tiles travel from memory straight into LDS (global_load_lds, 16 bytes per
-// lane, no registers, no VALU) into a ring of kStages stages; one barrier per step publishes the stage that is
-// multiplied next and retires the one read before.  LDS rows are 128 bytes, swizzled (segment s of row r at
+// lane, no registers, no VALU) into a ring of kStages stages; one barrier per step, in its middle, publishes the
+// stage that is multiplied next and retires the one read last.  LDS rows are 128 bytes, swizzled (segment s of row r at
 // s ^ ((r >> 1) & 7)) so that operand reads are conflict-free; a load instruction of a wave fills 8 consecutive
 // rows, lane l landing on 16-byte slot l, so lane l fetches the segment that belongs there.
 #include "salr_device.hpp"
@@ -106,6 +106,7 @@ __global__ __launch_bounds__(64 * (8 / kMI) * kWN, (8 / kMI) * kWN / 4) void den
     };
     // the requests of the newest kStages - 2 steps may stay in flight, everything older has landed
     static_assert((kStages - 2) * kLoads <= 15, "vmcnt immediate");
+    static_assert(kStages >= 2, "the stage that is read and the one that lands are different ones");
     auto older_landed = [&]() { __builtin_amdgcn_s_waitcnt(0x0F70 | ((kStages - 2) * kLoads)); };
 
     f32x16 acc[kMI][kNI];
@@ -136,33 +137,61 @@ __global__ __launch_bounds__(64 * (8 / kMI) * kWN, (8 / kMI) * kWN / 4) void den
             for (int j = 0; j < kNI; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
     };
-    // the operands of sub-step j + 1 are requested before the MFMAs of sub-step j issue
-    auto mfma_step = [&](const uint16_t* xs, const uint16_t* ws, int substeps) {
-        const uint16_t* xa = xs + (wm * 32 * kMI + frag_row) * kDK;
-        const uint16_t* wb = ws + (wn * 32 * kNI + frag_row) * kDK;
-        Frags f0 = load_frags(xa, wb, 0);
-        Frags f1 = load_frags(xa, wb, 1);
-        multiply(f0);
-        if (substeps == 4) {
-            f0 = load_frags(xa, wb, 2);
-            multiply(f1);
-            f1 = load_frags(xa, wb, 3);
-            multiply(f0);
-            multiply(f1);
-        } else {
-            multiply(f1);
-        }
+    // one k-step of 32 (two sub-steps) on stage 0: the shape of an adapter step
+    auto rank_step = [&]() {
+        const uint16_t* xa = Xs[0] + (wm * 32 * kMI + frag_row) * kDK;
+        const uint16_t* wb = Ws[0] + (wn * 32 * kNI + frag_row) * kDK;
+        const Frags r0 = load_frags(xa, wb, 0);
+        const Frags r1 = load_frags(xa, wb, 1);
+        multiply(r0);
+        multiply(r1);
     };
 
-    // ---- k loop: stage s % kStages is multiplied while the requests of the next kStages - 1 steps are in flight
-    for (int p = 0; p < kStages - 1; ++p) fetch(Xs[p], Ws[p], p);
-    int cur = 0, nxt = kStages - 1;   // stage of step s, stage that step s + kStages - 1 goes into
+    // ---- k loop.  The ring holds steps s .. s + kStages - 1.  The one barrier of a step sits in its middle, after
+    // the last operand read of stage `cur`: it retires that stage (refilled at once with step s + kStages) and
+    // publishes stage `nxt`, whose first operands are then requested under the MFMAs of the step's second half, so
+    // that no wave starts a step with an empty matrix pipe.
+    // Operands are requested one sub-step before they are multiplied.  The scheduling fences keep the compiler from
+    // sinking the reads down to their first use, where every one of them would be waited for with nothing else to
+    // issue (only where three sets of operands fit into the registers beside the accumulators).
+    constexpr bool kFenced = kMI * kNI * 16 + 12 * (kMI + kNI) <= 200;
+    auto fence = [&]() {
+        if constexpr (kFenced) __builtin_amdgcn_sched_barrier(0);
+    };
+    for (int p = 0; p < kStages; ++p) fetch(Xs[p], Ws[p], p);
+    // step 0 has landed (a count of requests allowed in flight only where every wave issues the same number)
+    __builtin_amdgcn_s_waitcnt(0x0F70 | ((kWRagged || (kStages - 1) * kLoads > 15) ? 0 : (kStages - 1) * kLoads));
+    __syncthreads();
+    const uint16_t* xa0 = Xs[0] + (wm * 32 * kMI + frag_row) * kDK;
+    const uint16_t* wb0 = Ws[0] + (wn * 32 * kNI + frag_row) * kDK;
+    Frags f0 = load_frags(xa0, wb0, 0);
+    Frags f1 = load_frags(xa0, wb0, 1);
+    int cur = 0, nxt = 1;
     for (int64_t s = 0; s < steps; ++s) {
-        older_landed();
-        __syncthreads();   // stage `cur` published; every wave is done with stage `nxt` (read in step s - 1)
-        fetch(Xs[nxt], Ws[nxt], s + kStages - 1);
-        mfma_step(Xs[cur], Ws[cur], 4);
-        cur = cur + 1 == kStages ? 0 : cur + 1;
+        const uint16_t* xa = Xs[cur] + (wm * 32 * kMI + frag_row) * kDK;
+        const uint16_t* wb = Ws[cur] + (wn * 32 * kNI + frag_row) * kDK;
+        const uint16_t* xn = Xs[nxt] + (wm * 32 * kMI + frag_row) * kDK;
+        const uint16_t* wn_ = Ws[nxt] + (wn * 32 * kNI + frag_row) * kDK;
+        const Frags f2 = load_frags(xa, wb, 2);
+        fence();
+        multiply(f0);
+        fence();
+        const Frags f3 = load_frags(xa, wb, 3);
+        fence();
+        multiply(f1);
+        fence();
+        older_landed();    // this wave's requests for step s + 1 have landed
+        __syncthreads();   // ... and everybody's; every wave has read all it needs of stage `cur`
+        fetch(Xs[cur], Ws[cur], s + kStages);
+        f0 = load_frags(xn, wn_, 0);
+        fence();
+        multiply(f2);
+        fence();
+        f1 = load_frags(xn, wn_, 1);
+        fence();
+        multiply(f3);
+        fence();
+        cur = nxt;
         nxt = nxt + 1 == kStages ? 0 : nxt + 1;
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): no request may land after this point
@@ -189,7 +218,7 @@ __global__ __launch_bounds__(64 * (8 / kMI) * kWN, (8 / kMI) * kWN / 4) void den
                 Ws[0][bcol * kDK + dswz(bcol, rr >> 3) + (rr & 7)] = rg < R ? v : (uint16_t)0;
             }
             __syncthreads();
-            mfma_step(Xs[0], Ws[0], 2);
+            rank_step();
             __syncthreads();
         }
     }

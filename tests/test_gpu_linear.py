@@ -183,3 +183,56 @@ def test_large_batch_full_size_sampled_rows(name, permille, M):
     y_ref = oracle.linear(np.ascontiguousarray(x[rows]), w_hat, a_cat, b_cat)
     _assert_close(y[rows], y_ref, f"{name} p={permille} M={M} (6 sampled rows)")
     assert np.isfinite(y).all()
+
+
+@pytest.mark.parametrize("M,ranks", [(1, (8, 8)), (16, (32,)), (40, (64, 30)), (64, (128, 128))])
+def test_small_batch_one_workspace_many_calls(M, ranks):
+    """The small-batch path keeps split-K partial sums of T = X A_cat in the workspace.  One workspace, first filled
+    with arbitrary bytes, then used by calls in a row whose X (and so T) changes: no call may see what an earlier
+    call, or nobody, left there."""
+    salr = _salr()
+    K, N = 512, 1000
+    x0, w, a_cat, b_cat = _problem(M, K, N, ranks, seed=900 + M)
+    rb, rv, ro = oracle.encode(w)
+    d = dict(bm=to_dev_u32(rb), v=to_dev_u16(rv), ro=to_dev_u32(ro), a=to_dev_u16(a_cat), b=to_dev_u16(b_cat))
+    need = salr.salr_linear_workspace_bytes(M, K, N, sum(ranks))
+    ws = torch.randint(0, 256, (need,), dtype=torch.uint8, device=dev())
+    for call in range(6):
+        x = wl.gaussian_bf16((M, K), 1.0 + call, 7000 + 13 * call + M)
+        y = salr.linear(to_dev_u16(x), d["bm"], d["v"], d["ro"], d["a"], d["b"], workspace=ws)
+        torch.cuda.synchronize()
+        _assert_close(y_to_f64(y), oracle.linear(x, w, a_cat, b_cat), f"M={M} R={sum(ranks)} call {call}")
+
+
+@pytest.mark.parametrize("M,K,N", [(16, 1024, 2048), (192, 512, 1000), (300, 1024, 520)])
+def test_graph_replays(M, K, N):
+    """A captured call (small-batch kernels; large-batch kernels, whose adapter part runs on a forked stream) is
+    replayed with new activations in place; the program's own eager work and synchronisations run between replays,
+    and every replay is checked."""
+    salr = _salr()
+    ranks = (32, 16)
+    x0, w, a_cat, b_cat = _problem(M, K, N, ranks, seed=4242)
+    rb, rv, ro = oracle.encode(w)
+    bm, v, rod = to_dev_u32(rb), to_dev_u16(rv), to_dev_u32(ro)
+    a, b = to_dev_u16(a_cat), to_dev_u16(b_cat)
+    x_dev = to_dev_u16(x0)
+    y = torch.empty((M, N), dtype=x_dev.dtype, device=dev())
+    ws = torch.empty(salr.salr_linear_workspace_bytes(M, K, N, sum(ranks)), dtype=torch.uint8, device=dev())
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):   # one eager call first, as a capture's warm-up
+        salr.salr_sparse_lowrank_linear(x_dev, bm, v, rod, a, b, y, ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        salr.salr_sparse_lowrank_linear(x_dev, bm, v, rod, a, b, y, ws)
+    for replay in range(5):
+        x = wl.gaussian_bf16((M, K), 0.5 + replay, 8100 + replay)
+        x_dev.copy_(to_dev_u16(x))
+        graph.replay()
+        torch.cuda.synchronize()
+        _assert_close(y_to_f64(y), oracle.linear(x, w, a_cat, b_cat), f"graph replay {replay}")
+        eager = salr.linear(x_dev, bm, v, rod, a, b)   # eager work between the replays, on another workspace
+        torch.cuda.synchronize()
+        assert torch.equal(eager.view(torch.int16), y.view(torch.int16)), f"replay {replay} differs from eager"
