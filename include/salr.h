@@ -161,6 +161,35 @@ salr_status_t salr_sparse_lowrank_linear(const uint16_t* x, int64_t M, int64_t K
                                          size_t workspace_bytes, void* stream);
 
 /*
+ * salr_residual -- Sec. 3.1 ("Sparsity Preservation Pruning"): the residual E = W - W-hat that the pruning
+ * leaves behind and whose truncated SVD becomes the residual adapter.
+ *
+ *   w, w_hat   in   [rows, cols] bf16
+ *   e          out  [rows, cols] bf16: bf16(float(w) - float(w_hat)), the subtraction in fp32, rounded to
+ *                   nearest even.  When every entry of w_hat is the entry of w or zero (a mask), this is exact:
+ *                   the entry of w where it was pruned and +0 where it was kept.  May alias neither input.
+ * Errors: INVALID_ARG, SHAPE (rows or cols >= 2^31), HIP.
+ */
+salr_status_t salr_residual(const uint16_t* w, const uint16_t* w_hat, int64_t rows, int64_t cols, uint16_t* e,
+                            void* stream);
+
+/*
+ * salr_concat_adapters -- Sec. 3.2 ("Concatenating Multi-LoRA adapters"): A_cat = [A_1 ... A_n] side by side
+ * and B_cat = [B_1; ...; B_n] stacked, so that (x A_cat) B_cat = sum_i (x A_i) B_i.
+ *
+ *   a_list, b_list  in   HOST arrays of n DEVICE pointers: A_i [K, ranks[i]] bf16, B_i [ranks[i], N] bf16
+ *   ranks           in   HOST array of n ranks r_i >= 0; R = sum r_i <= 65535 (else SHAPE).  An adapter of rank 0
+ *                        contributes nothing and its pointers are not looked at.
+ *   a_cat           out  [K, R] bf16: columns [sum_{j<i} r_j, sum_{j<=i} r_j) are A_i
+ *   b_cat           out  [R, N] bf16: the same range of rows is B_i
+ * The host arrays are read before the call returns.  Pure data movement: outputs are bit copies.
+ * Errors: INVALID_ARG (null where data is required, negative size or rank), SHAPE, HIP.
+ */
+salr_status_t salr_concat_adapters(const uint16_t* const* a_list, const uint16_t* const* b_list,
+                                   const int64_t* ranks, int64_t n, int64_t K, int64_t N, uint16_t* a_cat,
+                                   uint16_t* b_cat, void* stream);
+
+/*
  * Measurement hook (not part of the method): when both events are non-NULL, the next calls of
  * salr_sparse_lowrank_linear on this host thread attach the two events to the launch of the fused
  * decode+GEMM kernel: `start_event` takes the time the kernel begins executing and `stop_event` the

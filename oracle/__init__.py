@@ -14,7 +14,8 @@ the row mask applied to each group), the paper's printed
 rule and Theorem 1's closed form and worked example; encode/decode against each other, the paper's
 byte-mask/LUT decoder, popcount identities and hand-worked masks; the linear against pure-Python
 loops, numpy fp64 matmul in the special cases that reduce to it, and the per-adapter sum; the SVD
-residual against Theorem 3's bound.  No function here is "parity unpinned".
+residual against Theorem 3's bound; the residual against W = What + E and hand-worked values; the
+concatenation against the sum over adapters on integer-valued matrices.  No function here is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -220,6 +221,41 @@ def pruning_mse_closed_form(p: float, sigma: float = 1.0) -> float:
 def bf16_to_f64(bits: np.ndarray) -> np.ndarray:
     b = np.ascontiguousarray(bits, dtype=np.uint16)
     return (b.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+
+
+def f32_to_bf16(x: np.ndarray) -> np.ndarray:
+    """Round fp32 to bf16 bit patterns, nearest even (NaN stays NaN).  Written out on the integer patterns:
+    add 0x7FFF plus the lowest kept bit, drop the low 16 bits."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    rounded = (u + np.uint64(0x7FFF) + ((u >> np.uint64(16)) & np.uint64(1))) >> np.uint64(16)
+    nan = (u & np.uint64(0x7FFFFFFF)) > np.uint64(0x7F800000)
+    return np.where(nan, (u >> np.uint64(16)) | np.uint64(0x40), rounded).astype(np.uint16)
+
+
+def residual(w: np.ndarray, w_hat: np.ndarray) -> np.ndarray:
+    """Sec. 3.1: E = W - What, entry by entry; the subtraction in fp32 (exact whenever What is a masked W),
+    the result as bf16 patterns."""
+    a = (np.ascontiguousarray(w, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+    b = (np.ascontiguousarray(w_hat, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+    with np.errstate(invalid="ignore", over="ignore"):   # Inf - Inf and NaN operands are legal inputs
+        return f32_to_bf16(a - b)
+
+
+def concat_adapters(As: Sequence[np.ndarray], Bs: Sequence[np.ndarray]) -> Tuple[np.ndarray, np.ndarray]:
+    """Sec. 3.2: A_cat = [A_1 ... A_n] in R^{d_in x (sum r_i)}, B_cat = [B_1; ...; B_n] in R^{(sum r_i) x d_out}."""
+    K, N = As[0].shape[0], Bs[0].shape[1]
+    R = sum(a.shape[1] for a in As)
+    a_cat = np.zeros((K, R), dtype=As[0].dtype)
+    b_cat = np.zeros((R, N), dtype=Bs[0].dtype)
+    first = 0
+    for a, b in zip(As, Bs):
+        r = a.shape[1]
+        assert a.shape == (K, r) and b.shape == (r, N)
+        for c in range(r):
+            a_cat[:, first + c] = a[:, c]
+            b_cat[first + c, :] = b[c, :]
+        first += r
+    return a_cat, b_cat
 
 
 def svd_residual_check(w: np.ndarray, w_hat: np.ndarray, r: int) -> Tuple[float, float]:

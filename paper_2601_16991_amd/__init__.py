@@ -12,7 +12,7 @@ from __future__ import annotations
 
 import ctypes
 import os
-from typing import Optional, Tuple
+from typing import Optional, Sequence, Tuple
 
 import torch
 
@@ -57,6 +57,11 @@ def lib() -> ctypes.CDLL:
         L.salr_sparse_lowrank_linear.restype = ctypes.c_int
         L.salr_sparse_lowrank_linear.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _vp,
                                                  ctypes.c_size_t, _vp]
+        L.salr_residual.restype = ctypes.c_int
+        L.salr_residual.argtypes = [_vp, _vp, _i64, _i64, _vp, _vp]
+        L.salr_concat_adapters.restype = ctypes.c_int
+        L.salr_concat_adapters.argtypes = [ctypes.POINTER(_vp), ctypes.POINTER(_vp), ctypes.POINTER(_i64), _i64, _i64, _i64,
+                                           _vp, _vp, _vp]
         L.salr_set_kernel_timing_events.restype = None
         L.salr_set_kernel_timing_events.argtypes = [_vp, _vp]
         _lib = L
@@ -210,6 +215,50 @@ def mask_nm(w: torch.Tensor, n_keep: int, m_group: int) -> torch.Tensor:
     w_hat = torch.empty_like(w)
     salr_magnitude_mask_nm(w, n_keep, m_group, w_hat)
     return w_hat
+
+
+def salr_residual(w: torch.Tensor, w_hat: torch.Tensor, e: torch.Tensor, stream=None) -> None:
+    """Enqueue E = W - What (bf16, [rows, cols])."""
+    if w.shape != w_hat.shape or w.shape != e.shape or w.dim() != 2:
+        raise ValueError("w, w_hat and e must be matrices of one shape")
+    rows, cols = w.shape
+    _check(lib().salr_residual(_ptr(w, _BF16_TYPES, "w"), _ptr(w_hat, _BF16_TYPES, "w_hat"), rows, cols,
+                               _ptr(e, _BF16_TYPES, "e"), _stream(stream)), "salr_residual")
+
+
+def salr_concat_adapters(a_list: Sequence[torch.Tensor], b_list: Sequence[torch.Tensor], a_cat: torch.Tensor,
+                         b_cat: torch.Tensor, stream=None) -> None:
+    """Enqueue A_cat = [A_1 ... A_n] ([K, R]) and B_cat = [B_1; ...; B_n] ([R, N])."""
+    n = len(a_list)
+    if len(b_list) != n:
+        raise ValueError("as many A_i as B_i")
+    K, N = a_cat.shape[0], b_cat.shape[1]
+    ranks = []
+    for i, (a, b) in enumerate(zip(a_list, b_list)):
+        if a.dim() != 2 or b.dim() != 2 or a.shape[0] != K or b.shape[1] != N or a.shape[1] != b.shape[0]:
+            raise ValueError(f"adapter {i}: shapes {tuple(a.shape)} {tuple(b.shape)}")
+        ranks.append(a.shape[1])
+    if a_cat.shape[1] != sum(ranks) or b_cat.shape[0] != sum(ranks):
+        raise ValueError("a_cat / b_cat do not have sum(ranks) columns / rows")
+    pa = (_vp * max(n, 1))(*[_ptr(a, _BF16_TYPES, "A_i") for a in a_list])
+    pb = (_vp * max(n, 1))(*[_ptr(b, _BF16_TYPES, "B_i") for b in b_list])
+    rk = (_i64 * max(n, 1))(*ranks)
+    _check(lib().salr_concat_adapters(pa, pb, rk, n, K, N, _ptr(a_cat, _BF16_TYPES, "a_cat"),
+                                      _ptr(b_cat, _BF16_TYPES, "b_cat"), _stream(stream)), "salr_concat_adapters")
+
+
+def residual(w: torch.Tensor, w_hat: torch.Tensor) -> torch.Tensor:
+    e = torch.empty_like(w)
+    salr_residual(w, w_hat, e)
+    return e
+
+
+def concat_adapters(a_list: Sequence[torch.Tensor], b_list: Sequence[torch.Tensor]) -> Tuple[torch.Tensor, torch.Tensor]:
+    R = sum(a.shape[1] for a in a_list)
+    a_cat = torch.empty((a_list[0].shape[0], R), dtype=a_list[0].dtype, device=a_list[0].device)
+    b_cat = torch.empty((R, b_list[0].shape[1]), dtype=b_list[0].dtype, device=b_list[0].device)
+    salr_concat_adapters(a_list, b_list, a_cat, b_cat)
+    return a_cat, b_cat
 
 
 def encode(w_dense: torch.Tensor) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:

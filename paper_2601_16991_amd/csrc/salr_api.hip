@@ -72,6 +72,33 @@ salr_status_t salr_decode(const uint32_t* bitmap, const uint16_t* values, const 
     return e == hipSuccess ? SALR_OK : SALR_ERR_HIP;
 }
 
+salr_status_t salr_residual(const uint16_t* w, const uint16_t* w_hat, int64_t rows, int64_t cols, uint16_t* e, void* stream) {
+    if (rows < 0 || cols < 0) return SALR_ERR_INVALID_ARG;
+    if (rows > 0 && cols > 0 && (!w || !w_hat || !e)) return SALR_ERR_INVALID_ARG;
+    if (rows > kMaxRows || cols > kMaxCols) return SALR_ERR_SHAPE;
+    hipError_t err = salr::launch_residual(w, w_hat, rows, cols, e, static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? SALR_OK : SALR_ERR_HIP;
+}
+
+salr_status_t salr_concat_adapters(const uint16_t* const* a_list, const uint16_t* const* b_list, const int64_t* ranks,
+                                   int64_t n, int64_t K, int64_t N, uint16_t* a_cat, uint16_t* b_cat, void* stream) {
+    if (n < 0 || K < 0 || N < 0) return SALR_ERR_INVALID_ARG;
+    if (n == 0) return SALR_OK;
+    if (!a_list || !b_list || !ranks) return SALR_ERR_INVALID_ARG;
+    if (K > kMaxCols || N > kMaxRows) return SALR_ERR_SHAPE;
+    int64_t R = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        if (ranks[i] < 0) return SALR_ERR_INVALID_ARG;
+        if (ranks[i] > 0 && ((K > 0 && !a_list[i]) || (N > 0 && !b_list[i]))) return SALR_ERR_INVALID_ARG;
+        R += ranks[i];
+        if (R > 65535) return SALR_ERR_SHAPE;   // rows of B_cat are a grid dimension
+    }
+    if (R == 0) return SALR_OK;
+    if ((K > 0 && !a_cat) || (N > 0 && !b_cat)) return SALR_ERR_INVALID_ARG;
+    hipError_t err = salr::launch_concat(a_list, b_list, ranks, n, K, N, R, a_cat, b_cat, static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? SALR_OK : SALR_ERR_HIP;
+}
+
 size_t salr_linear_workspace_bytes(int64_t M, int64_t K, int64_t N, int64_t R) {
     if (M <= 0 || K < 0 || N <= 0 || R < 0 || R > kMaxRank || K % 32 != 0) return 0;
     return salr::linear_workspace_bytes(M, K, N, R);

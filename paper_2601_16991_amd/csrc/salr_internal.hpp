@@ -20,6 +20,14 @@ hipError_t launch_mask_rows(const uint16_t* w, int64_t rows, int64_t cols, int64
 hipError_t launch_mask_nm(const uint16_t* w, int64_t rows, int64_t cols, int n_keep, int m_group, uint16_t* out,
                           hipStream_t stream);
 
+hipError_t launch_residual(const uint16_t* w, const uint16_t* w_hat, int64_t rows, int64_t cols, uint16_t* e,
+                           hipStream_t stream);
+
+// Host arrays of n device pointers / ranks; R = sum of the ranks.
+constexpr int kConcatBatch = 16;
+hipError_t launch_concat(const uint16_t* const* a_list, const uint16_t* const* b_list, const int64_t* ranks, int64_t n,
+                         int64_t K, int64_t N, int64_t R, uint16_t* a_cat, uint16_t* b_cat, hipStream_t stream);
+
 // Columns of the bf16 workspace matrix T = X * A_cat: R rounded up to the MFMA k-step.
 inline int64_t adapter_rank_padded(int64_t R) { return (R + 31) / 32 * 32; }
 

@@ -130,3 +130,58 @@ def test_residual_adapter_reconstructs_truncated_svd():
     np.testing.assert_allclose(A @ B, E_r.T, atol=1e-12)
     _, ratio = oracle.svd_residual_check(w, w_hat, r)
     assert abs(np.linalg.norm(E - E_r) ** 2 / np.linalg.norm(E) ** 2 - ratio) < 1e-12
+
+
+def test_f32_to_bf16_hand_values():
+    # 1.0 -> 0x3F80; 1 + 2^-8 is a tie between 0x3F80 and 0x3F81 -> even (0x3F80); 1 + 3 * 2^-8 ties to 0x3F82;
+    # just above the first tie goes up; -0.0 keeps its sign; the largest fp32 rounds to +inf
+    x = np.array([1.0, 1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -8 + 2.0 ** -20, -0.0, 3.4028234e38],
+                 dtype=np.float32)
+    np.testing.assert_array_equal(oracle.f32_to_bf16(x), np.array([0x3F80, 0x3F80, 0x3F82, 0x3F81, 0x8000, 0x7F80],
+                                                                  dtype=np.uint16))
+    assert oracle.f32_to_bf16(np.array([np.nan], dtype=np.float32))[0] & 0x7FFF > 0x7F80
+
+
+def test_residual_of_a_mask_is_the_pruned_part():
+    """Sec. 3.1: W = What + E exactly, E and What have disjoint support, ||E||_F^2 / size is Theorem 1's MSE."""
+    N, K = 64, 512
+    w = wl.gaussian_bf16((N, K), 0.02, 4711)
+    w_hat = oracle.mask_topk_rows(w, K // 2)
+    e = oracle.residual(w, w_hat)
+    assert e.dtype == np.uint16 and e.shape == w.shape
+    kept = (w_hat & 0x7FFF) != 0
+    np.testing.assert_array_equal(e[~kept], w[~kept])          # pruned entries move to E bit for bit
+    assert not np.any(e[kept] & 0x7FFF)                         # kept entries leave a zero
+    np.testing.assert_array_equal(_f64(w_hat) + _f64(e), _f64(w))
+    mse = float(np.sum(_f64(e) ** 2)) / e.size
+    assert abs(mse / oracle.pruning_mse_closed_form(0.5, 0.02) - 1.0) < 0.05
+
+
+def test_residual_hand_values():
+    # bf16 patterns: 1.0 = 0x3F80, 0.5 = 0x3F00, 2^-8 = 0x3B80, 255/256 = 0x3F7F, -1.5 = 0xBFC0, 2.5 = 0x4020
+    w = np.array([[0x3F80, 0x3F80, 0x3F00, 0xBFC0]], dtype=np.uint16)
+    h = np.array([[0x3F00, 0x3B80, 0x3F00, 0x3F80]], dtype=np.uint16)
+    # 1 - 0.5 = 0.5; 1 - 2^-8 = 255/256; 0.5 - 0.5 = +0; -1.5 - 1 = -2.5
+    np.testing.assert_array_equal(oracle.residual(w, h), np.array([[0x3F00, 0x3F7F, 0x0000, 0xC020]], dtype=np.uint16))
+
+
+def test_concat_adapters_is_the_sum_over_adapters():
+    """Sec. 3.2 on small integers (every product and sum exact in fp64): (x A_cat) B_cat = sum_i (x A_i) B_i, and the
+    blocks sit where the definition puts them."""
+    rng = np.random.default_rng(5)
+    K, N, ranks = 7, 5, (1, 3, 2)
+    As = [rng.integers(-4, 5, (K, r)).astype(np.float64) for r in ranks]
+    Bs = [rng.integers(-4, 5, (r, N)).astype(np.float64) for r in ranks]
+    a_cat, b_cat = oracle.concat_adapters(As, Bs)
+    assert a_cat.shape == (K, 6) and b_cat.shape == (6, N)
+    np.testing.assert_array_equal(a_cat[:, 1:4], As[1])
+    np.testing.assert_array_equal(b_cat[4:6, :], Bs[2])
+    x = rng.integers(-3, 4, (4, K)).astype(np.float64)
+    np.testing.assert_array_equal((x @ a_cat) @ b_cat, sum((x @ a) @ b for a, b in zip(As, Bs)))
+    # and on bf16 patterns it is a bit copy, equal to the input generator's stacking
+    A16 = [wl.gaussian_bf16((K, r), 0.01, 30 + i) for i, r in enumerate(ranks)]
+    B16 = [wl.gaussian_bf16((r, N), 0.01, 40 + i) for i, r in enumerate(ranks)]
+    a1, b1 = oracle.concat_adapters(A16, B16)
+    a2, b2 = wl.concat_adapters(A16, B16)
+    np.testing.assert_array_equal(a1, a2)
+    np.testing.assert_array_equal(b1, b2)
