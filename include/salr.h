@@ -174,6 +174,39 @@ salr_status_t salr_residual(const uint16_t* w, const uint16_t* w_hat, int64_t ro
                             void* stream);
 
 /*
+ * salr_residual_adapter -- Sec. 3.1: the residual adapter, a low-rank pair whose product is the best rank-r
+ * approximation E_r (truncated SVD) of the residual E, in the orientation of the linear layer:
+ *
+ *     (A_res B_res)^T ~ E_r,   A_res = V_r S_r^{1/2} [K, r],   B_res = S_r^{1/2} U_r^T [r, N]   for E = U S V^T,
+ *
+ * so that appending (A_res, B_res) to A_cat / B_cat adds x E_r^T to the layer output.  The factors are computed
+ * by randomized subspace iteration (the paper names no algorithm): a sketch E Omega with l = r + oversample
+ * columns, `power_iterations` rounds of multiplying by E^T and E with re-orthonormalisation, then the SVD of the
+ * small projected matrix.  The pair itself is not unique (signs, rotations inside equal singular values); its
+ * product is, up to the method's error: ||E - (A_res B_res)^T||_F exceeds the optimum ||E - E_r||_F by a factor
+ * that falls geometrically with power_iterations, at a rate set by the decay of E's singular values.
+ *
+ *   e            in   [N, K] bf16 (salr_residual's output, or any matrix)
+ *   r            rank of the pair; oversample >= 0 extra sketch columns; r + oversample <= 128 (else
+ *                UNSUPPORTED) and <= min(N, K) (else SHAPE)
+ *   omega        in   [K, r + oversample] fp32, row-major: the test matrix, independent standard normal entries
+ *                     drawn by the caller (the library draws no random numbers)
+ *   a_res        out  [K, r] bf16
+ *   b_res        out  [r, N] bf16
+ *   sigma        out  [r] fp32, the singular values found, descending; may be NULL
+ *   workspace    --   at least salr_residual_adapter_workspace_bytes(N, K, r, oversample) bytes, 256-byte aligned
+ *                     (it holds a transposed copy of E and the tall fp32 factors); contents unspecified
+ *
+ * Constraints: N % 32 == 0, K % 32 == 0 (else SHAPE); power_iterations <= 64.  A matrix of rank below r yields
+ * zero columns / rows for the missing directions.  The workspace query returns 0 for sizes the call would refuse.
+ * Errors: INVALID_ARG, SHAPE, UNSUPPORTED, CAPACITY, HIP.
+ */
+size_t salr_residual_adapter_workspace_bytes(int64_t N, int64_t K, int64_t r, int64_t oversample);
+salr_status_t salr_residual_adapter(const uint16_t* e, int64_t N, int64_t K, int64_t r, int64_t oversample,
+                                    int64_t power_iterations, const float* omega, uint16_t* a_res, uint16_t* b_res,
+                                    float* sigma, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * salr_concat_adapters -- Sec. 3.2 ("Concatenating Multi-LoRA adapters"): A_cat = [A_1 ... A_n] side by side
  * and B_cat = [B_1; ...; B_n] stacked, so that (x A_cat) B_cat = sum_i (x A_i) B_i.
  *

@@ -62,6 +62,10 @@ def lib() -> ctypes.CDLL:
         L.salr_concat_adapters.restype = ctypes.c_int
         L.salr_concat_adapters.argtypes = [ctypes.POINTER(_vp), ctypes.POINTER(_vp), ctypes.POINTER(_i64), _i64, _i64, _i64,
                                            _vp, _vp, _vp]
+        L.salr_residual_adapter_workspace_bytes.restype = ctypes.c_size_t
+        L.salr_residual_adapter_workspace_bytes.argtypes = [_i64, _i64, _i64, _i64]
+        L.salr_residual_adapter.restype = ctypes.c_int
+        L.salr_residual_adapter.argtypes = [_vp, _i64, _i64, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
         L.salr_set_kernel_timing_events.restype = None
         L.salr_set_kernel_timing_events.argtypes = [_vp, _vp]
         _lib = L
@@ -245,6 +249,44 @@ def salr_concat_adapters(a_list: Sequence[torch.Tensor], b_list: Sequence[torch.
     rk = (_i64 * max(n, 1))(*ranks)
     _check(lib().salr_concat_adapters(pa, pb, rk, n, K, N, _ptr(a_cat, _BF16_TYPES, "a_cat"),
                                       _ptr(b_cat, _BF16_TYPES, "b_cat"), _stream(stream)), "salr_concat_adapters")
+
+
+def salr_residual_adapter_workspace_bytes(N: int, K: int, r: int, oversample: int) -> int:
+    return int(lib().salr_residual_adapter_workspace_bytes(N, K, r, oversample))
+
+
+def salr_residual_adapter(e: torch.Tensor, r: int, oversample: int, power_iterations: int, omega: torch.Tensor,
+                          a_res: torch.Tensor, b_res: torch.Tensor, sigma: Optional[torch.Tensor],
+                          workspace: torch.Tensor, stream=None) -> None:
+    """Enqueue the rank-r residual adapter of E [N, K]: a_res [K, r], b_res [r, N] (bf16), sigma [r] (fp32)."""
+    N, K = e.shape
+    if tuple(omega.shape) != (K, r + oversample) or omega.dtype != torch.float32 or not omega.is_contiguous():
+        raise ValueError("omega must be a contiguous fp32 [K, r + oversample] tensor")
+    if tuple(a_res.shape) != (K, r) or tuple(b_res.shape) != (r, N):
+        raise ValueError("a_res must be [K, r] and b_res [r, N]")
+    if sigma is not None and (sigma.dtype != torch.float32 or sigma.numel() != r):
+        raise ValueError("sigma must hold r fp32 values")
+    st = lib().salr_residual_adapter(_ptr(e, _BF16_TYPES, "e"), N, K, r, oversample, power_iterations,
+                                     _ptr(omega, (torch.float32,), "omega"), _ptr(a_res, _BF16_TYPES, "a_res"),
+                                     _ptr(b_res, _BF16_TYPES, "b_res"),
+                                     None if sigma is None else _ptr(sigma, (torch.float32,), "sigma"),
+                                     workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream(stream))
+    _check(st, "salr_residual_adapter")
+
+
+def residual_adapter(e: torch.Tensor, r: int, omega: torch.Tensor, power_iterations: int = 2):
+    """(a_res, b_res, sigma) with oversample = omega.shape[1] - r."""
+    N, K = e.shape
+    oversample = omega.shape[1] - r
+    need = salr_residual_adapter_workspace_bytes(N, K, r, oversample)
+    if need == 0:
+        raise ValueError("sizes not supported by salr_residual_adapter")
+    ws = torch.empty(need, dtype=torch.uint8, device=e.device)
+    a_res = torch.empty((K, r), dtype=e.dtype, device=e.device)
+    b_res = torch.empty((r, N), dtype=e.dtype, device=e.device)
+    sigma = torch.empty(r, dtype=torch.float32, device=e.device)
+    salr_residual_adapter(e, r, oversample, power_iterations, omega, a_res, b_res, sigma, ws)
+    return a_res, b_res, sigma
 
 
 def residual(w: torch.Tensor, w_hat: torch.Tensor) -> torch.Tensor:

@@ -15,12 +15,14 @@ namespace salr {
 // times the X requests and their L2 traffic, not X, sets the pace), the four waves walk the slice in step.
 // kRT rank tiles of 16 columns per pass over the slice (all of them in one pass up to rank 64); 16x16x32 bf16
 // MFMAs; with more than one slice the fp32 partial results go to partial[z] and splitk_reduce_kernel adds
-// them in a fixed order.  Padding columns come out as exact zeros.
+// them in a fixed order.  Padding columns come out as exact zeros.  keep_fp32: the caller wants the fp32 sums
+// (the subspace iteration of the residual adapter), so even a single slice goes to partial[0].
 // ---------------------------------------------------------------------------------------------------
 template <int kMB, int kRT, int kDepth>
 __global__ __launch_bounds__(256) void adapter_t_kernel(const uint16_t* __restrict__ x, int64_t M, int64_t K,
                                                         const uint16_t* __restrict__ a_t, int Rpad, int ksplit,
-                                                        uint16_t* __restrict__ t, float* __restrict__ partial) {
+                                                        uint16_t* __restrict__ t, float* __restrict__ partial,
+                                                        int keep_fp32) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int i16 = lane & 15, g = lane >> 4;
@@ -85,7 +87,7 @@ __global__ __launch_bounds__(256) void adapter_t_kernel(const uint16_t* __restri
                 for (int e = 0; e < 4; ++e) {
                     const int64_t m = m0 + 16 * mb + 4 * g + e;
                     if (m < M && r < Rpad) {
-                        if (ksplit == 1) t[m * Rpad + r] = f32_to_bf16_rne(acc[mb][rt][e]);
+                        if (ksplit == 1 && !keep_fp32) t[m * Rpad + r] = f32_to_bf16_rne(acc[mb][rt][e]);
                         else partial[((int64_t)z * M + m) * Rpad + r] = acc[mb][rt][e];
                     }
                 }
@@ -127,6 +129,22 @@ __global__ __launch_bounds__(256) void adapter_transpose_kernel(const uint16_t* 
     }
 }
 
+void launch_tall_product(const uint16_t* x, int64_t M, int64_t K, const uint16_t* a_t, int Rpad, int ksplit, uint16_t* t,
+                         float* partial, bool keep_fp32, hipStream_t stream) {
+    const int rows = adapter_rows_per_block(M);
+    const dim3 grid((unsigned)((M + rows - 1) / rows), (unsigned)ksplit);
+    const bool four = Rpad % 64 == 0;   // rank tiles per pass over the slice
+    const int keep = keep_fp32 ? 1 : 0;
+    if (rows == 256 && four)
+        hipLaunchKernelGGL((adapter_t_kernel<4, 4, 2>), grid, dim3(256), 0, stream, x, M, K, a_t, Rpad, ksplit, t, partial, keep);
+    else if (rows == 256)
+        hipLaunchKernelGGL((adapter_t_kernel<4, 2, 2>), grid, dim3(256), 0, stream, x, M, K, a_t, Rpad, ksplit, t, partial, keep);
+    else if (four)
+        hipLaunchKernelGGL((adapter_t_kernel<1, 4, 4>), grid, dim3(256), 0, stream, x, M, K, a_t, Rpad, ksplit, t, partial, keep);
+    else
+        hipLaunchKernelGGL((adapter_t_kernel<1, 2, 4>), grid, dim3(256), 0, stream, x, M, K, a_t, Rpad, ksplit, t, partial, keep);
+}
+
 void launch_adapter_t(const LinearArgs& a, hipStream_t stream) {
     const int R = (int)a.R, Rpad = (int)adapter_rank_padded(a.R);
     char* base = reinterpret_cast<char*>(a.t);
@@ -135,18 +153,7 @@ void launch_adapter_t(const LinearArgs& a, hipStream_t stream) {
     hipLaunchKernelGGL(adapter_transpose_kernel, dim3((unsigned)((a.K + 255) / 256), Rpad / 8), dim3(256), 0, stream, a.a_cat,
                        a.K, R, Rpad, a_t);
     const int ksplit = adapter_ksplit(a.M, a.K);
-    const int rows = adapter_rows_per_block(a.M);
-    const dim3 grid((unsigned)((a.M + rows - 1) / rows), (unsigned)ksplit);
-    const uint16_t* at = a_t;
-    const bool four = Rpad % 64 == 0;   // rank tiles per pass over the slice
-    if (rows == 256 && four)
-        hipLaunchKernelGGL((adapter_t_kernel<4, 4, 2>), grid, dim3(256), 0, stream, a.x, a.M, a.K, at, Rpad, ksplit, a.t, partial);
-    else if (rows == 256)
-        hipLaunchKernelGGL((adapter_t_kernel<4, 2, 2>), grid, dim3(256), 0, stream, a.x, a.M, a.K, at, Rpad, ksplit, a.t, partial);
-    else if (four)
-        hipLaunchKernelGGL((adapter_t_kernel<1, 4, 4>), grid, dim3(256), 0, stream, a.x, a.M, a.K, at, Rpad, ksplit, a.t, partial);
-    else
-        hipLaunchKernelGGL((adapter_t_kernel<1, 2, 4>), grid, dim3(256), 0, stream, a.x, a.M, a.K, at, Rpad, ksplit, a.t, partial);
+    launch_tall_product(a.x, a.M, a.K, a_t, Rpad, ksplit, a.t, partial, false, stream);
     if (ksplit > 1) launch_splitk_reduce(partial, a.M * Rpad, ksplit, a.t, stream);
 }
 

@@ -99,6 +99,28 @@ salr_status_t salr_concat_adapters(const uint16_t* const* a_list, const uint16_t
     return err == hipSuccess ? SALR_OK : SALR_ERR_HIP;
 }
 
+size_t salr_residual_adapter_workspace_bytes(int64_t N, int64_t K, int64_t r, int64_t oversample) {
+    if (N <= 0 || K <= 0 || r <= 0 || oversample < 0 || N % 32 != 0 || K % 32 != 0 || N > kMaxRows || K > kMaxRows) return 0;
+    if (r + oversample > salr::kSvdMaxColumns || r + oversample > (N < K ? N : K)) return 0;
+    return salr::residual_adapter_workspace_bytes(N, K, r + oversample);
+}
+
+salr_status_t salr_residual_adapter(const uint16_t* e, int64_t N, int64_t K, int64_t r, int64_t oversample,
+                                    int64_t power_iterations, const float* omega, uint16_t* a_res, uint16_t* b_res,
+                                    float* sigma, void* workspace, size_t workspace_bytes, void* stream) {
+    if (N < 0 || K < 0 || r < 0 || oversample < 0 || power_iterations < 0) return SALR_ERR_INVALID_ARG;
+    if (N == 0 || K == 0 || r == 0) return SALR_OK;
+    if (!e || !omega || !a_res || !b_res) return SALR_ERR_INVALID_ARG;
+    if (N % 32 != 0 || K % 32 != 0 || N > kMaxRows || K > kMaxRows) return SALR_ERR_SHAPE;
+    if (r + oversample > (N < K ? N : K)) return SALR_ERR_SHAPE;
+    if (r + oversample > salr::kSvdMaxColumns || power_iterations > 64) return SALR_ERR_UNSUPPORTED;
+    const size_t need = salr::residual_adapter_workspace_bytes(N, K, r + oversample);
+    if (!workspace || workspace_bytes < need) return SALR_ERR_CAPACITY;
+    hipError_t err = salr::launch_residual_adapter(e, N, K, r, r + oversample, power_iterations, omega, a_res, b_res, sigma,
+                                                   workspace, static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? SALR_OK : SALR_ERR_HIP;
+}
+
 size_t salr_linear_workspace_bytes(int64_t M, int64_t K, int64_t N, int64_t R) {
     if (M <= 0 || K < 0 || N <= 0 || R < 0 || R > kMaxRank || K % 32 != 0) return 0;
     return salr::linear_workspace_bytes(M, K, N, R);

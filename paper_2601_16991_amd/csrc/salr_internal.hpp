@@ -28,6 +28,13 @@ constexpr int kConcatBatch = 16;
 hipError_t launch_concat(const uint16_t* const* a_list, const uint16_t* const* b_list, const int64_t* ranks, int64_t n,
                          int64_t K, int64_t N, int64_t R, uint16_t* a_cat, uint16_t* b_cat, hipStream_t stream);
 
+// Residual adapter: rank-r factors of E [N, K] by subspace iteration with l = r + oversample columns (l <= 128)
+constexpr int64_t kSvdMaxColumns = 128;
+size_t residual_adapter_workspace_bytes(int64_t N, int64_t K, int64_t l);
+hipError_t launch_residual_adapter(const uint16_t* e, int64_t N, int64_t K, int64_t r, int64_t l, int64_t iterations,
+                                   const float* omega, uint16_t* a_res, uint16_t* b_res, float* sigma, void* workspace,
+                                   hipStream_t stream);
+
 // Columns of the bf16 workspace matrix T = X * A_cat: R rounded up to the MFMA k-step.
 inline int64_t adapter_rank_padded(int64_t R) { return (R + 31) / 32 * 32; }
 
@@ -128,6 +135,10 @@ hipError_t launch_linear_stream(const LinearArgs& args, hipStream_t stream, cons
 hipError_t launch_linear_twostage(const LinearArgs& args, hipStream_t stream, const TimingEvents& ev);
 // T = X * A_cat in bf16 [M, Rpad] at the start of the workspace (every path with M > kStreamMaxM)
 void launch_adapter_t(const LinearArgs& args, hipStream_t stream);
+// x [M, K] bf16 times the transpose of a_t [Rpad, K] bf16 (Rpad % 32 == 0, K % 32 == 0), K split over `ksplit`
+// slices: bf16 t [M, Rpad] (one slice, !keep_fp32) or fp32 partial [ksplit, M, Rpad]
+void launch_tall_product(const uint16_t* x, int64_t M, int64_t K, const uint16_t* a_t, int Rpad, int ksplit, uint16_t* t,
+                         float* partial, bool keep_fp32, hipStream_t stream);
 // out[i] = bf16(sum over z < ksplit of partial[z * count + i]); count % 4 == 0
 void launch_splitk_reduce(const float* partial, int64_t count, int ksplit, uint16_t* out, hipStream_t stream);
 

@@ -1,0 +1,425 @@
+// Residual adapter (paper Sec. 3.1, "Sparsity Preservation Pruning"): factors A_res [K, r], B_res [r, N] of the best
+// rank-r approximation of the residual E [N, K], so that (A_res B_res)^T ~ E_r.
+//
+// The paper asks for the truncated SVD of E and names no algorithm.  Here: randomized subspace iteration with a
+// caller-supplied Gaussian test matrix Omega [K, l], l = r + oversample (a published method: range finder with power
+// iterations, then the SVD of the small projected matrix).  With L = l rounded up to 16:
+//     Y = E Omega;  Q = orth(Y);   q times { Z = E^T Q;  Z = orth(Z);  Y = E Z;  Q = orth(Y) };   Z = E^T Q
+//     Z^T Z = U~ diag(s^2) U~^T  (l x l, Jacobi);   A_res = Z U~_r s_r^{-1/2},   B_res = s_r^{1/2} (Q U~_r)^T
+// (E ~ Q Q^T E = Q Z^T, and Z = V~ S U~^T gives E ~ (Q U~) S V~^T.)
+//
+// Kernels: the two big products stream E (or its transposed copy) once each through launch_tall_product, the MFMA
+// kernel of the adapter stage, with the fp32 matrix on the other side split into bf16 high and low parts (2 L
+// columns, added up again by fold_reduce_kernel); orth = CholeskyQR twice (gram_partial_kernel, chol_inverse_kernel,
+// apply_kernel); the l x l eigenproblem runs in one workgroup (eig_kernel).  Everything small is fp32.
+#include "salr_device.hpp"
+#include "salr_internal.hpp"
+#include "salr_linear_common.hpp"
+
+namespace salr {
+
+// out [C, R] = in [R, C]^T, bf16, 32 x 32 tiles through LDS
+__global__ __launch_bounds__(256) void transpose_bf16_kernel(const uint16_t* __restrict__ in, int64_t R, int64_t C,
+                                                             uint16_t* __restrict__ out) {
+    __shared__ uint16_t tile[32][33];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    const int64_t c0 = (int64_t)blockIdx.x * 32, r0 = (int64_t)blockIdx.y * 32;
+    for (int i = ty; i < 32; i += 8)
+        if (r0 + i < R && c0 + tx < C) tile[i][tx] = in[(r0 + i) * C + c0 + tx];
+    __syncthreads();
+    for (int i = ty; i < 32; i += 8)
+        if (c0 + i < C && r0 + tx < R) out[(c0 + i) * R + r0 + tx] = tile[tx][i];
+}
+
+// fp32 v = hi + lo with hi = bf16(v), lo = bf16(v - hi): 16 significant bits survive
+__device__ __forceinline__ void split_bf16(float v, uint16_t& hi, uint16_t& lo) {
+    hi = f32_to_bf16_rne(v);
+    lo = f32_to_bf16_rne(v - bf16_bits_to_f32(hi));
+}
+
+// in [rows, l] fp32 -> out_t [2 L, rows] bf16: row c = high parts of column c, row L + c = low parts; columns
+// l .. L - 1 are zero
+__global__ __launch_bounds__(256) void split_transpose_kernel(const float* __restrict__ in, int64_t rows, int l, int L,
+                                                              uint16_t* __restrict__ out_t) {
+    const int64_t row = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (row >= rows) return;
+    for (int c = 0; c < L; ++c) {
+        uint16_t hi = 0, lo = 0;
+        if (c < l) split_bf16(in[row * l + c], hi, lo);
+        out_t[(int64_t)c * rows + row] = hi;
+        out_t[(int64_t)(L + c) * rows + row] = lo;
+    }
+}
+
+// y [rows, L] = sum over slices z of (partial[z][row][j] + partial[z][row][L + j]), z ascending
+__global__ __launch_bounds__(256) void fold_reduce_kernel(const float* __restrict__ partial, int64_t rows, int L, int ksplit,
+                                                          float* __restrict__ y) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int quads = L / 4;
+    if (idx >= rows * quads) return;
+    const int64_t row = idx / quads;
+    const int j = (int)(idx % quads) * 4;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int z = 0; z < ksplit; ++z) {
+        const float* p = partial + ((int64_t)z * rows + row) * (2 * L);
+        const float4 a = *reinterpret_cast<const float4*>(p + j);
+        const float4 b = *reinterpret_cast<const float4*>(p + L + j);
+        s.x += a.x + b.x; s.y += a.y + b.y; s.z += a.z + b.z; s.w += a.w + b.w;
+    }
+    *reinterpret_cast<float4*>(y + row * L + j) = s;
+}
+
+// gp[b] = Y_b^T Y_b for the 256 rows of block b (L = 16 TL columns); thread (ti, tj) owns entries (ti + 16 u, tj + 16 v)
+template <int TL>
+__global__ __launch_bounds__(256) void gram_partial_kernel(const float* __restrict__ y, int64_t rows, float* __restrict__ gp) {
+    constexpr int L = 16 * TL;
+    __shared__ float ys[32][L + 4];
+    const int tid = threadIdx.x, ti = tid >> 4, tj = tid & 15;
+    float acc[TL][TL];
+#pragma unroll
+    for (int u = 0; u < TL; ++u)
+#pragma unroll
+        for (int v = 0; v < TL; ++v) acc[u][v] = 0.f;
+    const int64_t r_begin = (int64_t)blockIdx.x * 256;
+    const int64_t r_end = r_begin + 256 < rows ? r_begin + 256 : rows;
+    for (int64_t r0 = r_begin; r0 < r_end; r0 += 32) {
+        for (int i = tid; i < 32 * L; i += 256) {
+            const int rr = i / L, c = i % L;
+            ys[rr][c] = r0 + rr < r_end ? y[(r0 + rr) * L + c] : 0.f;
+        }
+        __syncthreads();
+        for (int rr = 0; rr < 32; ++rr) {
+            float a[TL], b[TL];
+#pragma unroll
+            for (int u = 0; u < TL; ++u) a[u] = ys[rr][ti + 16 * u];
+#pragma unroll
+            for (int v = 0; v < TL; ++v) b[v] = ys[rr][tj + 16 * v];
+#pragma unroll
+            for (int u = 0; u < TL; ++u)
+#pragma unroll
+                for (int v = 0; v < TL; ++v) acc[u][v] += a[u] * b[v];
+        }
+        __syncthreads();
+    }
+    float* g = gp + (int64_t)blockIdx.x * L * L;
+#pragma unroll
+    for (int u = 0; u < TL; ++u)
+#pragma unroll
+        for (int v = 0; v < TL; ++v) g[(ti + 16 * u) * L + tj + 16 * v] = acc[u][v];
+}
+
+// One workgroup: G = sum of the partial Gram matrices (block order), G = R^T R (Cholesky, R upper triangular),
+// rinv = R^{-1}, so that Y rinv has orthonormal columns.  A column whose pivot falls below kDropRel of its own
+// squared norm depends on the columns before it: it gets a zero column in rinv, i.e. it leaves the basis.
+constexpr float kDropRel = 3e-6f;
+template <int TL>
+__global__ __launch_bounds__(256) void chol_inverse_kernel(const float* __restrict__ gp, int nblocks, float* __restrict__ rinv) {
+    constexpr int L = 16 * TL;
+    __shared__ float g[L][L + 1];
+    __shared__ float x[L][L + 1];
+    __shared__ float diag0[L];
+    __shared__ int dropped[L];
+    __shared__ float pivot;
+    const int tid = threadIdx.x;
+    for (int idx = tid; idx < L * L; idx += 256) {
+        float s = 0.f;
+        for (int b = 0; b < nblocks; ++b) s += gp[(int64_t)b * L * L + idx];
+        g[idx / L][idx % L] = s;
+    }
+    __syncthreads();
+    if (tid < L) diag0[tid] = g[tid][tid];
+    __syncthreads();
+    for (int c = 0; c < L; ++c) {
+        if (tid == 0) {
+            const float d = g[c][c];
+            const bool ok = d > kDropRel * diag0[c] && d > 0.f;
+            pivot = ok ? sqrtf(d) : 0.f;
+            dropped[c] = ok ? 0 : 1;
+            g[c][c] = ok ? pivot : 1.f;
+        }
+        __syncthreads();
+        const float piv = pivot;
+        for (int j = c + 1 + tid; j < L; j += 256) g[c][j] = piv > 0.f ? g[c][j] / piv : 0.f;
+        __syncthreads();
+        const int rem = L - c - 1;
+        for (int idx = tid; idx < rem * rem; idx += 256) {
+            const int i = c + 1 + idx / rem, j = c + 1 + idx % rem;
+            if (j >= i) g[i][j] -= g[c][i] * g[c][j];
+        }
+        __syncthreads();
+    }
+    // column j of X = R^{-1} by back substitution, one thread per column
+    if (tid < L) {
+        const int j = tid;
+        for (int i = L - 1; i > j; --i) x[i][j] = 0.f;
+        if (dropped[j]) {
+            for (int i = j; i >= 0; --i) x[i][j] = 0.f;
+        } else {
+            x[j][j] = 1.f / g[j][j];
+            for (int i = j - 1; i >= 0; --i) {
+                float s = 0.f;
+                for (int p = i + 1; p <= j; ++p) s += g[i][p] * x[p][j];
+                x[i][j] = -s / g[i][i];
+            }
+        }
+    }
+    __syncthreads();
+    for (int idx = tid; idx < L * L; idx += 256) rinv[idx] = x[idx / L][idx % L];
+}
+
+// out = in [rows, L] * m [L, L] for 64 rows per workgroup; thread (tr, tc) owns rows 4 tr .. + 3, columns tc + 16 u.
+//   mode 0: out32 [rows, L] fp32 (may be `in`: a workgroup reads its rows before it writes them) and
+//           out16 [2 L, pitch] bf16 = the transposed high and low parts (the other side of the next product)
+//   mode 1: out16 [rows, ncols] bf16                      mode 2: out16 [ncols, pitch] bf16, transposed
+// rows % 4 == 0 and pitch % 4 == 0 (the transposed stores are 8 bytes wide).
+template <int TL>
+__global__ __launch_bounds__(256) void apply_kernel(const float* in, int64_t rows, const float* __restrict__ m, int mode,
+                                                    int ncols, float* out32, uint16_t* __restrict__ out16, int64_t pitch) {
+    constexpr int L = 16 * TL;
+    __shared__ float ms[L][L];
+    __shared__ float ins[64][L + 1];
+    const int tid = threadIdx.x, tr = tid >> 4, tc = tid & 15;
+    const int64_t r0 = (int64_t)blockIdx.x * 64;
+    for (int idx = tid; idx < L * L; idx += 256) ms[idx / L][idx % L] = m[idx];
+    for (int idx = tid; idx < 64 * L; idx += 256) {
+        const int rr = idx / L, c = idx % L;
+        ins[rr][c] = r0 + rr < rows ? in[(r0 + rr) * L + c] : 0.f;
+    }
+    __syncthreads();
+    float acc[4][TL];
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int u = 0; u < TL; ++u) acc[q][u] = 0.f;
+    for (int p = 0; p < L; ++p) {
+        float a[4], b[TL];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) a[q] = ins[4 * tr + q][p];
+#pragma unroll
+        for (int u = 0; u < TL; ++u) b[u] = ms[p][tc + 16 * u];
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int u = 0; u < TL; ++u) acc[q][u] += a[q] * b[u];
+    }
+    const int64_t row = r0 + 4 * tr;   // rows % 4 == 0: the thread's four rows are all inside or all outside
+    if (row >= rows) return;
+#pragma unroll
+    for (int u = 0; u < TL; ++u) {
+        const int c = tc + 16 * u;
+        if (mode == 0) {
+            uint16_t hi[4], lo[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                out32[(row + q) * L + c] = acc[q][u];
+                split_bf16(acc[q][u], hi[q], lo[q]);
+            }
+            *reinterpret_cast<uint2*>(out16 + (int64_t)c * pitch + row) =
+                make_uint2(hi[0] | ((uint32_t)hi[1] << 16), hi[2] | ((uint32_t)hi[3] << 16));
+            *reinterpret_cast<uint2*>(out16 + (int64_t)(L + c) * pitch + row) =
+                make_uint2(lo[0] | ((uint32_t)lo[1] << 16), lo[2] | ((uint32_t)lo[3] << 16));
+        } else if (c < ncols) {
+            uint16_t h[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) h[q] = f32_to_bf16_rne(acc[q][u]);
+            if (mode == 1) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) out16[(row + q) * ncols + c] = h[q];
+            } else {
+                *reinterpret_cast<uint2*>(out16 + (int64_t)c * pitch + row) =
+                    make_uint2(h[0] | ((uint32_t)h[1] << 16), h[2] | ((uint32_t)h[3] << 16));
+            }
+        }
+    }
+}
+
+// One workgroup: G = sum of partial Gram matrices of Z (= Z^T Z, symmetric l x l), G = U~ diag(lambda) U~^T by
+// cyclic Jacobi with the L / 2 disjoint rotations of a round-robin round applied together, eigenvalues ranked in
+// descending order; then  ma[:, k] = u_k lambda_k^{-1/4},  mb[:, k] = u_k lambda_k^{1/4}  for the r largest (other
+// columns zero) and sigma[k] = sqrt(lambda_k).
+constexpr int kJacobiSweeps = 10;
+template <int TL>
+__global__ __launch_bounds__(256) void eig_kernel(const float* __restrict__ gp, int nblocks, int r, float* __restrict__ ma,
+                                                  float* __restrict__ mb, float* __restrict__ sigma) {
+    constexpr int L = 16 * TL, H = L / 2;
+    __shared__ float a[L][L + 1];
+    __shared__ float v[L][L + 1];
+    __shared__ float rot[H][2];
+    __shared__ int pair[H][2];
+    __shared__ float lam[L];
+    __shared__ int order[L];
+    const int tid = threadIdx.x;
+    for (int idx = tid; idx < L * L; idx += 256) {
+        float s = 0.f;
+        for (int b = 0; b < nblocks; ++b) s += gp[(int64_t)b * L * L + idx];
+        a[idx / L][idx % L] = s;
+        v[idx / L][idx % L] = idx / L == idx % L ? 1.f : 0.f;
+    }
+    __syncthreads();
+    for (int sweep = 0; sweep < kJacobiSweeps; ++sweep) {
+        for (int t = 0; t < L - 1; ++t) {
+            if (tid < H) {   // round t of the round-robin schedule: index L - 1 stays put, the others turn
+                int p = tid == 0 ? L - 1 : (t + tid) % (L - 1);
+                int q = tid == 0 ? t : (t - tid + (L - 1)) % (L - 1);
+                if (p > q) { const int s = p; p = q; q = s; }
+                const float app = a[p][p], aqq = a[q][q], apq = a[p][q];
+                float c = 1.f, s = 0.f;
+                if (fabsf(apq) > 1e-30f) {
+                    const float theta = (aqq - app) / (2.f * apq);
+                    const float tt = copysignf(1.f, theta) / (fabsf(theta) + sqrtf(1.f + theta * theta));
+                    c = 1.f / sqrtf(1.f + tt * tt);
+                    s = tt * c;
+                }
+                pair[tid][0] = p; pair[tid][1] = q;
+                rot[tid][0] = c; rot[tid][1] = s;
+            }
+            __syncthreads();
+            for (int idx = tid; idx < H * L; idx += 256) {   // columns p, q of a and of v
+                const int pr = idx / L, k = idx % L;
+                const int p = pair[pr][0], q = pair[pr][1];
+                const float c = rot[pr][0], s = rot[pr][1];
+                const float ap = a[k][p], aq = a[k][q];
+                a[k][p] = c * ap - s * aq;
+                a[k][q] = s * ap + c * aq;
+                const float vp = v[k][p], vq = v[k][q];
+                v[k][p] = c * vp - s * vq;
+                v[k][q] = s * vp + c * vq;
+            }
+            __syncthreads();
+            for (int idx = tid; idx < H * L; idx += 256) {   // rows p, q of a
+                const int pr = idx / L, k = idx % L;
+                const int p = pair[pr][0], q = pair[pr][1];
+                const float c = rot[pr][0], s = rot[pr][1];
+                const float ap = a[p][k], aq = a[q][k];
+                a[p][k] = c * ap - s * aq;
+                a[q][k] = s * ap + c * aq;
+            }
+            __syncthreads();
+        }
+    }
+    if (tid < L) lam[tid] = a[tid][tid] > 0.f ? a[tid][tid] : 0.f;
+    __syncthreads();
+    if (tid < L) {
+        int rk = 0;
+        for (int j = 0; j < L; ++j) rk += (lam[j] > lam[tid] || (lam[j] == lam[tid] && j < tid)) ? 1 : 0;
+        order[tid] = rk;
+    }
+    __syncthreads();
+    float lmax = 0.f;
+    for (int j = 0; j < L; ++j) lmax = lam[j] > lmax ? lam[j] : lmax;
+    for (int idx = tid; idx < L * L; idx += 256) {
+        const int p = idx / L, i = idx % L;
+        const int rk = order[i];
+        float fa = 0.f, fb = 0.f;
+        if (rk < r && lam[i] > 1e-12f * lmax) {
+            fb = sqrtf(sqrtf(lam[i]));
+            fa = 1.f / fb;
+        }
+        ma[p * L + rk] = v[p][i] * fa;
+        mb[p * L + rk] = v[p][i] * fb;
+    }
+    if (sigma != nullptr && tid < L && order[tid] < r) sigma[order[tid]] = sqrtf(lam[tid]);
+}
+
+// ---------------------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------------------
+struct SvdPlan {
+    int L, ks_n, ks_k, gram_blocks;
+    size_t off_et, off_y, off_z, off_bt, off_partial, off_gp, off_small, total;
+};
+
+static SvdPlan svd_plan(int64_t N, int64_t K, int64_t l) {
+    SvdPlan p;
+    p.L = (int)((l + 15) / 16 * 16);
+    p.ks_n = adapter_ksplit(N, K);   // rows N, contraction over K
+    p.ks_k = adapter_ksplit(K, N);   // rows K, contraction over N
+    const int64_t big = N > K ? N : K;
+    p.gram_blocks = (int)((big + 255) / 256);
+    size_t o = 0;
+    p.off_et = o; o += round_up_256((size_t)N * K * sizeof(uint16_t));
+    p.off_y = o; o += round_up_256((size_t)N * p.L * sizeof(float));
+    p.off_z = o; o += round_up_256((size_t)K * p.L * sizeof(float));
+    p.off_bt = o; o += round_up_256((size_t)2 * p.L * big * sizeof(uint16_t));
+    const size_t pn = (size_t)p.ks_n * N, pk = (size_t)p.ks_k * K;
+    p.off_partial = o; o += round_up_256((pn > pk ? pn : pk) * 2 * p.L * sizeof(float));
+    p.off_gp = o; o += round_up_256((size_t)p.gram_blocks * p.L * p.L * sizeof(float));
+    p.off_small = o; o += round_up_256((size_t)2 * p.L * p.L * sizeof(float));
+    p.total = o;
+    return p;
+}
+
+size_t residual_adapter_workspace_bytes(int64_t N, int64_t K, int64_t l) { return svd_plan(N, K, l).total; }
+
+template <int TL>
+static void run_svd(const uint16_t* e, int64_t N, int64_t K, int r, int l, int iterations, const float* omega,
+                    uint16_t* a_res, uint16_t* b_res, float* sigma, char* ws, const SvdPlan& p, hipStream_t stream) {
+    constexpr int L = 16 * TL;
+    uint16_t* et = reinterpret_cast<uint16_t*>(ws + p.off_et);
+    float* y = reinterpret_cast<float*>(ws + p.off_y);
+    float* z = reinterpret_cast<float*>(ws + p.off_z);
+    uint16_t* bt = reinterpret_cast<uint16_t*>(ws + p.off_bt);
+    float* partial = reinterpret_cast<float*>(ws + p.off_partial);
+    float* gp = reinterpret_cast<float*>(ws + p.off_gp);
+    float* small_a = reinterpret_cast<float*>(ws + p.off_small);
+    float* small_b = small_a + L * L;
+
+    auto product = [&](const uint16_t* mat, int64_t rows, int64_t cols, int ks, float* out) {   // out = mat * (bt as fp32)^T
+        launch_tall_product(mat, rows, cols, bt, 2 * L, ks, nullptr, partial, true, stream);
+        hipLaunchKernelGGL(fold_reduce_kernel, dim3((unsigned)((rows * (L / 4) + 255) / 256)), dim3(256), 0, stream, partial, rows,
+                           L, ks, out);
+    };
+    auto gram = [&](const float* buf, int64_t rows) -> int {
+        const int nb = (int)((rows + 255) / 256);
+        hipLaunchKernelGGL((gram_partial_kernel<TL>), dim3(nb), dim3(256), 0, stream, buf, rows, gp);
+        return nb;
+    };
+    auto orth = [&](float* buf, int64_t rows) {   // CholeskyQR, twice; leaves the transposed split copy in bt
+        for (int pass = 0; pass < 2; ++pass) {
+            const int nb = gram(buf, rows);
+            hipLaunchKernelGGL((chol_inverse_kernel<TL>), dim3(1), dim3(256), 0, stream, gp, nb, small_a);
+            hipLaunchKernelGGL((apply_kernel<TL>), dim3((unsigned)((rows + 63) / 64)), dim3(256), 0, stream, buf, rows, small_a, 0,
+                               L, buf, bt, rows);
+        }
+    };
+
+    hipLaunchKernelGGL(transpose_bf16_kernel, dim3((unsigned)((K + 31) / 32), (unsigned)((N + 31) / 32)), dim3(256), 0, stream, e, N,
+                       K, et);
+    hipLaunchKernelGGL(split_transpose_kernel, dim3((unsigned)((K + 255) / 256)), dim3(256), 0, stream, omega, K, l, L, bt);
+    product(e, N, K, p.ks_n, y);          // Y = E Omega
+    orth(y, N);                           // Q
+    product(et, K, N, p.ks_k, z);         // Z = E^T Q
+    for (int it = 0; it < iterations; ++it) {
+        orth(z, K);
+        product(e, N, K, p.ks_n, y);
+        orth(y, N);
+        product(et, K, N, p.ks_k, z);
+    }
+    const int nb = gram(z, K);
+    hipLaunchKernelGGL((eig_kernel<TL>), dim3(1), dim3(256), 0, stream, gp, nb, r, small_a, small_b, sigma);
+    hipLaunchKernelGGL((apply_kernel<TL>), dim3((unsigned)((K + 63) / 64)), dim3(256), 0, stream, z, K, small_a, 1, r,
+                       (float*)nullptr, a_res, (int64_t)r);
+    hipLaunchKernelGGL((apply_kernel<TL>), dim3((unsigned)((N + 63) / 64)), dim3(256), 0, stream, y, N, small_b, 2, r,
+                       (float*)nullptr, b_res, N);
+}
+
+hipError_t launch_residual_adapter(const uint16_t* e, int64_t N, int64_t K, int64_t r, int64_t l, int64_t iterations,
+                                   const float* omega, uint16_t* a_res, uint16_t* b_res, float* sigma, void* workspace,
+                                   hipStream_t stream) {
+    const SvdPlan p = svd_plan(N, K, l);
+    char* ws = static_cast<char*>(workspace);
+    switch (p.L / 16) {
+        case 1: run_svd<1>(e, N, K, (int)r, (int)l, (int)iterations, omega, a_res, b_res, sigma, ws, p, stream); break;
+        case 2: run_svd<2>(e, N, K, (int)r, (int)l, (int)iterations, omega, a_res, b_res, sigma, ws, p, stream); break;
+        case 3: run_svd<3>(e, N, K, (int)r, (int)l, (int)iterations, omega, a_res, b_res, sigma, ws, p, stream); break;
+        case 4: run_svd<4>(e, N, K, (int)r, (int)l, (int)iterations, omega, a_res, b_res, sigma, ws, p, stream); break;
+        case 5: run_svd<5>(e, N, K, (int)r, (int)l, (int)iterations, omega, a_res, b_res, sigma, ws, p, stream); break;
+        case 6: run_svd<6>(e, N, K, (int)r, (int)l, (int)iterations, omega, a_res, b_res, sigma, ws, p, stream); break;
+        case 7: run_svd<7>(e, N, K, (int)r, (int)l, (int)iterations, omega, a_res, b_res, sigma, ws, p, stream); break;
+        case 8: run_svd<8>(e, N, K, (int)r, (int)l, (int)iterations, omega, a_res, b_res, sigma, ws, p, stream); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace salr

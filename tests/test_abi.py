@@ -151,3 +151,45 @@ def test_host_validation_rejects_before_launch(lib):
     assert lib.salr_magnitude_mask_nm(fake, 4, 128, 2, 128, fake, None) == salr.SALR_ERR_UNSUPPORTED
     assert lib.salr_magnitude_mask_nm(fake, 4, 8, 2, 4, None, None) == salr.SALR_ERR_INVALID_ARG
     assert lib.salr_magnitude_mask_nm(fake, 0, 8, 2, 4, fake, None) == salr.SALR_OK
+
+
+def test_residual_adapter_validation_and_workspace(lib):
+    import paper_2601_16991_amd as salr
+    fake = 0x1000  # never dereferenced: every call below fails validation first
+    q = lib.salr_residual_adapter_workspace_bytes
+    assert q(4096, 4096, 32, 16) > 4096 * 4096 * 2          # holds at least the transposed copy of E
+    assert q(4096, 4096, 32, 16) % 256 == 0
+    assert q(4096, 4100, 32, 16) == 0 and q(4096, 4096, 120, 16) == 0 and q(64, 64, 60, 8) == 0 and q(0, 64, 4, 4) == 0
+
+    def call(N=64, K=96, r=8, over=8, iters=1, e=fake, omega=fake, a=fake, b=fake, ws=fake, ws_bytes=1 << 30):
+        return lib.salr_residual_adapter(e, N, K, r, over, iters, omega, a, b, None, ws, ws_bytes, None)
+
+    assert call(N=-1) == salr.SALR_ERR_INVALID_ARG
+    assert call(e=None) == salr.SALR_ERR_INVALID_ARG
+    assert call(omega=None) == salr.SALR_ERR_INVALID_ARG
+    assert call(K=100) == salr.SALR_ERR_SHAPE
+    assert call(r=60, over=8) == salr.SALR_ERR_SHAPE            # more sketch columns than min(N, K)
+    assert call(N=256, K=256, r=120, over=16) == salr.SALR_ERR_UNSUPPORTED
+    assert call(iters=65) == salr.SALR_ERR_UNSUPPORTED
+    assert call(ws=None) == salr.SALR_ERR_CAPACITY
+    assert call(ws_bytes=1024) == salr.SALR_ERR_CAPACITY
+    assert call(r=0) == salr.SALR_OK and call(N=0) == salr.SALR_OK   # nothing to do
+
+
+def test_residual_and_concat_validation(lib):
+    import ctypes
+    import paper_2601_16991_amd as salr
+    fake = 0x1000
+    assert lib.salr_residual(fake, fake, -1, 4, fake, None) == salr.SALR_ERR_INVALID_ARG
+    assert lib.salr_residual(None, fake, 4, 4, fake, None) == salr.SALR_ERR_INVALID_ARG
+    assert lib.salr_residual(None, None, 0, 4, None, None) == salr.SALR_OK
+    ptrs = (ctypes.c_void_p * 2)(fake, fake)
+    nulls = (ctypes.c_void_p * 2)(fake, None)
+    ranks = (ctypes.c_int64 * 2)(4, 4)
+    bad = (ctypes.c_int64 * 2)(4, -1)
+    big = (ctypes.c_int64 * 2)(40000, 40000)
+    assert lib.salr_concat_adapters(ptrs, ptrs, bad, 2, 8, 8, fake, fake, None) == salr.SALR_ERR_INVALID_ARG
+    assert lib.salr_concat_adapters(nulls, ptrs, ranks, 2, 8, 8, fake, fake, None) == salr.SALR_ERR_INVALID_ARG
+    assert lib.salr_concat_adapters(ptrs, ptrs, ranks, 2, 8, 8, None, fake, None) == salr.SALR_ERR_INVALID_ARG
+    assert lib.salr_concat_adapters(ptrs, ptrs, big, 2, 8, 8, fake, fake, None) == salr.SALR_ERR_SHAPE
+    assert lib.salr_concat_adapters(None, None, None, 0, 8, 8, None, None, None) == salr.SALR_OK
