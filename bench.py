@@ -215,6 +215,45 @@ def time_codec(layer, steps):
     return res
 
 
+def time_prepare(layer, steps):
+    """Model-preparation steps on the bench layer: residual, adapter concatenation, residual adapter (rank 32, 16
+    extra sketch columns, 2 power iterations: 6 passes over E, each 2 N K bytes, plus one transposed copy)."""
+    import numpy as np
+    import torch
+    import paper_2601_16991_amd as salr
+    cfg = layer.cfg
+    dev = layer.w_hat.device
+    import salr_workloads as wl
+    w = torch.from_numpy(wl.dense_weight(cfg).view(np.int16)).to(dev)
+    e = torch.empty_like(w)
+    r, over, iters = 32, 16, 2
+    omega = torch.from_numpy(np.random.default_rng(1).standard_normal((cfg.K, r + over)).astype(np.float32)).to(dev)
+    ws = torch.empty(salr.salr_residual_adapter_workspace_bytes(cfg.N, cfg.K, r, over), dtype=torch.uint8, device=dev)
+    a_res = torch.empty((cfg.K, r), dtype=torch.int16, device=dev)
+    b_res = torch.empty((r, cfg.N), dtype=torch.int16, device=dev)
+    sigma = torch.empty(r, dtype=torch.float32, device=dev)
+    a_cat = torch.empty((cfg.K, layer.R + r), dtype=torch.int16, device=dev)
+    b_cat = torch.empty((layer.R + r, cfg.N), dtype=torch.int16, device=dev)
+    res = {}
+    nk = cfg.N * cfg.K
+    for name, nbytes, fn in (
+            ("residual", 6 * nk, lambda: salr.salr_residual(w, layer.w_hat, e)),
+            ("concat_adapters", 4 * (layer.R + r) * (cfg.K + cfg.N),
+             lambda: salr.salr_concat_adapters([layer.a_cat, a_res], [layer.b_cat, b_res], a_cat, b_cat)),
+            ("residual_adapter_r32", (2 * iters + 2) * 2 * nk + 4 * nk,
+             lambda: salr.salr_residual_adapter(e, r, over, iters, omega, a_res, b_res, sigma, ws))):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        res[name] = {"ms": round(ms, 4), "GB/s": round(nbytes / ms / 1e6, 1)}
+    return res
+
+
 def cpu_baseline(cfg, permille, M, alg_bytes, budget_s=10.0, max_reps=50):
     import numpy as np
     import oracle
@@ -377,6 +416,8 @@ def main():
         del layer24
         extras["codec_" + cfg.name] = time_codec(layer, 20)
         log("codec:", extras["codec_" + cfg.name])
+        extras["prepare_" + cfg.name] = time_prepare(layer, 10)
+        log("prepare:", extras["prepare_" + cfg.name])
         del layer
         torch.cuda.empty_cache()
         # prefill-sized, MFMA-bound layers: decode stage + T + dense MFMA stage per call (wall), and the MFMA stage alone

@@ -13,7 +13,7 @@ namespace salr {
 // else is large), so the grid is made wide: workgroup (b, z) = 64 kMB rows of X times slice z of K, wave w owns
 // 16 kMB of the rows (each a_t operand it loads is used for kMB row blocks: at kMB = 1 the a_t requests are kRT
 // times the X requests and their L2 traffic, not X, sets the pace), the four waves walk the slice in step.
-// kRT rank tiles of 16 columns per pass over the slice (all of them in one pass up to rank 64); 16x16x32 bf16
+// kRT rank tiles of 16 columns per pass over the slice (all of them in one pass up to rank 128); 16x16x32 bf16
 // MFMAs; with more than one slice the fp32 partial results go to partial[z] and splitk_reduce_kernel adds
 // them in a fixed order.  Padding columns come out as exact zeros.  keep_fp32: the caller wants the fp32 sums
 // (the subspace iteration of the residual adapter), so even a single slice goes to partial[0].
@@ -41,7 +41,7 @@ __global__ __launch_bounds__(256) void adapter_t_kernel(const uint16_t* __restri
         xrow[mb] = x + (mrow < M ? mrow : M - 1) * K + 8 * g;
     }
     for (int rb = 0; rb < Rpad; rb += 16 * kRT) {
-        // Rpad is a multiple of 32 and kRT of 2, so a pass never starts past the end; tiles past it are clamped
+        // a pass starts inside the Rpad columns (loop bound); tiles of it that lie past them are clamped, not stored
         const uint16_t* arow[kRT];
 #pragma unroll
         for (int rt = 0; rt < kRT; ++rt) {
@@ -129,20 +129,31 @@ __global__ __launch_bounds__(256) void adapter_transpose_kernel(const uint16_t* 
     }
 }
 
+template <int kMB, int kDepth>
+static void launch_tall_product_rt(int rank_tiles, dim3 grid, hipStream_t stream, const uint16_t* x, int64_t M, int64_t K,
+                                   const uint16_t* a_t, int Rpad, int ksplit, uint16_t* t, float* partial, int keep) {
+    switch (rank_tiles) {
+#define SALR_CASE(RT)                                                                                                   \
+    case RT:                                                                                                            \
+        hipLaunchKernelGGL((adapter_t_kernel<kMB, RT, kDepth>), grid, dim3(256), 0, stream, x, M, K, a_t, Rpad, ksplit, t, \
+                           partial, keep);                                                                              \
+        break;
+        SALR_CASE(2) SALR_CASE(3) SALR_CASE(4) SALR_CASE(5) SALR_CASE(6) SALR_CASE(7) SALR_CASE(8)
+#undef SALR_CASE
+        default: break;
+    }
+}
+
 void launch_tall_product(const uint16_t* x, int64_t M, int64_t K, const uint16_t* a_t, int Rpad, int ksplit, uint16_t* t,
                          float* partial, bool keep_fp32, hipStream_t stream) {
     const int rows = adapter_rows_per_block(M);
     const dim3 grid((unsigned)((M + rows - 1) / rows), (unsigned)ksplit);
-    const bool four = Rpad % 64 == 0;   // rank tiles per pass over the slice
+    // rank tiles of 16 columns per pass over the slice: as few passes as eight tiles at a time allow, evenly filled
+    const int tiles = Rpad / 16, passes = (tiles + 7) / 8;
+    const int rank_tiles = (tiles + passes - 1) / passes;
     const int keep = keep_fp32 ? 1 : 0;
-    if (rows == 256 && four)
-        hipLaunchKernelGGL((adapter_t_kernel<4, 4, 2>), grid, dim3(256), 0, stream, x, M, K, a_t, Rpad, ksplit, t, partial, keep);
-    else if (rows == 256)
-        hipLaunchKernelGGL((adapter_t_kernel<4, 2, 2>), grid, dim3(256), 0, stream, x, M, K, a_t, Rpad, ksplit, t, partial, keep);
-    else if (four)
-        hipLaunchKernelGGL((adapter_t_kernel<1, 4, 4>), grid, dim3(256), 0, stream, x, M, K, a_t, Rpad, ksplit, t, partial, keep);
-    else
-        hipLaunchKernelGGL((adapter_t_kernel<1, 2, 4>), grid, dim3(256), 0, stream, x, M, K, a_t, Rpad, ksplit, t, partial, keep);
+    if (rows == 256) launch_tall_product_rt<4, 2>(rank_tiles, grid, stream, x, M, K, a_t, Rpad, ksplit, t, partial, keep);
+    else launch_tall_product_rt<1, 4>(rank_tiles, grid, stream, x, M, K, a_t, Rpad, ksplit, t, partial, keep);
 }
 
 void launch_adapter_t(const LinearArgs& a, hipStream_t stream) {

@@ -69,7 +69,8 @@ __global__ __launch_bounds__(256) void fold_reduce_kernel(const float* __restric
     *reinterpret_cast<float4*>(y + row * L + j) = s;
 }
 
-// gp[b] = Y_b^T Y_b for the 256 rows of block b (L = 16 TL columns); thread (ti, tj) owns entries (ti + 16 u, tj + 16 v)
+// gp[b] = Y_b^T Y_b for the kGramRows rows of block b (L = 16 TL columns); thread (ti, tj) owns entries (ti + 16 u, tj + 16 v)
+constexpr int kGramRows = 128;
 template <int TL>
 __global__ __launch_bounds__(256) void gram_partial_kernel(const float* __restrict__ y, int64_t rows, float* __restrict__ gp) {
     constexpr int L = 16 * TL;
@@ -80,8 +81,8 @@ __global__ __launch_bounds__(256) void gram_partial_kernel(const float* __restri
     for (int u = 0; u < TL; ++u)
 #pragma unroll
         for (int v = 0; v < TL; ++v) acc[u][v] = 0.f;
-    const int64_t r_begin = (int64_t)blockIdx.x * 256;
-    const int64_t r_end = r_begin + 256 < rows ? r_begin + 256 : rows;
+    const int64_t r_begin = (int64_t)blockIdx.x * kGramRows;
+    const int64_t r_end = r_begin + kGramRows < rows ? r_begin + kGramRows : rows;
     for (int64_t r0 = r_begin; r0 < r_end; r0 += 32) {
         for (int i = tid; i < 32 * L; i += 256) {
             const int rr = i / L, c = i % L;
@@ -108,62 +109,106 @@ __global__ __launch_bounds__(256) void gram_partial_kernel(const float* __restri
         for (int v = 0; v < TL; ++v) g[(ti + 16 * u) * L + tj + 16 * v] = acc[u][v];
 }
 
-// One workgroup: G = sum of the partial Gram matrices (block order), G = R^T R (Cholesky, R upper triangular),
+// g = sum of the partial Gram matrices in block order, one thread per entry (the loads of a thread are independent,
+// so they overlap; inside the one-workgroup kernels below the same sum would be a chain of round trips)
+__global__ __launch_bounds__(256) void gram_reduce_kernel(const float* __restrict__ gp, int nblocks, int count,
+                                                          float* __restrict__ g) {
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx >= count) return;
+    float s = 0.f;
+    int b = 0;
+    for (; b + 8 <= nblocks; b += 8) {
+        float t[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) t[u] = gp[(int64_t)(b + u) * count + idx];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += t[u];
+    }
+    for (; b < nblocks; ++b) s += gp[(int64_t)b * count + idx];
+    g[idx] = s;
+}
+
+// One workgroup: G (the summed Gram matrix) = R^T R (Cholesky, R upper triangular),
 // rinv = R^{-1}, so that Y rinv has orthonormal columns.  A column whose pivot falls below kDropRel of its own
 // squared norm depends on the columns before it: it gets a zero column in rinv, i.e. it leaves the basis.
 constexpr float kDropRel = 3e-6f;
 template <int TL>
-__global__ __launch_bounds__(256) void chol_inverse_kernel(const float* __restrict__ gp, int nblocks, float* __restrict__ rinv) {
+__global__ __launch_bounds__(256) void chol_inverse_kernel(const float* __restrict__ gsum, float* __restrict__ rinv) {
     constexpr int L = 16 * TL;
     __shared__ float g[L][L + 1];
     __shared__ float x[L][L + 1];
     __shared__ float diag0[L];
     __shared__ int dropped[L];
-    __shared__ float pivot;
     const int tid = threadIdx.x;
-    for (int idx = tid; idx < L * L; idx += 256) {
-        float s = 0.f;
-        for (int b = 0; b < nblocks; ++b) s += gp[(int64_t)b * L * L + idx];
-        g[idx / L][idx % L] = s;
-    }
+    for (int idx = tid; idx < L * L; idx += 256) g[idx / L][idx % L] = gsum[idx];
     __syncthreads();
     if (tid < L) diag0[tid] = g[tid][tid];
     __syncthreads();
-    for (int c = 0; c < L; ++c) {
-        if (tid == 0) {
+    // Right-looking elimination on the raw rows: step c subtracts g[c][i] g[c][j] / g[c][c] from the trailing part
+    // and leaves row c alone, so one barrier per step is enough; the rows are scaled to R afterwards.
+    {
+        const int ti = tid >> 4, tj = tid & 15;
+        for (int c = 0; c < L; ++c) {
             const float d = g[c][c];
-            const bool ok = d > kDropRel * diag0[c] && d > 0.f;
-            pivot = ok ? sqrtf(d) : 0.f;
-            dropped[c] = ok ? 0 : 1;
-            g[c][c] = ok ? pivot : 1.f;
-        }
-        __syncthreads();
-        const float piv = pivot;
-        for (int j = c + 1 + tid; j < L; j += 256) g[c][j] = piv > 0.f ? g[c][j] / piv : 0.f;
-        __syncthreads();
-        const int rem = L - c - 1;
-        for (int idx = tid; idx < rem * rem; idx += 256) {
-            const int i = c + 1 + idx / rem, j = c + 1 + idx % rem;
-            if (j >= i) g[i][j] -= g[c][i] * g[c][j];
-        }
-        __syncthreads();
-    }
-    // column j of X = R^{-1} by back substitution, one thread per column
-    if (tid < L) {
-        const int j = tid;
-        for (int i = L - 1; i > j; --i) x[i][j] = 0.f;
-        if (dropped[j]) {
-            for (int i = j; i >= 0; --i) x[i][j] = 0.f;
-        } else {
-            x[j][j] = 1.f / g[j][j];
-            for (int i = j - 1; i >= 0; --i) {
-                float s = 0.f;
-                for (int p = i + 1; p <= j; ++p) s += g[i][p] * x[p][j];
-                x[i][j] = -s / g[i][i];
+            if (d > kDropRel * diag0[c] && d > 0.f) {   // the same decision in every thread
+                const float inv_d = 1.f / d;
+                for (int i = c + 1 + ti; i < L; i += 16) {
+                    const float gi = g[c][i] * inv_d;
+                    for (int j = c + 1 + tj; j < L; j += 16)
+                        if (j >= i) g[i][j] -= gi * g[c][j];
+                }
             }
+            __syncthreads();
+        }
+    }
+    if (tid < L) {
+        const int c = tid;
+        const float d = g[c][c];
+        const bool ok = d > kDropRel * diag0[c] && d > 0.f;
+        dropped[c] = ok ? 0 : 1;
+        const float scale = ok ? 1.f / sqrtf(d) : 0.f;
+        for (int j = c + 1; j < L; ++j) g[c][j] *= scale;
+        g[c][c] = ok ? sqrtf(d) : 1.f;
+    }
+    __syncthreads();
+    // X = R^{-1} in 16 x 16 blocks.  Diagonal blocks by back substitution (one thread per column, 16 steps deep);
+    // above the diagonal  X[I][J] = -X[I][I] * sum_{P = I+1 .. J} R[I][P] X[P][J],  block row I descending, every
+    // thread one entry of the 16 x 16 product: the block columns J are independent of each other.
+    for (int idx = tid; idx < L * L; idx += 256) x[idx / L][idx % L] = 0.f;
+    __syncthreads();
+    if (tid < L && !dropped[tid]) {
+        const int j = tid, j0 = j & ~15;
+        x[j][j] = 1.f / g[j][j];
+        for (int i = j - 1; i >= j0; --i) {
+            float s = 0.f;
+            for (int p = i + 1; p <= j; ++p) s += g[i][p] * x[p][j];
+            x[i][j] = -s / g[i][i];
         }
     }
     __syncthreads();
+    {
+        __shared__ float tmp[TL][16][17];
+        const int bi = tid >> 4, bj = tid & 15;   // entry (bi, bj) of a 16 x 16 block
+        for (int step = 1; step < TL; ++step) {   // block row I = J - step for every block column J >= step
+            for (int J = step; J < TL; ++J) {
+                const int I = J - step;
+                float s = 0.f;
+                for (int P = I + 1; P <= J; ++P)
+#pragma unroll
+                    for (int c = 0; c < 16; ++c) s += g[16 * I + bi][16 * P + c] * x[16 * P + c][16 * J + bj];
+                tmp[J][bi][bj] = s;
+            }
+            __syncthreads();
+            for (int J = step; J < TL; ++J) {
+                const int I = J - step;
+                float s = 0.f;
+#pragma unroll
+                for (int c = 0; c < 16; ++c) s += x[16 * I + bi][16 * I + c] * tmp[J][c][bj];
+                x[16 * I + bi][16 * J + bj] = dropped[16 * J + bj] ? 0.f : -s;
+            }
+            __syncthreads();
+        }
+    }
     for (int idx = tid; idx < L * L; idx += 256) rinv[idx] = x[idx / L][idx % L];
 }
 
@@ -237,10 +282,10 @@ __global__ __launch_bounds__(256) void apply_kernel(const float* in, int64_t row
 // cyclic Jacobi with the L / 2 disjoint rotations of a round-robin round applied together, eigenvalues ranked in
 // descending order; then  ma[:, k] = u_k lambda_k^{-1/4},  mb[:, k] = u_k lambda_k^{1/4}  for the r largest (other
 // columns zero) and sigma[k] = sqrt(lambda_k).
-constexpr int kJacobiSweeps = 10;
+constexpr int kJacobiSweeps = 8;   // upper bound (fp32 Jacobi on up to 128 columns is through by then); a sweep that meets nothing worth rotating ends the loop
 template <int TL>
-__global__ __launch_bounds__(256) void eig_kernel(const float* __restrict__ gp, int nblocks, int r, float* __restrict__ ma,
-                                                  float* __restrict__ mb, float* __restrict__ sigma) {
+__global__ __launch_bounds__(256) void eig_kernel(const float* gsum, int r, float* __restrict__ ma, float* mb,
+                                                  float* __restrict__ sigma) {
     constexpr int L = 16 * TL, H = L / 2;
     __shared__ float a[L][L + 1];
     __shared__ float v[L][L + 1];
@@ -248,15 +293,16 @@ __global__ __launch_bounds__(256) void eig_kernel(const float* __restrict__ gp, 
     __shared__ int pair[H][2];
     __shared__ float lam[L];
     __shared__ int order[L];
-    const int tid = threadIdx.x;
-    for (int idx = tid; idx < L * L; idx += 256) {
-        float s = 0.f;
-        for (int b = 0; b < nblocks; ++b) s += gp[(int64_t)b * L * L + idx];
-        a[idx / L][idx % L] = s;
+    const int tid = threadIdx.x, nthreads = blockDim.x;
+    __shared__ float off_max[H];
+    __shared__ int done;
+    for (int idx = tid; idx < L * L; idx += nthreads) {   // gsum may be the memory that mb goes to at the end
+        a[idx / L][idx % L] = gsum[idx];
         v[idx / L][idx % L] = idx / L == idx % L ? 1.f : 0.f;
     }
     __syncthreads();
     for (int sweep = 0; sweep < kJacobiSweeps; ++sweep) {
+        if (tid < H) off_max[tid] = 0.f;
         for (int t = 0; t < L - 1; ++t) {
             if (tid < H) {   // round t of the round-robin schedule: index L - 1 stays put, the others turn
                 int p = tid == 0 ? L - 1 : (t + tid) % (L - 1);
@@ -270,32 +316,69 @@ __global__ __launch_bounds__(256) void eig_kernel(const float* __restrict__ gp, 
                     c = 1.f / sqrtf(1.f + tt * tt);
                     s = tt * c;
                 }
+                off_max[tid] = fmaxf(off_max[tid], fabsf(apq));
                 pair[tid][0] = p; pair[tid][1] = q;
                 rot[tid][0] = c; rot[tid][1] = s;
             }
             __syncthreads();
-            for (int idx = tid; idx < H * L; idx += 256) {   // columns p, q of a and of v
-                const int pr = idx / L, k = idx % L;
-                const int p = pair[pr][0], q = pair[pr][1];
-                const float c = rot[pr][0], s = rot[pr][1];
-                const float ap = a[k][p], aq = a[k][q];
-                a[k][p] = c * ap - s * aq;
-                a[k][q] = s * ap + c * aq;
-                const float vp = v[k][p], vq = v[k][q];
-                v[k][p] = c * vp - s * vq;
-                v[k][q] = s * vp + c * vq;
+            // The items of a phase touch disjoint entries; they are taken kBatch at a time with all reads before
+            // the first write, or every item would wait for the LDS round trip of the one before it.
+            constexpr int kBatch = 4;
+            for (int base = tid; base < H * L; base += nthreads * kBatch) {   // columns p, q of a and of v
+                int p[kBatch], q[kBatch], k[kBatch];
+                float c[kBatch], s[kBatch], ap[kBatch], aq[kBatch], vp[kBatch], vq[kBatch];
+#pragma unroll
+                for (int b = 0; b < kBatch; ++b) {
+                    const int idx = base + b * nthreads;
+                    const int pr = idx < H * L ? idx / L : 0;
+                    k[b] = idx < H * L ? idx % L : -1;
+                    p[b] = pair[pr][0]; q[b] = pair[pr][1];
+                    c[b] = rot[pr][0]; s[b] = rot[pr][1];
+                    const int kk = k[b] < 0 ? 0 : k[b];
+                    ap[b] = a[kk][p[b]]; aq[b] = a[kk][q[b]];
+                    vp[b] = v[kk][p[b]]; vq[b] = v[kk][q[b]];
+                }
+#pragma unroll
+                for (int b = 0; b < kBatch; ++b) {
+                    if (k[b] < 0) continue;
+                    a[k[b]][p[b]] = c[b] * ap[b] - s[b] * aq[b];
+                    a[k[b]][q[b]] = s[b] * ap[b] + c[b] * aq[b];
+                    v[k[b]][p[b]] = c[b] * vp[b] - s[b] * vq[b];
+                    v[k[b]][q[b]] = s[b] * vp[b] + c[b] * vq[b];
+                }
             }
             __syncthreads();
-            for (int idx = tid; idx < H * L; idx += 256) {   // rows p, q of a
-                const int pr = idx / L, k = idx % L;
-                const int p = pair[pr][0], q = pair[pr][1];
-                const float c = rot[pr][0], s = rot[pr][1];
-                const float ap = a[p][k], aq = a[q][k];
-                a[p][k] = c * ap - s * aq;
-                a[q][k] = s * ap + c * aq;
+            for (int base = tid; base < H * L; base += nthreads * kBatch) {   // rows p, q of a
+                int p[kBatch], q[kBatch], k[kBatch];
+                float c[kBatch], s[kBatch], ap[kBatch], aq[kBatch];
+#pragma unroll
+                for (int b = 0; b < kBatch; ++b) {
+                    const int idx = base + b * nthreads;
+                    const int pr = idx < H * L ? idx / L : 0;
+                    k[b] = idx < H * L ? idx % L : -1;
+                    p[b] = pair[pr][0]; q[b] = pair[pr][1];
+                    c[b] = rot[pr][0]; s[b] = rot[pr][1];
+                    const int kk = k[b] < 0 ? 0 : k[b];
+                    ap[b] = a[p[b]][kk]; aq[b] = a[q[b]][kk];
+                }
+#pragma unroll
+                for (int b = 0; b < kBatch; ++b) {
+                    if (k[b] < 0) continue;
+                    a[p[b]][k[b]] = c[b] * ap[b] - s[b] * aq[b];
+                    a[q[b]][k[b]] = s[b] * ap[b] + c[b] * aq[b];
+                }
             }
             __syncthreads();
         }
+        // converged when no off-diagonal entry met in this sweep exceeds a few fp32 roundings of the largest diagonal entry
+        if (tid == 0) {
+            float off = 0.f, dmax = 0.f;
+            for (int i = 0; i < H; ++i) off = fmaxf(off, off_max[i]);
+            for (int i = 0; i < L; ++i) dmax = fmaxf(dmax, fabsf(a[i][i]));
+            done = off <= 5e-7f * dmax ? 1 : 0;
+        }
+        __syncthreads();
+        if (done) break;
     }
     if (tid < L) lam[tid] = a[tid][tid] > 0.f ? a[tid][tid] : 0.f;
     __syncthreads();
@@ -307,7 +390,7 @@ __global__ __launch_bounds__(256) void eig_kernel(const float* __restrict__ gp, 
     __syncthreads();
     float lmax = 0.f;
     for (int j = 0; j < L; ++j) lmax = lam[j] > lmax ? lam[j] : lmax;
-    for (int idx = tid; idx < L * L; idx += 256) {
+    for (int idx = tid; idx < L * L; idx += nthreads) {
         const int p = idx / L, i = idx % L;
         const int rk = order[i];
         float fa = 0.f, fb = 0.f;
@@ -335,7 +418,7 @@ static SvdPlan svd_plan(int64_t N, int64_t K, int64_t l) {
     p.ks_n = adapter_ksplit(N, K);   // rows N, contraction over K
     p.ks_k = adapter_ksplit(K, N);   // rows K, contraction over N
     const int64_t big = N > K ? N : K;
-    p.gram_blocks = (int)((big + 255) / 256);
+    p.gram_blocks = (int)((big + kGramRows - 1) / kGramRows);
     size_t o = 0;
     p.off_et = o; o += round_up_256((size_t)N * K * sizeof(uint16_t));
     p.off_y = o; o += round_up_256((size_t)N * p.L * sizeof(float));
@@ -369,15 +452,17 @@ static void run_svd(const uint16_t* e, int64_t N, int64_t K, int r, int l, int i
         hipLaunchKernelGGL(fold_reduce_kernel, dim3((unsigned)((rows * (L / 4) + 255) / 256)), dim3(256), 0, stream, partial, rows,
                            L, ks, out);
     };
-    auto gram = [&](const float* buf, int64_t rows) -> int {
-        const int nb = (int)((rows + 255) / 256);
+    auto gram = [&](const float* buf, int64_t rows) {   // small_b = buf^T buf
+        const int nb = (int)((rows + kGramRows - 1) / kGramRows);
         hipLaunchKernelGGL((gram_partial_kernel<TL>), dim3(nb), dim3(256), 0, stream, buf, rows, gp);
-        return nb;
+        hipLaunchKernelGGL(gram_reduce_kernel, dim3((L * L + 255) / 256), dim3(256), 0, stream, gp, nb, L * L, small_b);
     };
-    auto orth = [&](float* buf, int64_t rows) {   // CholeskyQR, twice; leaves the transposed split copy in bt
-        for (int pass = 0; pass < 2; ++pass) {
-            const int nb = gram(buf, rows);
-            hipLaunchKernelGGL((chol_inverse_kernel<TL>), dim3(1), dim3(256), 0, stream, gp, nb, small_a);
+    // CholeskyQR; leaves the transposed split copy in bt.  Inside the iteration one pass is enough (it only has to
+    // keep the columns from collapsing onto the leading direction); the basis that the result is built on gets two.
+    auto orth = [&](float* buf, int64_t rows, int passes) {
+        for (int pass = 0; pass < passes; ++pass) {
+            gram(buf, rows);
+            hipLaunchKernelGGL((chol_inverse_kernel<TL>), dim3(1), dim3(256), 0, stream, small_b, small_a);
             hipLaunchKernelGGL((apply_kernel<TL>), dim3((unsigned)((rows + 63) / 64)), dim3(256), 0, stream, buf, rows, small_a, 0,
                                L, buf, bt, rows);
         }
@@ -386,17 +471,17 @@ static void run_svd(const uint16_t* e, int64_t N, int64_t K, int r, int l, int i
     hipLaunchKernelGGL(transpose_bf16_kernel, dim3((unsigned)((K + 31) / 32), (unsigned)((N + 31) / 32)), dim3(256), 0, stream, e, N,
                        K, et);
     hipLaunchKernelGGL(split_transpose_kernel, dim3((unsigned)((K + 255) / 256)), dim3(256), 0, stream, omega, K, l, L, bt);
-    product(e, N, K, p.ks_n, y);          // Y = E Omega
-    orth(y, N);                           // Q
-    product(et, K, N, p.ks_k, z);         // Z = E^T Q
+    product(e, N, K, p.ks_n, y);                      // Y = E Omega
+    orth(y, N, iterations == 0 ? 2 : 1);              // Q
+    product(et, K, N, p.ks_k, z);                     // Z = E^T Q
     for (int it = 0; it < iterations; ++it) {
-        orth(z, K);
+        orth(z, K, 1);
         product(e, N, K, p.ks_n, y);
-        orth(y, N);
+        orth(y, N, it + 1 == iterations ? 2 : 1);
         product(et, K, N, p.ks_k, z);
     }
-    const int nb = gram(z, K);
-    hipLaunchKernelGGL((eig_kernel<TL>), dim3(1), dim3(256), 0, stream, gp, nb, r, small_a, small_b, sigma);
+    gram(z, K);
+    hipLaunchKernelGGL((eig_kernel<TL>), dim3(1), dim3(256), 0, stream, small_b, r, small_a, small_b, sigma);
     hipLaunchKernelGGL((apply_kernel<TL>), dim3((unsigned)((K + 63) / 64)), dim3(256), 0, stream, z, K, small_a, 1, r,
                        (float*)nullptr, a_res, (int64_t)r);
     hipLaunchKernelGGL((apply_kernel<TL>), dim3((unsigned)((N + 63) / 64)), dim3(256), 0, stream, y, N, small_b, 2, r,
