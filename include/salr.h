@@ -197,7 +197,7 @@ salr_status_t salr_residual(const uint16_t* w, const uint16_t* w_hat, int64_t ro
  *   workspace    --   at least salr_residual_adapter_workspace_bytes(N, K, r, oversample) bytes, 256-byte aligned
  *                     (it holds a transposed copy of E and the tall fp32 factors); contents unspecified
  *
- * Constraints: N % 32 == 0, K % 32 == 0 (else SHAPE); power_iterations <= 64.  A matrix of rank below r yields
+ * Constraints: N % 32 == 0, K % 32 == 0, N and K <= 2097120 (else SHAPE); power_iterations <= 64.  A matrix of rank below r yields
  * zero columns / rows for the missing directions.  The workspace query returns 0 for sizes the call would refuse.
  * Errors: INVALID_ARG, SHAPE, UNSUPPORTED, CAPACITY, HIP.
  */

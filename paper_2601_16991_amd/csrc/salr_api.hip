@@ -9,6 +9,7 @@ constexpr int64_t kMaxRows = 2147483647LL;        // gridDim.x
 constexpr int64_t kMaxCols = 2147483647LL - 31;   // so that ceil(cols/32)*32 stays in int32 range
 constexpr int64_t kMaxRank = 256;
 constexpr int64_t kMaxM = 65535LL * 64;           // gridDim.y of the generic kernel
+constexpr int64_t kMaxSvdDim = 65535LL * 32;      // gridDim.y of the transposing kernel
 
 }  // namespace
 
@@ -76,6 +77,7 @@ salr_status_t salr_residual(const uint16_t* w, const uint16_t* w_hat, int64_t ro
     if (rows < 0 || cols < 0) return SALR_ERR_INVALID_ARG;
     if (rows > 0 && cols > 0 && (!w || !w_hat || !e)) return SALR_ERR_INVALID_ARG;
     if (rows > kMaxRows || cols > kMaxCols) return SALR_ERR_SHAPE;
+    if (cols > 0 && rows > (kMaxRows * 2048) / cols) return SALR_ERR_SHAPE;   // 2048 elements per workgroup
     hipError_t err = salr::launch_residual(w, w_hat, rows, cols, e, static_cast<hipStream_t>(stream));
     return err == hipSuccess ? SALR_OK : SALR_ERR_HIP;
 }
@@ -93,6 +95,7 @@ salr_status_t salr_concat_adapters(const uint16_t* const* a_list, const uint16_t
         R += ranks[i];
         if (R > 65535) return SALR_ERR_SHAPE;   // rows of B_cat are a grid dimension
     }
+    if (R > 0 && K > (kMaxRows * 256) / R) return SALR_ERR_SHAPE;   // one thread per element of A_cat
     if (R == 0) return SALR_OK;
     if ((K > 0 && !a_cat) || (N > 0 && !b_cat)) return SALR_ERR_INVALID_ARG;
     hipError_t err = salr::launch_concat(a_list, b_list, ranks, n, K, N, R, a_cat, b_cat, static_cast<hipStream_t>(stream));
@@ -100,7 +103,7 @@ salr_status_t salr_concat_adapters(const uint16_t* const* a_list, const uint16_t
 }
 
 size_t salr_residual_adapter_workspace_bytes(int64_t N, int64_t K, int64_t r, int64_t oversample) {
-    if (N <= 0 || K <= 0 || r <= 0 || oversample < 0 || N % 32 != 0 || K % 32 != 0 || N > kMaxRows || K > kMaxRows) return 0;
+    if (N <= 0 || K <= 0 || r <= 0 || oversample < 0 || N % 32 != 0 || K % 32 != 0 || N > kMaxSvdDim || K > kMaxSvdDim) return 0;
     if (r + oversample > salr::kSvdMaxColumns || r + oversample > (N < K ? N : K)) return 0;
     return salr::residual_adapter_workspace_bytes(N, K, r + oversample);
 }
@@ -111,7 +114,7 @@ salr_status_t salr_residual_adapter(const uint16_t* e, int64_t N, int64_t K, int
     if (N < 0 || K < 0 || r < 0 || oversample < 0 || power_iterations < 0) return SALR_ERR_INVALID_ARG;
     if (N == 0 || K == 0 || r == 0) return SALR_OK;
     if (!e || !omega || !a_res || !b_res) return SALR_ERR_INVALID_ARG;
-    if (N % 32 != 0 || K % 32 != 0 || N > kMaxRows || K > kMaxRows) return SALR_ERR_SHAPE;
+    if (N % 32 != 0 || K % 32 != 0 || N > kMaxSvdDim || K > kMaxSvdDim) return SALR_ERR_SHAPE;
     if (r + oversample > (N < K ? N : K)) return SALR_ERR_SHAPE;
     if (r + oversample > salr::kSvdMaxColumns || power_iterations > 64) return SALR_ERR_UNSUPPORTED;
     const size_t need = salr::residual_adapter_workspace_bytes(N, K, r + oversample);
