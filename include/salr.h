@@ -161,6 +161,35 @@ salr_status_t salr_sparse_lowrank_linear(const uint16_t* x, int64_t M, int64_t K
                                          size_t workspace_bytes, void* stream);
 
 /*
+ * salr_sparse_lowrank_linear_backward -- the adjoint of the layer of Sec. 3.2 / 3.3, which fine-tuning (the
+ * training-throughput comparison of Sec. 4) runs every step.  The pruned base weight is frozen and gets no
+ * gradient; the concatenated adapters do:
+ *
+ *     dX [M, K] = dY W-hat + (dY B_cat^T) A_cat^T
+ *     dA [K, R] = X^T (dY B_cat^T)           (gradient of A_cat: columns in the order of the concatenation)
+ *     dB [R, N] = (X A_cat)^T dY
+ *
+ * bf16 in and out, fp32 sums; as in the forward pass the two [M, R] intermediates are rounded to bf16 once.
+ *
+ *   x            in   [M, K] bf16, the layer's input (needed for dA / dB only; may be NULL otherwise)
+ *   dy           in   [M, N] bf16, the gradient of the layer's output
+ *   bitmap, values, row_offsets, a_cat, b_cat, R   as for salr_sparse_lowrank_linear (the weight is needed for dX only)
+ *   dx, da, db   out  any of them may be NULL: that gradient is not computed
+ *   workspace    --   at least salr_linear_backward_workspace_bytes(M, K, N, R, dx != NULL, da != NULL || db != NULL)
+ *                     bytes, 256-byte aligned (for dX it holds the decoded weight and its transpose, 4 N K bytes)
+ *
+ * Constraints: K % 32 == 0 (SHAPE); N % 64 == 0 for dX, N % 32 == 0 with adapters, M % 32 == 0 for dA / dB,
+ * R <= 256 (UNSUPPORTED otherwise).  The workspace query returns 0 for sizes the call would refuse.
+ * Errors: INVALID_ARG, SHAPE, UNSUPPORTED, CAPACITY, HIP.
+ */
+size_t salr_linear_backward_workspace_bytes(int64_t M, int64_t K, int64_t N, int64_t R, int want_dx, int want_dadb);
+salr_status_t salr_sparse_lowrank_linear_backward(const uint16_t* x, const uint16_t* dy, int64_t M, int64_t K,
+                                                  int64_t N, const uint32_t* bitmap, const uint16_t* values,
+                                                  const uint32_t* row_offsets, const uint16_t* a_cat,
+                                                  const uint16_t* b_cat, int64_t R, uint16_t* dx, uint16_t* da,
+                                                  uint16_t* db, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * salr_residual -- Sec. 3.1 ("Sparsity Preservation Pruning"): the residual E = W - W-hat that the pruning
  * leaves behind and whose truncated SVD becomes the residual adapter.
  *

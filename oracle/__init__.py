@@ -15,7 +15,8 @@ rule and Theorem 1's closed form and worked example; encode/decode against each 
 byte-mask/LUT decoder, popcount identities and hand-worked masks; the linear against pure-Python
 loops, numpy fp64 matmul in the special cases that reduce to it, and the per-adapter sum; the SVD
 residual against Theorem 3's bound; the residual against W = What + E and hand-worked values; the
-concatenation against the sum over adapters on integer-valued matrices.  No function here is "parity unpinned".
+concatenation against the sum over adapters on integer-valued matrices; the backward pass against the
+forward pass (C code, not numpy) through the adjoint identities and against pure-Python loops.  No function here is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -204,6 +205,20 @@ def linear_per_adapter(x: np.ndarray, w_hat: np.ndarray, As: Sequence[np.ndarray
         if rc:
             raise RuntimeError("adapter_accumulate failed")
     return y
+
+
+def linear_backward(x: np.ndarray, dy: np.ndarray, w_hat: np.ndarray, a_cat: Optional[np.ndarray],
+                    b_cat: Optional[np.ndarray]) -> Tuple[np.ndarray, Optional[np.ndarray], Optional[np.ndarray]]:
+    """The adjoint of the layer Y = X What^T + (X A_cat) B_cat (Sec. 3.2 / 3.3) in fp64, written out from the chain
+    rule: dX = dY What + (dY B_cat^T) A_cat^T, dA = X^T (dY B_cat^T), dB = (X A_cat)^T dY.  bf16 patterns in, fp64 out.
+    The frozen What gets no gradient."""
+    X, dY, W = bf16_to_f64(x), bf16_to_f64(dy), bf16_to_f64(w_hat)
+    dX = dY @ W
+    if a_cat is None or a_cat.shape[1] == 0:
+        return dX, None, None
+    A, B = bf16_to_f64(a_cat), bf16_to_f64(b_cat)
+    Tp = dY @ B.T            # [M, R]
+    return dX + Tp @ A.T, X.T @ Tp, (X @ A).T @ dY
 
 
 # ---------------------------------------------------------------------------------------------------

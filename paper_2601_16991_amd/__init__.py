@@ -66,6 +66,11 @@ def lib() -> ctypes.CDLL:
         L.salr_residual_adapter_workspace_bytes.argtypes = [_i64, _i64, _i64, _i64]
         L.salr_residual_adapter.restype = ctypes.c_int
         L.salr_residual_adapter.argtypes = [_vp, _i64, _i64, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
+        L.salr_linear_backward_workspace_bytes.restype = ctypes.c_size_t
+        L.salr_linear_backward_workspace_bytes.argtypes = [_i64, _i64, _i64, _i64, ctypes.c_int, ctypes.c_int]
+        L.salr_sparse_lowrank_linear_backward.restype = ctypes.c_int
+        L.salr_sparse_lowrank_linear_backward.argtypes = [_vp, _vp, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _vp,
+                                                          _vp, _vp, ctypes.c_size_t, _vp]
         L.salr_set_kernel_timing_events.restype = None
         L.salr_set_kernel_timing_events.argtypes = [_vp, _vp]
         _lib = L
@@ -165,6 +170,51 @@ def salr_sparse_lowrank_linear(x: torch.Tensor, bitmap: torch.Tensor, values: to
                                           _ptr(a_cat, _BF16_TYPES, "a_cat"), _ptr(b_cat, _BF16_TYPES, "b_cat"), R,
                                           _ptr(y, _BF16_TYPES, "y"), ws_ptr, ws_bytes, _stream(stream))
     _check(st, "salr_sparse_lowrank_linear")
+
+
+def salr_linear_backward_workspace_bytes(M: int, K: int, N: int, R: int, want_dx: bool, want_dadb: bool) -> int:
+    return int(lib().salr_linear_backward_workspace_bytes(M, K, N, R, int(want_dx), int(want_dadb)))
+
+
+def salr_sparse_lowrank_linear_backward(x: Optional[torch.Tensor], dy: torch.Tensor, bitmap: torch.Tensor,
+                                        values: torch.Tensor, row_offsets: torch.Tensor, a_cat: Optional[torch.Tensor],
+                                        b_cat: Optional[torch.Tensor], dx: Optional[torch.Tensor],
+                                        da: Optional[torch.Tensor], db: Optional[torch.Tensor],
+                                        workspace: Optional[torch.Tensor], stream=None) -> None:
+    """Enqueue dX = dY What + (dY B_cat^T) A_cat^T, dA = X^T (dY B_cat^T), dB = (X A_cat)^T dY; None = not computed."""
+    M, N = dy.shape
+    K = bitmap.shape[1] * 32
+    R = 0 if a_cat is None else a_cat.shape[1]
+    if bitmap.shape[0] != N or row_offsets.numel() != N + 1:
+        raise ValueError("inconsistent shapes")
+    if R and (tuple(a_cat.shape) != (K, R) or tuple(b_cat.shape) != (R, N)):
+        raise ValueError("adapter shapes")
+    for name, t, shape in (("x", x, (M, K)), ("dx", dx, (M, K)), ("da", da, (K, R)), ("db", db, (R, N))):
+        if t is not None and tuple(t.shape) != shape:
+            raise ValueError(f"{name} must be {shape}")
+    ws_ptr = None if workspace is None else workspace.data_ptr()
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = lib().salr_sparse_lowrank_linear_backward(
+        _ptr(x, _BF16_TYPES, "x"), _ptr(dy, _BF16_TYPES, "dy"), M, K, N, _ptr(bitmap, _U32_TYPES, "bitmap"),
+        _ptr(values, _BF16_TYPES, "values"), _ptr(row_offsets, _U32_TYPES, "row_offsets"),
+        _ptr(a_cat, _BF16_TYPES, "a_cat"), _ptr(b_cat, _BF16_TYPES, "b_cat"), R, _ptr(dx, _BF16_TYPES, "dx"),
+        _ptr(da, _BF16_TYPES, "da"), _ptr(db, _BF16_TYPES, "db"), ws_ptr, ws_bytes, _stream(stream))
+    _check(st, "salr_sparse_lowrank_linear_backward")
+
+
+def linear_backward(x, dy, bitmap, values, row_offsets, a_cat, b_cat, need_dx=True, need_dadb=True):
+    """(dx, da, db); entries not asked for (or without adapters) are None."""
+    M, N = dy.shape
+    K = bitmap.shape[1] * 32
+    R = 0 if a_cat is None else a_cat.shape[1]
+    dev = dy.device
+    dx = torch.empty((M, K), dtype=dy.dtype, device=dev) if need_dx else None
+    da = torch.empty((K, R), dtype=dy.dtype, device=dev) if need_dadb and R else None
+    db = torch.empty((R, N), dtype=dy.dtype, device=dev) if need_dadb and R else None
+    need = salr_linear_backward_workspace_bytes(M, K, N, R, need_dx, need_dadb and R > 0)
+    ws = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+    salr_sparse_lowrank_linear_backward(x, dy, bitmap, values, row_offsets, a_cat, b_cat, dx, da, db, ws)
+    return dx, da, db
 
 
 class PreparedLinear:

@@ -129,6 +129,11 @@ __global__ __launch_bounds__(256) void adapter_transpose_kernel(const uint16_t* 
     }
 }
 
+void launch_adapter_transpose(const uint16_t* a_cat, int64_t K, int R, int Rpad, uint16_t* a_t, hipStream_t stream) {
+    hipLaunchKernelGGL(adapter_transpose_kernel, dim3((unsigned)((K + 255) / 256), Rpad / 8), dim3(256), 0, stream, a_cat, K, R,
+                       Rpad, a_t);
+}
+
 template <int kMB, int kDepth>
 static void launch_tall_product_rt(int rank_tiles, dim3 grid, hipStream_t stream, const uint16_t* x, int64_t M, int64_t K,
                                    const uint16_t* a_t, int Rpad, int ksplit, uint16_t* t, float* partial, int keep) {
@@ -161,8 +166,7 @@ void launch_adapter_t(const LinearArgs& a, hipStream_t stream) {
     char* base = reinterpret_cast<char*>(a.t);
     uint16_t* a_t = reinterpret_cast<uint16_t*>(base + adapter_t_bytes(a.M, a.R));
     float* partial = reinterpret_cast<float*>(base + adapter_t_bytes(a.M, a.R) + adapter_at_bytes(a.K, a.R));
-    hipLaunchKernelGGL(adapter_transpose_kernel, dim3((unsigned)((a.K + 255) / 256), Rpad / 8), dim3(256), 0, stream, a.a_cat,
-                       a.K, R, Rpad, a_t);
+    launch_adapter_transpose(a.a_cat, a.K, R, Rpad, a_t, stream);
     const int ksplit = adapter_ksplit(a.M, a.K);
     launch_tall_product(a.x, a.M, a.K, a_t, Rpad, ksplit, a.t, partial, false, stream);
     if (ksplit > 1) launch_splitk_reduce(partial, a.M * Rpad, ksplit, a.t, stream);

@@ -153,6 +153,45 @@ salr_status_t salr_sparse_lowrank_linear(const uint16_t* x, int64_t M, int64_t K
     return e == hipSuccess ? SALR_OK : SALR_ERR_HIP;
 }
 
+static salr_status_t backward_shape_check(int64_t M, int64_t K, int64_t N, int64_t R, bool want_dx, bool want_dadb) {
+    if (K % 32 != 0) return SALR_ERR_SHAPE;
+    if (N > kMaxSvdDim || K > kMaxCols || M > kMaxM) return SALR_ERR_SHAPE;
+    if (R > kMaxRank) return SALR_ERR_UNSUPPORTED;
+    if (want_dx && N % 64 != 0) return SALR_ERR_UNSUPPORTED;
+    if (R > 0 && N % 32 != 0) return SALR_ERR_UNSUPPORTED;
+    if (want_dadb && R > 0 && (M % 32 != 0 || M > kMaxSvdDim)) return SALR_ERR_UNSUPPORTED;
+    return SALR_OK;
+}
+
+size_t salr_linear_backward_workspace_bytes(int64_t M, int64_t K, int64_t N, int64_t R, int want_dx, int want_dadb) {
+    if (M <= 0 || K <= 0 || N <= 0 || R < 0) return 0;
+    if (backward_shape_check(M, K, N, R, want_dx != 0, want_dadb != 0) != SALR_OK) return 0;
+    return salr::linear_backward_workspace_bytes(M, K, N, R, want_dx != 0, want_dadb != 0);
+}
+
+salr_status_t salr_sparse_lowrank_linear_backward(const uint16_t* x, const uint16_t* dy, int64_t M, int64_t K, int64_t N,
+                                                  const uint32_t* bitmap, const uint16_t* values,
+                                                  const uint32_t* row_offsets, const uint16_t* a_cat, const uint16_t* b_cat,
+                                                  int64_t R, uint16_t* dx, uint16_t* da, uint16_t* db, void* workspace,
+                                                  size_t workspace_bytes, void* stream) {
+    if (M < 0 || K < 0 || N < 0 || R < 0) return SALR_ERR_INVALID_ARG;
+    if (M == 0 || K == 0 || N == 0) return SALR_OK;
+    const bool want_dx = dx != nullptr, want_dadb = R > 0 && (da != nullptr || db != nullptr);
+    if (!want_dx && !want_dadb) return SALR_OK;
+    if (!dy) return SALR_ERR_INVALID_ARG;
+    if (want_dx && (!bitmap || !row_offsets)) return SALR_ERR_INVALID_ARG;
+    if (R > 0 && (!a_cat || !b_cat)) return SALR_ERR_INVALID_ARG;
+    if (want_dadb && !x) return SALR_ERR_INVALID_ARG;
+    const salr_status_t st = backward_shape_check(M, K, N, R, want_dx, want_dadb);
+    if (st != SALR_OK) return st;
+    const size_t need = salr::linear_backward_workspace_bytes(M, K, N, R, want_dx, want_dadb);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return SALR_ERR_CAPACITY;
+    hipError_t e = salr::launch_linear_backward(x, dy, M, K, N, bitmap, values, row_offsets, a_cat, b_cat, R, dx,
+                                                want_dadb ? da : nullptr, want_dadb ? db : nullptr, workspace,
+                                                static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SALR_OK : SALR_ERR_HIP;
+}
+
 void salr_set_kernel_timing_events(void* start_event, void* stop_event) {
     salr::g_timing_events.start = static_cast<hipEvent_t>(start_event);
     salr::g_timing_events.stop = static_cast<hipEvent_t>(stop_event);

@@ -130,6 +130,13 @@ inline size_t linear_workspace_bytes(int64_t M, int64_t K, int64_t N, int64_t R)
     return b;
 }
 
+// Backward pass of the layer: dx [M, K], da [K, R], db [R, N]; any of them may be null (not computed)
+size_t linear_backward_workspace_bytes(int64_t M, int64_t K, int64_t N, int64_t R, bool want_dx, bool want_dadb);
+hipError_t launch_linear_backward(const uint16_t* x, const uint16_t* dy, int64_t M, int64_t K, int64_t N,
+                                  const uint32_t* bitmap, const uint16_t* values, const uint32_t* row_offsets,
+                                  const uint16_t* a_cat, const uint16_t* b_cat, int64_t R, uint16_t* dx, uint16_t* da,
+                                  uint16_t* db, void* workspace, hipStream_t stream);
+
 hipError_t launch_linear(const LinearArgs& args, hipStream_t stream);
 hipError_t launch_linear_stream(const LinearArgs& args, hipStream_t stream, const TimingEvents& ev);
 hipError_t launch_linear_twostage(const LinearArgs& args, hipStream_t stream, const TimingEvents& ev);
@@ -139,6 +146,15 @@ void launch_adapter_t(const LinearArgs& args, hipStream_t stream);
 // slices: bf16 t [M, Rpad] (one slice, !keep_fp32) or fp32 partial [ksplit, M, Rpad]
 void launch_tall_product(const uint16_t* x, int64_t M, int64_t K, const uint16_t* a_t, int Rpad, int ksplit, uint16_t* t,
                          float* partial, bool keep_fp32, hipStream_t stream);
+// a_t [Rpad, K] = A_cat [K, R]^T, rows R .. Rpad - 1 zero
+void launch_adapter_transpose(const uint16_t* a_cat, int64_t K, int R, int Rpad, uint16_t* a_t, hipStream_t stream);
+// out [C, R] = in [R, C]^T (bf16); R <= 65535 * 32
+void launch_transpose_bf16(const uint16_t* in, int64_t R, int64_t C, uint16_t* out, hipStream_t stream);
+// y [M, N] = x [M, K] * wd [N, K]^T (+ t [M, Rpad] * b_cat [R, N], pitch N, when R > 0): the dense MFMA stage with its
+// tile choice; K % 64 == 0; partial holds dense_ksplit(M, K, N) fp32 copies of y when that is > 1
+void launch_dense_stage(const uint16_t* x, int64_t M, int64_t K, int64_t N, const uint16_t* wd, const uint16_t* t,
+                        const uint16_t* b_cat, int R, int Rpad, uint16_t* y, float* partial, const TimingEvents& ev,
+                        hipStream_t stream);
 // out[i] = bf16(sum over z < ksplit of partial[z * count + i]); count % 4 == 0
 void launch_splitk_reduce(const float* partial, int64_t count, int ksplit, uint16_t* out, hipStream_t stream);
 

@@ -240,37 +240,39 @@ __global__ __launch_bounds__(64 * (8 / kMI) * kWN, (8 / kMI) * kWN / 4) void den
         }
 }
 
+void launch_dense_stage(const uint16_t* x, int64_t M, int64_t K, int64_t N, const uint16_t* wd, const uint16_t* t,
+                        const uint16_t* b_cat, int R, int Rpad, uint16_t* y, float* partial, const TimingEvents& ev,
+                        hipStream_t stream) {
+    const int m_tiles = (int)((M + kDM - 1) / kDM);
+    // Tile width: 256 or 224 columns, whichever needs less time in whole rounds of the 256 CUs (one workgroup per
+    // CU, so a round costs its tile width); 128, with K split over workgroups if need be, when neither fills the chip.
+    const int64_t t256 = (int64_t)m_tiles * ((N + 255) / 256), t224 = (int64_t)m_tiles * ((N + 223) / 224);
+    const int64_t cost256 = (t256 + 255) / 256 * 256, cost224 = (t224 + 255) / 256 * 224;
+    const int tn = t256 < 224 ? 128 : (cost224 < cost256 ? 224 : 256);
+    const int n_tiles = (int)((N + tn - 1) / tn);
+    const int n_groups = (n_tiles + kDXcds - 1) / kDXcds;
+    const int ksplit = tn == 128 ? dense_ksplit(M, K, N) : 1;
+    const dim3 grid((unsigned)(n_groups * m_tiles * kDXcds), (unsigned)ksplit);
+    if (tn == 256)
+        SALR_LAUNCH((dense_gemm_kernel<4, 2, 4, 2>), grid, dim3(512), stream, ev, x, M, K, N, wd, t, b_cat, R, Rpad, y, m_tiles,
+                    n_tiles, ksplit, partial);
+    else if (tn == 224)
+        SALR_LAUNCH((dense_gemm_kernel<1, 7, 1, 2>), grid, dim3(512), stream, ev, x, M, K, N, wd, t, b_cat, R, Rpad, y, m_tiles,
+                    n_tiles, ksplit, partial);
+    else
+        SALR_LAUNCH((dense_gemm_kernel<2, 2, 2, 3>), grid, dim3(512), stream, ev, x, M, K, N, wd, t, b_cat, R, Rpad, y, m_tiles,
+                    n_tiles, ksplit, partial);
+    if (ksplit > 1) launch_splitk_reduce(partial, M * N, ksplit, y, stream);
+}
+
 hipError_t launch_linear_twostage(const LinearArgs& a, hipStream_t stream, const TimingEvents& ev) {
     const int R = (int)a.R, Rpad = (int)adapter_rank_padded(a.R);
     uint16_t* wd = reinterpret_cast<uint16_t*>(reinterpret_cast<char*>(a.t) + twostage_dense_offset(a.M, a.K, a.R));
     hipError_t e = launch_decode(a.bitmap, a.values, a.row_offsets, a.N, a.K, wd, stream);
     if (e != hipSuccess) return e;
     if (R > 0) launch_adapter_t(a, stream);
-    const int m_tiles = (int)((a.M + kDM - 1) / kDM);
-    // Tile width: 256 or 224 columns, whichever needs less time in whole rounds of the 256 CUs (one workgroup per
-    // CU, so a round costs its tile width); 128, with K split over workgroups if need be, when neither fills the chip.
-    const int64_t t256 = (int64_t)m_tiles * ((a.N + 255) / 256), t224 = (int64_t)m_tiles * ((a.N + 223) / 224);
-    const int64_t cost256 = (t256 + 255) / 256 * 256, cost224 = (t224 + 255) / 256 * 224;
-    const int tn = t256 < 224 ? 128 : (cost224 < cost256 ? 224 : 256);
-    const int n_tiles = (int)((a.N + tn - 1) / tn);
-    const int n_groups = (n_tiles + kDXcds - 1) / kDXcds;
-    const int ksplit = tn == 128 ? dense_ksplit(a.M, a.K, a.N) : 1;
     float* partial = reinterpret_cast<float*>(reinterpret_cast<char*>(wd) + round_up_256((size_t)a.N * (size_t)a.K * sizeof(uint16_t)));
-    const dim3 grid((unsigned)(n_groups * m_tiles * kDXcds), (unsigned)ksplit);
-    const uint16_t* wdc = wd;
-    const uint16_t* tc = a.t;
-    if (tn == 256)
-        SALR_LAUNCH((dense_gemm_kernel<4, 2, 4, 2>), grid, dim3(512), stream, ev, a.x, a.M, a.K, a.N, wdc, tc, a.b_cat, R, Rpad,
-                    a.y, m_tiles, n_tiles, ksplit, partial);
-    else if (tn == 224)
-        SALR_LAUNCH((dense_gemm_kernel<1, 7, 1, 2>), grid, dim3(512), stream, ev, a.x, a.M, a.K, a.N, wdc, tc, a.b_cat, R, Rpad,
-                    a.y, m_tiles, n_tiles, ksplit, partial);
-    else
-        SALR_LAUNCH((dense_gemm_kernel<2, 2, 2, 3>), grid, dim3(512), stream, ev, a.x, a.M, a.K, a.N, wdc, tc, a.b_cat, R, Rpad,
-                    a.y, m_tiles, n_tiles, ksplit, partial);
-    if (ksplit > 1) {
-        launch_splitk_reduce(partial, a.M * a.N, ksplit, a.y, stream);
-    }
+    launch_dense_stage(a.x, a.M, a.K, a.N, wd, a.t, a.b_cat, R, Rpad, a.y, partial, ev, stream);
     return hipGetLastError();
 }
 

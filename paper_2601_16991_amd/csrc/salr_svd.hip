@@ -31,6 +31,12 @@ __global__ __launch_bounds__(256) void transpose_bf16_kernel(const uint16_t* __r
         if (c0 + i < C && r0 + tx < R) out[(c0 + i) * R + r0 + tx] = tile[tx][i];
 }
 
+void launch_transpose_bf16(const uint16_t* in, int64_t R, int64_t C, uint16_t* out, hipStream_t stream) {
+    if (R == 0 || C == 0) return;
+    hipLaunchKernelGGL(transpose_bf16_kernel, dim3((unsigned)((C + 31) / 32), (unsigned)((R + 31) / 32)), dim3(256), 0, stream, in, R,
+                       C, out);
+}
+
 // fp32 v = hi + lo with hi = bf16(v), lo = bf16(v - hi): 16 significant bits survive
 __device__ __forceinline__ void split_bf16(float v, uint16_t& hi, uint16_t& lo) {
     hi = f32_to_bf16_rne(v);
@@ -468,8 +474,7 @@ static void run_svd(const uint16_t* e, int64_t N, int64_t K, int r, int l, int i
         }
     };
 
-    hipLaunchKernelGGL(transpose_bf16_kernel, dim3((unsigned)((K + 31) / 32), (unsigned)((N + 31) / 32)), dim3(256), 0, stream, e, N,
-                       K, et);
+    launch_transpose_bf16(e, N, K, et, stream);
     hipLaunchKernelGGL(split_transpose_kernel, dim3((unsigned)((K + 255) / 256)), dim3(256), 0, stream, omega, K, l, L, bt);
     product(e, N, K, p.ks_n, y);                      // Y = E Omega
     orth(y, N, iterations == 0 ? 2 : 1);              // Q

@@ -193,3 +193,32 @@ def test_residual_and_concat_validation(lib):
     assert lib.salr_concat_adapters(ptrs, ptrs, ranks, 2, 8, 8, None, fake, None) == salr.SALR_ERR_INVALID_ARG
     assert lib.salr_concat_adapters(ptrs, ptrs, big, 2, 8, 8, fake, fake, None) == salr.SALR_ERR_SHAPE
     assert lib.salr_concat_adapters(None, None, None, 0, 8, 8, None, None, None) == salr.SALR_OK
+
+
+def test_backward_validation_and_workspace(lib):
+    import paper_2601_16991_amd as salr
+    fake = 0x1000
+    q = lib.salr_linear_backward_workspace_bytes
+    assert q(512, 4096, 4096, 32, 1, 1) > 2 * 4096 * 4096 * 2     # decoded weight and its transpose
+    assert q(512, 4096, 4096, 32, 0, 1) < q(512, 4096, 4096, 32, 1, 1)
+    assert q(512, 4096, 4096, 32, 1, 1) % 256 == 0
+    assert q(500, 4096, 4096, 32, 1, 1) == 0 and q(500, 4096, 4096, 32, 1, 0) > 0    # dA / dB want M % 32 == 0
+    assert q(512, 4096, 4000, 32, 1, 0) == 0 and q(512, 4100, 4096, 32, 1, 0) == 0 and q(512, 4096, 4096, 300, 1, 1) == 0
+
+    def call(M=64, K=64, N=64, R=8, x=fake, dy=fake, bm=fake, ro=fake, a=fake, b=fake, dx=fake, da=fake, db=fake, ws=fake,
+             ws_bytes=1 << 30):
+        return lib.salr_sparse_lowrank_linear_backward(x, dy, M, K, N, bm, fake, ro, a, b, R, dx, da, db, ws, ws_bytes, None)
+
+    assert call(M=-1) == salr.SALR_ERR_INVALID_ARG
+    assert call(dy=None) == salr.SALR_ERR_INVALID_ARG
+    assert call(bm=None) == salr.SALR_ERR_INVALID_ARG
+    assert call(x=None) == salr.SALR_ERR_INVALID_ARG              # dA / dB asked for
+    assert call(a=None) == salr.SALR_ERR_INVALID_ARG
+    assert call(K=40) == salr.SALR_ERR_SHAPE
+    assert call(N=96) == salr.SALR_ERR_UNSUPPORTED                # dX wants N % 64 == 0
+    assert call(M=40) == salr.SALR_ERR_UNSUPPORTED                # dA / dB want M % 32 == 0
+    assert call(R=257) == salr.SALR_ERR_UNSUPPORTED
+    assert call(ws=None) == salr.SALR_ERR_CAPACITY
+    assert call(ws_bytes=64) == salr.SALR_ERR_CAPACITY
+    assert call(dx=None, da=None, db=None) == salr.SALR_OK        # nothing asked for
+    assert call(M=0) == salr.SALR_OK

@@ -185,3 +185,50 @@ def test_concat_adapters_is_the_sum_over_adapters():
     a2, b2 = wl.concat_adapters(A16, B16)
     np.testing.assert_array_equal(a1, a2)
     np.testing.assert_array_equal(b1, b2)
+
+
+def test_backward_is_the_adjoint_of_the_forward():
+    """<dY, Y(X)> = <dX, X>;  <dY, Y(A + dA') - Y(A)> = <dA, dA'>;  the same for B.  The forward pass is the oracle's C
+    code, so the numpy products in linear_backward are pinned by something that is not numpy."""
+    M, K, N, ranks = 5, 64, 12, (3, 2)
+    x, w, a_cat, b_cat = (wl.gaussian_bf16((M, K), 1.0, 1), wl.gaussian_bf16((N, K), 0.5, 2), None, None)
+    w_hat = oracle.mask_topk_rows(w, K // 2)
+    As = [wl.gaussian_bf16((K, r), 0.5, 10 + i) for i, r in enumerate(ranks)]
+    Bs = [wl.gaussian_bf16((r, N), 0.5, 20 + i) for i, r in enumerate(ranks)]
+    a_cat, b_cat = wl.concat_adapters(As, Bs)
+    dy = wl.gaussian_bf16((M, N), 1.0, 3)
+    dx, da, db = oracle.linear_backward(x, dy, w_hat, a_cat, b_cat)
+    assert dx.shape == (M, K) and da.shape == a_cat.shape and db.shape == b_cat.shape
+    y = oracle.linear(x, w_hat, a_cat, b_cat)
+    assert abs(np.sum(_f64(dy) * y) - np.sum(dx * _f64(x))) < 1e-9 * np.sum(np.abs(_f64(dy) * y))
+    # directions that are themselves bf16 patterns, so that A + dA' is exactly representable as an oracle input is not
+    # needed: Y is linear in A and in B, so Y(dA', B) - Y(0, B) = (X dA') B
+    a2 = wl.gaussian_bf16(a_cat.shape, 0.5, 30)
+    y_dir = oracle.linear(x, np.zeros_like(w_hat), a2, b_cat)
+    assert abs(np.sum(_f64(dy) * y_dir) - np.sum(da * _f64(a2))) < 1e-9 * np.sum(np.abs(_f64(dy) * y_dir))
+    b2 = wl.gaussian_bf16(b_cat.shape, 0.5, 31)
+    y_dir = oracle.linear(x, np.zeros_like(w_hat), a_cat, b2)
+    assert abs(np.sum(_f64(dy) * y_dir) - np.sum(db * _f64(b2))) < 1e-9 * np.sum(np.abs(_f64(dy) * y_dir))
+
+
+def test_backward_against_python_loops():
+    M, K, N, R = 2, 32, 3, 2
+    x, dy = wl.gaussian_bf16((M, K), 1.0, 4), wl.gaussian_bf16((M, N), 1.0, 5)
+    w_hat = oracle.mask_topk_rows(wl.gaussian_bf16((N, K), 0.5, 6), 10)
+    a, b = wl.gaussian_bf16((K, R), 0.5, 7), wl.gaussian_bf16((R, N), 0.5, 8)
+    X, dY, W, A, B = (_f64(t) for t in (x, dy, w_hat, a, b))
+    dx, da, db = oracle.linear_backward(x, dy, w_hat, a, b)
+    for m in range(M):
+        for k in range(K):
+            s = sum(dY[m, n] * W[n, k] for n in range(N))
+            s += sum(sum(dY[m, n] * B[r, n] for n in range(N)) * A[k, r] for r in range(R))
+            assert abs(dx[m, k] - s) < 1e-12
+    for k in range(K):
+        for r in range(R):
+            assert abs(da[k, r] - sum(X[m, k] * sum(dY[m, n] * B[r, n] for n in range(N)) for m in range(M))) < 1e-12
+    for r in range(R):
+        for n in range(N):
+            assert abs(db[r, n] - sum(sum(X[m, k] * A[k, r] for k in range(K)) * dY[m, n] for m in range(M))) < 1e-12
+    only_dx, none_a, none_b = oracle.linear_backward(x, dy, w_hat, None, None)
+    assert none_a is None and none_b is None
+    np.testing.assert_allclose(only_dx, dY @ W, atol=1e-12)
