@@ -254,6 +254,42 @@ def time_prepare(layer, steps):
     return res
 
 
+def time_backward(layer, M, steps):
+    """Backward pass of the layer (dX, dA, dB) at batch M: wall time per call and TFLOP/s on its algorithmic flops
+    2 M N K (dX) + 2 M R (N + K) (dY B^T and its way back through A^T) + 4 M K R (X A, dA) + 2 M R N (dB)."""
+    import numpy as np
+    import torch
+    import paper_2601_16991_amd as salr
+    import salr_workloads as wl
+    cfg = layer.cfg
+    dev = layer.w_hat.device
+    x = torch.from_numpy(wl.activations(cfg, M).view(np.int16)).to(dev)
+    dy = torch.from_numpy(wl.gaussian_bf16((M, cfg.N), 1.0, 4242).view(np.int16)).to(dev)
+    bitmap, values, offsets = layer.enc[0]
+    R = layer.R
+    dx = torch.empty((M, cfg.K), dtype=torch.int16, device=dev)
+    da = torch.empty((cfg.K, R), dtype=torch.int16, device=dev)
+    db = torch.empty((R, cfg.N), dtype=torch.int16, device=dev)
+    ws = torch.empty(salr.salr_linear_backward_workspace_bytes(M, cfg.K, cfg.N, R, True, True), dtype=torch.uint8, device=dev)
+    res = {}
+    for name, outs in (("dx", (dx, None, None)), ("dx_da_db", (dx, da, db))):
+        def fn():
+            salr.salr_sparse_lowrank_linear_backward(x, dy, bitmap, values, offsets, layer.a_cat, layer.b_cat, *outs, ws)
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        flops = 2 * M * cfg.N * cfg.K + 2 * M * R * (cfg.N + cfg.K)
+        if outs[1] is not None:
+            flops += 4 * M * cfg.K * R + 2 * M * R * cfg.N
+        res[name] = {"ms": round(ms, 4), "TFLOP/s": round(flops / ms / 1e9, 1)}
+    return res
+
+
 def cpu_baseline(cfg, permille, M, alg_bytes, budget_s=10.0, max_reps=50):
     import numpy as np
     import oracle
@@ -418,6 +454,8 @@ def main():
         log("codec:", extras["codec_" + cfg.name])
         extras["prepare_" + cfg.name] = time_prepare(layer, 10)
         log("prepare:", extras["prepare_" + cfg.name])
+        extras["backward_" + cfg.name + "_M2048"] = time_backward(layer, 2048, 10)
+        log("backward:", extras["backward_" + cfg.name + "_M2048"])
         del layer
         torch.cuda.empty_cache()
         # prefill-sized, MFMA-bound layers: decode stage + T + dense MFMA stage per call (wall), and the MFMA stage alone
