@@ -195,6 +195,15 @@ __global__ __launch_bounds__(NW * 64, (S == 2 && MT == 1) ? 4 : 1) void linear_s
     // A piece of up to 89 values spans at most 12 vectors (3 per lane); denser chunks need 5 per lane.
     const bool dense_slice = __builtin_amdgcn_ballot_w64(longest > 89u) != 0;  // wave-uniform
 
+    // X rows of this lane: row 16 mt + n, its 8 k of a k-step at + 8 g (rows past M are computed on row M-1's data
+    // and never stored)
+    const uint16_t* xrow[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const int m = 16 * mt + n;
+        xrow[mt] = x + (int64_t)(m < M ? m : M - 1) * K + 8 * g;
+    }
+
     // Fetch everything chunk c needs: NV value vectors per lane and the X operands of its 4 k-steps.
     // Lanes whose vector lies past the piece re-read its last vector (never used); an empty piece reads
     // the start of X instead (always mapped).  No per-lane branches: all requests go out back to back.
@@ -212,14 +221,25 @@ __global__ __launch_bounds__(NW * 64, (S == 2 && MT == 1) ? 4 : 1) void linear_s
             const uint32_t v = g + 4 * i;
             st.vq[i] = vb[v < last ? v : last];
         }
-#pragma unroll
-        for (int s = 0; s < kChunkWords; ++s) {
-            int64_t k = (c * kChunkWords + s) * 32 + 8 * g;
-            k = k < K ? k : K - 8;  // ragged last chunk: the weight operand is zero there
+        if constexpr (kVecBitmap && MT >= 2) {
+            // whole chunks only (K % 128 == 0): one address per row tile, the 4 k-steps at constant offsets (with one
+            // row tile the two registers of the hoisted pointer cost more than the address arithmetic they save)
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
-                const int m = 16 * mt + n;  // rows past M are computed on row M-1's data and never stored
-                st.xq[s * MT + mt] = *reinterpret_cast<const uint4*>(x + (int64_t)(m < M ? m : M - 1) * K + k);
+                const uint16_t* xc = xrow[mt] + c * (kChunkWords * 32);
+#pragma unroll
+                for (int s = 0; s < kChunkWords; ++s) st.xq[s * MT + mt] = *reinterpret_cast<const uint4*>(xc + 32 * s);
+            }
+        } else {
+#pragma unroll
+            for (int s = 0; s < kChunkWords; ++s) {
+                int64_t k = (c * kChunkWords + s) * 32 + 8 * g;
+                k = k < K ? k : K - 8;  // ragged last chunk: the weight operand is zero there
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    const int m = 16 * mt + n;
+                    st.xq[s * MT + mt] = *reinterpret_cast<const uint4*>(x + (int64_t)(m < M ? m : M - 1) * K + k);
+                }
             }
         }
     };
