@@ -141,6 +141,23 @@ def test_residual_adapter_on_a_decaying_spectrum(N, K, r, oversample, iters, dec
     assert np.all(np.diff(s) <= 1e-6 * s[0])
 
 
+def test_residual_adapter_smallest_sizes_and_full_rank():
+    """32 x 32 (the smallest legal size) with a sketch as wide as the matrix: the range finder spans everything, the
+    result is the exact truncated SVD up to rounding; also a sketch width that is not a multiple of 16."""
+    rng = np.random.default_rng(11)
+    e_bits = oracle.f32_to_bf16(rng.standard_normal((32, 32)).astype(np.float32))
+    for r, over in ((4, 28), (5, 6)):
+        a, b, s = _run_adapter(e_bits, r, over, 3)
+        sv, opt = _optimum(e_bits, r)
+        err = np.linalg.norm(_f64(e_bits) - (_f64(a) @ _f64(b)).T)
+        print(f"[adapter] 32x32 r={r} l={r + over}: err/opt = {err / opt:.4f}", flush=True)
+        assert err >= opt * (1 - 1e-6)
+        rounding = 2.0 ** -8 * np.sqrt(np.sum(sv[:r] ** 2))
+        assert err <= np.hypot((1.001 if over == 28 else 1.10) * opt, rounding)
+        if over == 28:
+            np.testing.assert_allclose(s, sv[:r], rtol=1e-3)
+
+
 def test_residual_adapter_on_a_pruning_residual():
     """E = W - What of a Gaussian W at p = 0.5 (the workload of this build: a flat, Marchenko-Pastur-like spectrum, the
     hardest case for a subspace iteration).  The captured energy ||E||^2 - err^2 reaches 90 % of the optimum's after
