@@ -234,7 +234,7 @@ __global__ __launch_bounds__(NW * 64, (S == 2 && MT == 1) ? 4 : 1) void linear_s
 #pragma unroll
             for (int s = 0; s < kChunkWords; ++s) {
                 int64_t k = (c * kChunkWords + s) * 32 + 8 * g;
-                k = k < K ? k : K - 8;  // ragged last chunk: the weight operand is zero there
+                if constexpr (!kVecBitmap) k = k < K ? k : K - 8;  // ragged last chunk: the weight operand is zero there
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt) {
                     const int m = 16 * mt + n;
