@@ -37,13 +37,23 @@ def test_mask_rows_tie_heavy(rows, cols, keep):
     _check_rows(_few_magnitudes((rows, cols), rows * 1000 + cols), keep, "ties")
 
 
+@pytest.mark.parametrize("rows,cols,keep", [
+    (5, 8, 0), (5, 8, 8), (6, 64, 1), (3, 4096, 4096), (7, 4096, 0), (9, 8192, 4000), (5, 2056, 2055), (1, 520, 13),
+    (4, 1024, 512), (6, 3072, 77)])
+def test_mask_rows_one_wave_per_row(rows, cols, keep):
+    """Rows of up to 8192 columns in whole 8-column units go through the kernel that keeps a row in the registers of
+    one wave (four rows per workgroup): row counts that are not multiples of four, the extreme `keep` values, ties."""
+    _check_rows(_few_magnitudes((rows, cols), rows * 77 + cols), keep, "wave kernel, ties")
+    _check_rows(wl.gaussian_bf16((rows, cols), 0.02, cols + keep + 1), keep, "wave kernel, gaussian")
+
+
 @pytest.mark.parametrize("rows,cols,keep", [(5, 37, 11), (4, 4096, 2048), (3, 4099, 1230), (2, 14336, 7168)])
 def test_mask_rows_gaussian(rows, cols, keep):
     _check_rows(wl.gaussian_bf16((rows, cols), 0.02, cols + keep), keep, "gaussian")
 
 
 def test_mask_rows_longer_than_the_lds_row_cache():
-    # rows beyond 30720 columns are re-read from memory on every counting pass; vector and ragged widths
+    # rows beyond 28672 columns are re-read from memory on every pass; vector and ragged widths
     _check_rows(_few_magnitudes((2, 30728), 5), 10000, "global vec")
     _check_rows(wl.gaussian_bf16((2, 40003), 0.02, 6), 20001, "global ragged")
 
