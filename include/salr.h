@@ -122,10 +122,11 @@ salr_status_t salr_decode(const uint32_t* bitmap, const uint16_t* values, const 
 
 /*
  * Bytes of device workspace salr_sparse_lowrank_linear needs for these sizes (0 is possible).
- * It holds T = X * A_cat and, for M > 64 (where the weight is decoded once per call into a dense
- * scratch matrix that the matrix-core stage then reads), a transposed copy of A_cat, N * K bf16
- * elements of decoded weight and fp32 partial results of contractions that are split over K; nothing
- * in it outlives the call.  Returns 0 for invalid sizes.
+ * It holds T = X * A_cat and fp32 partial results of contractions that are split over K; for large
+ * batches (M > 128, or M > 64 where K is no multiple of 128), where the weight is decoded once per
+ * call into a dense scratch matrix that the matrix-core stage then reads, also a transposed copy of
+ * A_cat and N * K bf16 elements of decoded weight.  Nothing in it outlives the call.  Returns 0 for
+ * invalid sizes.
  */
 size_t salr_linear_workspace_bytes(int64_t M, int64_t K, int64_t N, int64_t R);
 

@@ -348,7 +348,7 @@ __global__ __launch_bounds__(NW * 64, (S == 2 && MT == 1) ? 4 : 1) void linear_s
 
 // ---------------------------------------------------------------------------------------------------
 // Split-K partials of T = X * A_cat for the small-batch path (Sec. 3.2, first concatenated GEMM).
-// Workgroup (slice b, rank tile rt) sums k over its slice for 16 columns of T and all M <= 64 rows
+// Workgroup (slice b, rank tile rt, row block) sums k over its slice for 16 columns of T and 64 rows of X
 // with 16x16x32 bf16 MFMAs and writes t_partial[b][m][16 rt + r] (fp32; columns >= R as zeros).
 // The main kernel adds the slices up, so no atomics and no zeroed workspace are needed.
 //   A operand: lane (m, g) = X[m][k0 + 8g .. +8)            (one 16-byte load)
@@ -369,7 +369,8 @@ __global__ __launch_bounds__(kTpThreads) void adapter_partial_kernel(const uint1
     const int64_t u_begin = units * b / slices, u_end = units * (b + 1) / slices;
     const int r = 16 * rt + i16;
     const int r_c = r < R ? r : R - 1;  // padded columns read a valid column and are zeroed at the store
-    const int mtiles = (M + 15) >> 4;
+    const int m_base = 64 * blockIdx.z;  // 64 rows of X per workgroup
+    const int mtiles = ((M - m_base < 64 ? M - m_base : 64) + 15) >> 4;
     f32x4 acc[4];
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -382,7 +383,7 @@ __global__ __launch_bounds__(kTpThreads) void adapter_partial_kernel(const uint1
 #pragma unroll
         for (int mt = 0; mt < 4; ++mt) {
             if (mt < mtiles) {  // uniform
-                const int m = 16 * mt + i16;
+                const int m = m_base + 16 * mt + i16;
                 const uint4 aq = *reinterpret_cast<const uint4*>(x + (int64_t)(m < M ? m : M - 1) * K + k0);
                 acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(aq), as_bf16x8(bq), acc[mt], 0, 0, 0);
             }
@@ -399,19 +400,23 @@ __global__ __launch_bounds__(kTpThreads) void adapter_partial_kernel(const uint1
         float s = 0.f;
 #pragma unroll
         for (int w = 0; w < kTpWaves; ++w) s += red[w][mt][e][l];
-        const int m = 16 * mt + 4 * (l >> 4) + e;
+        const int m = m_base + 16 * mt + 4 * (l >> 4) + e;
         const int rr = 16 * rt + (l & 15);
         if (m < M) t_partial[((int64_t)b * M + m) * Rpad + rr] = rr < R ? s : 0.f;
     }
+}
+
+void launch_adapter_partial(const LinearArgs& a, hipStream_t stream) {
+    const int R = (int)a.R, Rpad = (int)adapter_rank_padded(a.R);
+    hipLaunchKernelGGL(adapter_partial_kernel, dim3(kStreamTSlices, Rpad / 16, (unsigned)((a.M + 63) / 64)), dim3(kTpThreads), 0,
+                       stream, a.x, (int)a.M, a.K, a.a_cat, R, Rpad, kStreamTSlices, reinterpret_cast<float*>(a.t));
 }
 
 template <int MT, int NW, int S>
 static void launch_stream_t(const LinearArgs& a, hipStream_t stream, const TimingEvents& ev) {
     const int R = (int)a.R, Rpad = (int)adapter_rank_padded(a.R);
     float* t_partial = reinterpret_cast<float*>(a.t);
-    if (R > 0)
-        hipLaunchKernelGGL(adapter_partial_kernel, dim3(kStreamTSlices, Rpad / 16), dim3(kTpThreads), 0, stream, a.x,
-                           (int)a.M, a.K, a.a_cat, R, Rpad, kStreamTSlices, t_partial);
+    if (R > 0) launch_adapter_partial(a, stream);
     // the optional events take the kernel's own begin/end timestamps (null events = plain launch)
     const unsigned grid = (unsigned)((a.N + kStreamRows - 1) / kStreamRows);
     const int64_t wpr = a.K / 32;

@@ -76,6 +76,26 @@ def test_ragged_shapes(M, K, N, ranks):
     _assert_close(_run(x, w, a_cat, b_cat), oracle.linear(x, w, a_cat, b_cat), f"M{M} K{K} N{N} R{sum(ranks)}")
 
 
+@pytest.mark.parametrize("M,K,N,ranks,density", [
+    # 17..128 tokens on whole 128-column chunks: the row-tiled streaming path (128 weight rows per workgroup, X tile in LDS)
+    (33, 128, 132, (8,), 0.5),            # one chunk; the second row tile holds 4 rows
+    (64, 1024, 260, (16, 16), 0.5),       # K split in 2: fp32 partials, adapters ride with slice 0
+    (128, 2048, 516, (40, 60), 0.5),      # 8 m-tiles, K split in 4, four rank steps
+    (100, 384, 1000, (5,), 0.5),          # three chunks, ragged M
+    (40, 4096, 96, (), 0.5),              # K split in 8, two waves of the tile past N, no adapters
+    (17, 512, 8320, (8, 8), 0.5),         # 17..32 tokens take this path on layers of 8192 rows and more
+    (48, 16384, 64, (4,), 0.5),           # K split in 16: cursors from popcounts of up to 120 chunks to the left
+    (48, 512, 256, (8,), 1.0),            # every bit set: pieces of 128 values (17 vectors, fetched in two goes)
+    (80, 1280, 384, (16,), 0.8),          # most chunks longer than the 12 prefetched vectors
+    (64, 256, 128, (128, 128), 0.5),      # rank 256 with 64 tokens
+    (128, 256, 128, (128, 128), 0.5),     # rank 256 with 128 tokens: T fills the LDS of both X tiles
+    (128, 128, 128, (1,), 0.1),           # sparse rows, empty pieces
+])
+def test_row_tiled_path(M, K, N, ranks, density):
+    x, w, a_cat, b_cat = _problem(M, K, N, ranks, 17 * M + K + 3 * N, density=density, std_ab=0.05)
+    _assert_close(_run(x, w, a_cat, b_cat), oracle.linear(x, w, a_cat, b_cat), f"row-tiled M{M} K{K} N{N} R{sum(ranks)}")
+
+
 @pytest.mark.parametrize("M,N", [(4096, 3584), (4090, 3580)])
 def test_many_tiles_224_wide(M, N):
     """16 row blocks x 14 column blocks of 256 x 256 would leave the second round of the 256 CUs mostly empty;
@@ -185,6 +205,24 @@ def test_large_batch_full_size_sampled_rows(name, permille, M):
     assert np.isfinite(y).all()
 
 
+@pytest.mark.parametrize("name,M", [
+    ("llama3_8b_gate_up_proj", 64),    # 224 row tiles, K in one piece, 4 m-tiles
+    ("llama3_8b_down_proj", 128),      # 32 row tiles, K split in 8 (14 chunks each), 8 m-tiles, R = 64
+    ("llama3_8b_q_proj", 96),          # 32 row tiles, K split in 8 (4 chunks each)
+])
+def test_row_tiled_full_size_sampled_rows(name, M):
+    """Full-size launches of the row-tiled streaming path; the oracle checks a fixed sample of 6 rows of X across all N."""
+    cfg = wl.CONFIGS[name]
+    w_hat = oracle.mask_topk_rows(wl.dense_weight(cfg), cfg.keep(500))
+    a_cat, b_cat = wl.concat_adapters(*wl.adapters(cfg))
+    x = wl.activations(cfg, M)
+    y = _run(x, w_hat, a_cat, b_cat)
+    rows = np.array([0, 15, 16, M // 2 + 1, M - 2, M - 1])
+    y_ref = oracle.linear(np.ascontiguousarray(x[rows]), w_hat, a_cat, b_cat)
+    _assert_close(y[rows], y_ref, f"{name} M={M} (6 sampled rows)")
+    assert np.isfinite(y).all()
+
+
 @pytest.mark.parametrize("M,ranks", [(1, (8, 8)), (16, (32,)), (40, (64, 30)), (64, (128, 128))])
 def test_small_batch_one_workspace_many_calls(M, ranks):
     """The small-batch path keeps split-K partial sums of T = X A_cat in the workspace.  One workspace, first filled
@@ -204,7 +242,7 @@ def test_small_batch_one_workspace_many_calls(M, ranks):
         _assert_close(y_to_f64(y), oracle.linear(x, w, a_cat, b_cat), f"M={M} R={sum(ranks)} call {call}")
 
 
-@pytest.mark.parametrize("M,K,N", [(16, 1024, 2048), (192, 512, 1000), (300, 1024, 520)])
+@pytest.mark.parametrize("M,K,N", [(16, 1024, 2048), (64, 1024, 520), (192, 512, 1000), (300, 1024, 520)])
 def test_graph_replays(M, K, N):
     """A captured call (small-batch kernels; large-batch kernels, whose adapter part runs on a forked stream) is
     replayed with new activations in place; the program's own eager work and synchronisations run between replays,
