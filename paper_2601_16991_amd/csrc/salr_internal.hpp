@@ -117,18 +117,20 @@ inline int dense_ksplit(int64_t M, int64_t K, int64_t N) {
 }
 
 // Row-tiled streaming path (one pass over the compressed weight, X shared by the 128 rows of a workgroup): batches of
-// 17 to 128 tokens on layers whose rows come in whole 128-column chunks.  K is split over workgroups when the
+// 9 to 128 tokens on layers whose rows come in whole 128-column chunks.  K is split over workgroups when the
 // 128-row tiles alone would leave most of the chip idle; the fp32 partial outputs [ksplit, M, N] follow T in the
 // workspace.  Measured against the other paths on the Llama-3 shapes: ahead from 33 tokens on everywhere (by 15 to
-// 45 %), from 17 tokens on where the layer has thousands of rows; below that the small-batch kernel, whose waves
+// 45 %), from 9 tokens on where the layer has thousands of rows; below that the small-batch kernel, whose waves
 // run independently of each other, is as fast or faster.
 // SALR_ROWTILE_POLICY (build-time, for experiments): 0 never, 1 whenever the shape allows it.
 constexpr int64_t kRowtileMaxM = 128;
-inline int rowtile_ksplit(int64_t K, int64_t N) {
+inline int rowtile_ksplit(int64_t M, int64_t K, int64_t N) {
     const int64_t tiles = (N + 127) / 128, chunks = K / 128;
     if (N % 4 != 0) return 1;   // the reducing pass stores four outputs per thread
+    // up to 64 tokens two workgroups share a CU (and hide each other's barriers), above that one fills it
+    const int64_t enough = M <= 64 ? 448 : 224;
     int s = 1;
-    while (s < 16 && tiles * s < 224 && chunks / (s * 2) >= 4) s *= 2;
+    while (s < 16 && tiles * s < enough && chunks / (s * 2) >= 4) s *= 2;
     return s;
 }
 inline bool rowtile_possible(int64_t M, int64_t K) { return M <= kRowtileMaxM && K >= 128 && K % 128 == 0; }
@@ -140,7 +142,7 @@ inline bool uses_rowtile(int64_t M, int64_t K, int64_t N) {
     return true;
 #else
     if (N % 4 != 0 && N < 64 * 128) return false;   // K cannot be split and the row tiles are few
-    return M > 32 || (M > 16 && N >= 8192);
+    return M > 32 || (M > 8 && N >= 8192);
 #endif
 }
 // T of the row-tiled path: the split-K partials of the small-batch pre-kernel
@@ -149,7 +151,7 @@ inline size_t rowtile_t_bytes(int64_t M, int64_t K, int64_t R) {
     return round_up_256((size_t)kStreamTSlices * (size_t)M * (size_t)adapter_rank_padded(R) * sizeof(float));
 }
 inline size_t rowtile_workspace_bytes(int64_t M, int64_t K, int64_t N, int64_t R) {
-    const int ks = rowtile_ksplit(K, N);
+    const int ks = rowtile_ksplit(M, K, N);
     return rowtile_t_bytes(M, K, R) + (ks > 1 ? round_up_256((size_t)ks * (size_t)M * (size_t)N * sizeof(float)) : 0);
 }
 

@@ -19,7 +19,10 @@
 //                and rounded to bf16 once) sits in LDS where the X tiles were; every wave multiplies it with the
 //                B_cat columns of its own rows.
 //   output       every wave owns its 16 output columns outright: bf16 to y, or fp32 to partial[slice] when K is split
-//                (few rows: not enough 128-row tiles to fill the chip), summed in slice order by the reducing pass.
+//                (not enough 128-row tiles to fill the chip twice over), summed in slice order by the reducing pass.
+// Tried and left out: 16 waves per workgroup walking the two halves of K side by side and adding them up through
+// LDS, in place of a split of K over two workgroups per CU.  It saves the reducing launch, but the barrier then
+// holds 16 waves in step, and on the 70B gate/up shape it was 10 to 18 % slower than the split.
 #include <hip/hip_ext.h>
 
 #include "salr_device.hpp"
@@ -46,12 +49,13 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));  // a 16-byte vector
 
 __device__ __forceinline__ uint32_t popc4(const uint4& q) { return __popc(q.x) + __popc(q.y) + __popc(q.z) + __popc(q.w); }
 
-// MT m-tiles of 16 rows (M <= 16 MT), S chunks of packed values in flight per wave.  K % 128 == 0.
+// MT m-tiles of 16 rows (M <= 16 MT), S chunks of packed values in flight per wave.  K % 128 == 0.  Up to 4 m-tiles
+// the kernel keeps to 128 registers so that two workgroups share a CU and run through each other's barriers.
 template <int MT, int S>
-__global__ __launch_bounds__(kRtThreads, MT <= 2 ? 4 : 2) void linear_rowtile_kernel(
+__global__ __launch_bounds__(kRtThreads, MT <= 4 ? 4 : 2) void linear_rowtile_kernel(
     const uint16_t* __restrict__ x, int M, int64_t K, int64_t N, const uint32_t* __restrict__ bitmap,
-    const uint16_t* __restrict__ values, const uint32_t* __restrict__ row_offsets, const float* __restrict__ t_partial, const uint16_t* __restrict__ b_cat, int R, int Rpad, int ksplit,
-    uint16_t* __restrict__ y, float* __restrict__ y_partial) {
+    const uint16_t* __restrict__ values, const uint32_t* __restrict__ row_offsets, const float* __restrict__ t_partial,
+    const uint16_t* __restrict__ b_cat, int R, int Rpad, int ksplit, uint16_t* __restrict__ y, float* __restrict__ y_partial) {
     constexpr int kRows = 16 * MT;                                    // X rows of the tile (M padded)
     constexpr int kXVecs = kRows * 16;                                // 16-byte vectors of one X tile
     constexpr int kXPer = (kXVecs + kRtThreads - 1) / kRtThreads;     // of them per thread
@@ -301,7 +305,7 @@ static void launch_rowtile_t(const LinearArgs& a, const float* t_partial, int ks
 }
 
 hipError_t launch_linear_rowtile(const LinearArgs& a, hipStream_t stream, const TimingEvents& ev) {
-    const int ksplit = rowtile_ksplit(a.K, a.N);
+    const int ksplit = rowtile_ksplit(a.M, a.K, a.N);
     char* base = reinterpret_cast<char*>(a.t);
     const float* t_partial = reinterpret_cast<const float*>(base);
     if (a.R > 0) launch_adapter_partial(a, stream);   // split-K partials of T, summed inside the kernel

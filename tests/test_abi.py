@@ -75,20 +75,20 @@ def _y_ksplit(M, K, N):
 
 
 def _rowtile(M, K, N):
-    """Batches of 17..128 tokens on whole 128-column chunks take the row-tiled streaming path (from 33 tokens on, or on
+    """Batches of 9..128 tokens on whole 128-column chunks take the row-tiled streaming path (from 33 tokens on, or on
     layers of 8192 rows and more); not when K cannot be split (N % 4) and the 128-row tiles are few."""
     if M > 128 or K < 128 or K % 128:
         return False
     if N % 4 and N < 64 * 128:
         return False
-    return M > 32 or (M > 16 and N >= 8192)
+    return M > 32 or (M > 8 and N >= 8192)
 
 
-def _rowtile_ksplit(K, N):
+def _rowtile_ksplit(M, K, N):
     tiles, chunks, s = (N + 127) // 128, K // 128, 1
     if N % 4:
         return 1
-    while s < 16 and tiles * s < 224 and chunks // (s * 2) >= 4:
+    while s < 16 and tiles * s < (448 if M <= 64 else 224) and chunks // (s * 2) >= 4:
         s *= 2
     return s
 
@@ -100,7 +100,7 @@ def _expected_workspace(M, K, N, R):
     bf16 and, when the output has few tiles, fp32 split-K partials of Y.  Each part rounded to 256 B."""
     rp = (R + 31) // 32 * 32
     if _rowtile(M, K, N):
-        ks = _rowtile_ksplit(K, N)
+        ks = _rowtile_ksplit(M, K, N)
         return (_r256(16 * M * rp * 4) if R else 0) + (_r256(ks * M * N * 4) if ks > 1 else 0)
     if M <= 64:
         return _r256(16 * M * rp * 4) if R else 0
@@ -124,16 +124,19 @@ def test_workspace_bytes(lib):
     assert lib.salr_linear_workspace_bytes(16, 4096, 4096, 32) == 16 * 16 * 32 * 4
     assert lib.salr_linear_workspace_bytes(1, 4096, 4096, 64) == 16 * 64 * 4
     assert lib.salr_linear_workspace_bytes(32, 4096, 4096, 0) == 0
-    assert lib.salr_linear_workspace_bytes(64, 4096, 28672, 0) == 0            # 224 row tiles: K is not split
-    assert lib.salr_linear_workspace_bytes(64, 4096, 4096, 0) == 8 * 64 * 4096 * 4   # 32 row tiles: K split 8 ways
-    assert lib.salr_linear_workspace_bytes(24, 4096, 8192, 16) == 16 * 24 * 32 * 4 + 4 * 24 * 8192 * 4   # 64 row tiles: K split 4 ways
+    assert lib.salr_linear_workspace_bytes(128, 4096, 28672, 0) == 0           # 224 row tiles: K is not split
+    assert lib.salr_linear_workspace_bytes(64, 4096, 28672, 0) == 2 * 64 * 28672 * 4   # up to 64 tokens: 448 workgroups wanted
+    assert lib.salr_linear_workspace_bytes(64, 4096, 20480, 0) == 4 * 64 * 20480 * 4   # 160 row tiles, up to 64 tokens: 448 workgroups wanted
+    assert lib.salr_linear_workspace_bytes(64, 4096, 4096, 0) == 8 * 64 * 4096 * 4     # 32 row tiles: K split 8 ways (4 chunks each)
+    assert lib.salr_linear_workspace_bytes(24, 4096, 8192, 16) == 16 * 24 * 32 * 4 + 8 * 24 * 8192 * 4   # 64 row tiles: K split 8 ways
     assert lib.salr_linear_workspace_bytes(128, 4000, 4096, 0) == 0            # K % 64 != 0: no dense scratch
     assert lib.salr_linear_workspace_bytes(16, 4096, 4096, 1000) == 0          # rank not supported
     assert lib.salr_linear_workspace_bytes(2048, 4096, 14336, 0) == 14336 * 4096 * 2
     assert _t_ksplit(4096, 14336) == 32 and _t_ksplit(2048, 4096) == 16 and _y_ksplit(512, 14336, 4096) == 4
     for (M, K, N, R) in [(16, 4096, 4096, 16), (65, 4096, 4096, 1), (128, 4096, 4096, 32), (255, 64, 8, 7),
                          (33, 14336, 4096, 64), (100, 128, 130, 3), (129, 4096, 4096, 32), (64, 4096, 28672, 40),
-                         (20, 1024, 8192, 8), (20, 1024, 8190, 8), (70, 4000, 4096, 8),
+                         (20, 1024, 8192, 8), (20, 1024, 8190, 8), (70, 4000, 4096, 8), (9, 1024, 8192, 8), (8, 1024, 8192, 8),
+                         (16, 4096, 28672, 32), (40, 1152, 28672, 32), (100, 4096, 28672, 32),
                          (256, 4096, 4096, 0), (256, 4096, 4096, 32), (512, 14336, 4096, 64), (2048, 4096, 14336, 32),
                          (4096, 14336, 4096, 64), (1024, 96, 8, 32), (1024, 64, 8, 0), (300, 1024, 262, 5)]:
         assert lib.salr_linear_workspace_bytes(M, K, N, R) == _expected_workspace(M, K, N, R), (M, K, N, R)
