@@ -324,7 +324,8 @@ def load_traffic(workload_key):
 
 WORKLOADS = {"q_proj_M16": ("llama3_8b_q_proj", 16), "gate_up_M2048": ("llama3_8b_gate_up_proj", 2048),
              "down_proj_M4096": ("llama3_8b_down_proj", 4096), "gate_up_70b_M1": ("llama3_70b_gate_up_proj", 1),
-             "gate_up_70b_M16": ("llama3_70b_gate_up_proj", 16)}
+             "gate_up_70b_M16": ("llama3_70b_gate_up_proj", 16), "gate_up_M16": ("llama3_8b_gate_up_proj", 16),
+             "gate_up_M64": ("llama3_8b_gate_up_proj", 64), "down_proj_M128": ("llama3_8b_down_proj", 128)}
 
 
 def decode_result(args, name, M):
@@ -393,7 +394,8 @@ def main():
     ap.add_argument("--workload", default="q_proj_M16", choices=sorted(WORKLOADS),
                     help="q_proj_M16 (default) is the memory-bound headline; the M2048 / M4096 ones time one prefill-sized, "
                          "MFMA-bound layer as the step instead (unit TFLOP/s, roofline against the bf16 MFMA peak), the "
-                         "70b ones the largest layer at decode batch sizes (GB/s against the HBM peak)")
+                         "70b ones the largest layer at decode batch sizes and the M16 / M64 / M128 ones the 8B MLP layers at "
+                         "batch sizes in between (GB/s against the HBM peak)")
     ap.add_argument("--no-extras", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
@@ -411,7 +413,7 @@ def main():
     log("device:", torch.cuda.get_device_name(0))
     if args.workload != "q_proj_M16":
         name, m = WORKLOADS[args.workload]
-        result = decode_result(args, name, m) if m <= 64 else prefill_result(args, name, m)
+        result = decode_result(args, name, m) if m <= 128 else prefill_result(args, name, m)
         print(json.dumps(result), flush=True)
         return
 
@@ -508,6 +510,17 @@ def main():
                 "dense_gemm_ms": round(d_ms, 5), "dense_gemm_TFLOP/s": round(2 * m2 * cfg2.N * cfg2.K / d_ms / 1e9, 1),
                 "speedup_vs_dense_gemm": round(d_ms / w_ms, 3)}
             log(f"{cfg2.name} M={m2}: {extras[f'{cfg2.name}_M{m2}']}")
+            # the same layer at batch sizes between decode and prefill: one pass over the compressed weight
+            for mm in (16, 64, 128):
+                w_ms, k_ms = time_linear(layer2, mm, steps2, 3, events=True)
+                ab = wl.algorithmic_bytes(mm, cfg2.K, cfg2.N, layer2.R, layer2.nnz)
+                d_ms = time_dense(layer2, mm, steps2, 3, with_lora=False)
+                k2 = float(np.mean(k_ms))
+                extras[f"{cfg2.name}_M{mm}"] = {
+                    "ms_per_step": round(w_ms, 5), "GB/s": round(ab / w_ms / 1e6, 1), "kernel_avg_us": round(k2 * 1e3, 2),
+                    "hbm_frac_kernel": round(ab / (k2 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                    "dense_gemm_ms": round(d_ms, 5), "speedup_vs_dense_gemm": round(d_ms / w_ms, 3)}
+                log(f"{cfg2.name} M={mm}: {extras[f'{cfg2.name}_M{mm}']}")
             del layer2
             torch.cuda.empty_cache()
         result["extras"] = extras
