@@ -45,7 +45,11 @@ struct RowStage {
     uint32_t vbase;   // index of its first vector in `values`
 };
 
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));  // a 16-byte vector the compiler keeps in registers
+// native vector types (a 16-byte and an 8-byte one) that the compiler keeps in registers
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+template <bool kHalf> struct XUnitType { using type = u32x4; };
+template <> struct XUnitType<true> { using type = u32x2; };
 
 __device__ __forceinline__ uint32_t popc4(const uint4& q) { return __popc(q.x) + __popc(q.y) + __popc(q.z) + __popc(q.w); }
 
@@ -57,8 +61,6 @@ __global__ __launch_bounds__(kRtThreads, MT <= 4 ? 4 : 2) void linear_rowtile_ke
     const uint16_t* __restrict__ values, const uint32_t* __restrict__ row_offsets, const float* __restrict__ t_partial,
     const uint16_t* __restrict__ b_cat, int R, int Rpad, int ksplit, uint16_t* __restrict__ y, float* __restrict__ y_partial) {
     constexpr int kRows = 16 * MT;                                    // X rows of the tile (M padded)
-    constexpr int kXVecs = kRows * 16;                                // 16-byte vectors of one X tile
-    constexpr int kXPer = (kXVecs + kRtThreads - 1) / kRtThreads;     // of them per thread
     constexpr int kXsElems = kRows * kRtChunkCols;                    // bf16 elements of one X tile
     __shared__ __attribute__((aligned(16))) uint16_t xs[2 * kXsElems];
     __shared__ __attribute__((aligned(16))) uint32_t slots[kRtWaves * 16 * kRtSlotDwords + 8];
@@ -84,38 +86,45 @@ __global__ __launch_bounds__(kRtThreads, MT <= 4 ? 4 : 2) void linear_rowtile_ke
 
     uint32_t cur = row_offsets[row_c];  // element index in `values` of the row's next value
 
+    // Chunks past the slice read its last chunk and count as empty.  No load of the stream is conditional: the
+    // compiler can then count the requests that are younger than the one a wave waits for, and leaves them in flight.
     auto load_bitmap_chunk = [&](int64_t c) -> uint4 {
-        return c < c_end ? *reinterpret_cast<const uint4*>(brow + c * kRtChunkWords) : make_uint4(0, 0, 0, 0);
+        uint4 q = *reinterpret_cast<const uint4*>(brow + (c < c_end ? c : c_end - 1) * kRtChunkWords);
+        const uint32_t keep = c < c_end ? 0xFFFFFFFFu : 0u;
+        q.x &= keep; q.y &= keep; q.z &= keep; q.w &= keep;
+        return q;
     };
     uint4 bmq[S];  // bitmap ring: the chunks that are issued next
 #pragma unroll
     for (int i = 0; i < S; ++i) bmq[i] = load_bitmap_chunk(c_begin + i);
 
-    // ---- X tile loader: vector idx = tid + kRtThreads j is vector idx % 16 of tile row idx / 16
+    // ---- X tile loader: every thread moves kXPer units of the tile (16 bytes; 8 bytes with one m-tile, where the
+    // tile has only 256 vectors for 512 threads): unit idx = tid + kRtThreads j belongs to tile row idx / units-per-row
+    using XUnit = typename XUnitType<MT == 1>::type;
+    constexpr int kUnitElems = sizeof(XUnit) / 2;                 // bf16 elements per unit
+    constexpr int kUnitsPerRow = kRtChunkCols / kUnitElems;
+    constexpr int kXPer = kRows * kUnitsPerRow / kRtThreads;     // units per thread
+    static_assert(kXPer * kRtThreads == kRows * kUnitsPerRow, "the threads cover the tile exactly");
     const uint16_t* xsrc[kXPer];
     int xdst[kXPer];
 #pragma unroll
     for (int j = 0; j < kXPer; ++j) {
         const int idx = tid + kRtThreads * j;
-        const int r = (idx >> 4) < kRows ? (idx >> 4) : kRows - 1, v = idx & 15;
-        xsrc[j] = x + (int64_t)(r < M ? r : M - 1) * K + 8 * v;   // rows past M repeat row M-1; never stored
-        xdst[j] = r * kRtChunkCols + 8 * (v ^ (r & 15));
+        const int r = idx / kUnitsPerRow, e = (idx % kUnitsPerRow) * kUnitElems;   // row, first element of the unit
+        const int v = e >> 3;                                                      // its 16-byte vector
+        xsrc[j] = x + (int64_t)(r < M ? r : M - 1) * K + e;   // rows past M repeat row M-1; never stored
+        xdst[j] = r * kRtChunkCols + 8 * (v ^ (r & 15)) + (e & 7);
     }
-    const bool x_loader = kXVecs >= kRtThreads || tid < kXVecs;
     // tile j of the slice waits in register set j % S from S chunks before it is read until it is written to LDS
-    u32x4 xring[S][kXPer];
-    auto load_x = [&](u32x4 (&xr)[kXPer], int64_t c) {
-        const int64_t cc = c < c_end ? c : c_end - 1;   // past the slice: reload its last tile (not used)
-        if (x_loader) {
+    XUnit xring[S][kXPer];
+    auto load_x = [&](XUnit (&xr)[kXPer], int64_t c) {
+        const int64_t cc = c < c_end ? c : c_end - 1;   // past the slice: reload its last tile (its weights count as zero)
 #pragma unroll
-            for (int j = 0; j < kXPer; ++j) xr[j] = *reinterpret_cast<const u32x4*>(xsrc[j] + cc * kRtChunkCols);
-        }
+        for (int j = 0; j < kXPer; ++j) xr[j] = *reinterpret_cast<const XUnit*>(xsrc[j] + cc * kRtChunkCols);
     };
-    auto store_x = [&](const u32x4 (&xr)[kXPer], int buf) {
-        if (x_loader) {
+    auto store_x = [&](const XUnit (&xr)[kXPer], int buf) {
 #pragma unroll
-            for (int j = 0; j < kXPer; ++j) *reinterpret_cast<u32x4*>(&xs[buf * kXsElems + xdst[j]]) = xr[j];
-        }
+        for (int j = 0; j < kXPer; ++j) *reinterpret_cast<XUnit*>(&xs[buf * kXsElems + xdst[j]]) = xr[j];
     };
     if (c_begin < c_end) {
 #pragma unroll
@@ -224,28 +233,40 @@ __global__ __launch_bounds__(kRtThreads, MT <= 4 ? 4 : 2) void linear_rowtile_ke
         RowStage st[S];
 #pragma unroll
         for (int i = 0; i < S; ++i) {
-            if (c_begin + i < c_end) {
-                issue(st[i], bmq[i]);
-                bmq[i] = load_bitmap_chunk(c_begin + i + S);
-            }
+            issue(st[i], bmq[i]);
+            bmq[i] = load_bitmap_chunk(c_begin + i + S);
         }
         store_x(xring[0], 0);
         load_x(xring[0], c_begin + S);
         __syncthreads();
         int buf = 0;
-        for (int64_t c = c_begin; c < c_end; c += S) {
+        int64_t c = c_begin;
+        // Rounds of S chunks whose prefetches all lie inside the slice run without a condition: with no load of the
+        // round conditional the compiler counts the requests younger than the one a wave waits for and leaves them in
+        // flight (behind a branch it waits for everything).
+        for (; c + 2 * S <= c_end; c += S) {
+#pragma unroll
+            for (int i = 0; i < S; ++i) {
+                consume(st[i], xs + buf * kXsElems);
+                issue(st[i], bmq[i]);
+                bmq[i] = load_bitmap_chunk(c + i + 2 * S);
+                // tile c + i + 1 into the buffer read one chunk ago (all waves are past that barrier)
+                store_x(xring[(i + 1) % S], buf ^ 1);
+                load_x(xring[(i + 1) % S], c + i + 1 + S);
+                __syncthreads();    // publishes tile c + i + 1, retires tile c + i
+                buf ^= 1;
+            }
+        }
+        // the last rounds: nothing is requested past the slice
+        for (; c < c_end; c += S) {
 #pragma unroll
             for (int i = 0; i < S; ++i) {
                 if (c + i < c_end) {   // the same for the whole workgroup
                     consume(st[i], xs + buf * kXsElems);
-                    if (c + i + S < c_end) {
-                        issue(st[i], bmq[i]);
-                        bmq[i] = load_bitmap_chunk(c + i + 2 * S);
-                    }
-                    // tile c + i + 1 into the buffer read one chunk ago (all waves are past that barrier)
-                    store_x(xring[(i + 1) % S], buf ^ 1);
-                    load_x(xring[(i + 1) % S], c + i + 1 + S);
-                    __syncthreads();    // publishes tile c + i + 1, retires tile c + i
+                    if (c + i + S < c_end) issue(st[i], bmq[i]);
+                    if (c + i + 1 < c_end) store_x(xring[(i + 1) % S], buf ^ 1);
+                    if (c + i + 1 + S < c_end) load_x(xring[(i + 1) % S], c + i + 1 + S);
+                    __syncthreads();
                     buf ^= 1;
                 }
             }
