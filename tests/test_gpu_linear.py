@@ -101,6 +101,24 @@ def test_row_tiled_path(M, K, N, ranks, density):
     _assert_close(_run(x, w, a_cat, b_cat), oracle.linear(x, w, a_cat, b_cat), f"row-tiled M{M} K{K} N{N} R{sum(ranks)}")
 
 
+def test_row_tiled_random_shapes():
+    """Seeded random shapes around the row-tiled path's limits (token counts 9..128, 1..20 chunks, ragged row tiles,
+    ranks 0..70, sparse to full rows); shapes that fall outside it take the other paths, which must agree as well."""
+    rng = np.random.default_rng(2601)
+    for case in range(28):
+        M = int(rng.integers(9, 129))
+        K = 128 * int(rng.integers(1, 21))
+        N = int(rng.integers(1, 176)) * 4 if case % 4 else int(rng.integers(4, 700))
+        if case % 7 == 0:
+            N, K = 8192 + 4 * int(rng.integers(0, 40)), 128 * int(rng.integers(1, 5))
+        n_ad = int(rng.integers(0, 4))
+        ranks = tuple(int(rng.integers(1, 25)) for _ in range(n_ad))
+        density = float(rng.choice([0.1, 0.3, 0.5, 0.75, 0.9, 1.0]))
+        x, w, a_cat, b_cat = _problem(M, K, N, ranks, 5000 + case, density=density, std_ab=0.05)
+        _assert_close(_run(x, w, a_cat, b_cat), oracle.linear(x, w, a_cat, b_cat),
+                      f"random {case}: M{M} K{K} N{N} R{sum(ranks)} density {density}")
+
+
 @pytest.mark.parametrize("M,N", [(4096, 3584), (4090, 3580)])
 def test_many_tiles_224_wide(M, N):
     """16 row blocks x 14 column blocks of 256 x 256 would leave the second round of the 256 CUs mostly empty;
