@@ -162,6 +162,32 @@ salr_status_t salr_sparse_lowrank_linear(const uint16_t* x, int64_t M, int64_t K
                                          size_t workspace_bytes, void* stream);
 
 /*
+ * The layer on 2:4-masked weights (the N:M protocol of the inference-throughput table, Sec. 4).
+ *
+ * salr_bitmap_is_2of4 writes 1 to *result (device memory, one uint32) when every aligned group of four
+ * columns of the bitmap has exactly two set bits, else 0; a layer is checked once, when it is prepared.
+ *   bitmap   in   [rows, cols/32] uint32;  cols % 32 == 0 (else SHAPE)
+ *   result   out  one uint32 in device memory, written on the stream
+ *
+ * salr_sparse_lowrank_linear_2of4 computes what salr_sparse_lowrank_linear computes, arguments and
+ * rounding as there, for a weight that passes that check.  In the SALR format such a weight already is the
+ * operand of the sparse matrix-core instructions (two stored values and two 2-bit positions per group of
+ * four), so for M <= 128 and K % 128 == 0 bitmap and packed values are multiplied as they are, without the
+ * decode stage; other shapes are passed on to salr_sparse_lowrank_linear.  The precondition is not checked
+ * by this call: on a weight that fails it the result is unspecified (no memory outside the buffers is read
+ * or written).  Workspace: salr_linear_2of4_workspace_bytes(M, K, N, R) bytes.
+ * Errors of both: INVALID_ARG, SHAPE, CAPACITY, UNSUPPORTED, HIP as above.
+ */
+salr_status_t salr_bitmap_is_2of4(const uint32_t* bitmap, int64_t rows, int64_t cols, uint32_t* result,
+                                  void* stream);
+size_t salr_linear_2of4_workspace_bytes(int64_t M, int64_t K, int64_t N, int64_t R);
+salr_status_t salr_sparse_lowrank_linear_2of4(const uint16_t* x, int64_t M, int64_t K, int64_t N,
+                                              const uint32_t* bitmap, const uint16_t* values,
+                                              const uint32_t* row_offsets, const uint16_t* a_cat,
+                                              const uint16_t* b_cat, int64_t R, uint16_t* y, void* workspace,
+                                              size_t workspace_bytes, void* stream);
+
+/*
  * salr_sparse_lowrank_linear_backward -- the adjoint of the layer of Sec. 3.2 / 3.3, which fine-tuning (the
  * training-throughput comparison of Sec. 4) runs every step.  The pruned base weight is frozen and gets no
  * gradient; the concatenated adapters do:

@@ -57,6 +57,13 @@ def lib() -> ctypes.CDLL:
         L.salr_sparse_lowrank_linear.restype = ctypes.c_int
         L.salr_sparse_lowrank_linear.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _vp,
                                                  ctypes.c_size_t, _vp]
+        L.salr_bitmap_is_2of4.restype = ctypes.c_int
+        L.salr_bitmap_is_2of4.argtypes = [_vp, _i64, _i64, _vp, _vp]
+        L.salr_linear_2of4_workspace_bytes.restype = ctypes.c_size_t
+        L.salr_linear_2of4_workspace_bytes.argtypes = [_i64, _i64, _i64, _i64]
+        L.salr_sparse_lowrank_linear_2of4.restype = ctypes.c_int
+        L.salr_sparse_lowrank_linear_2of4.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _vp,
+                                                      ctypes.c_size_t, _vp]
         L.salr_residual.restype = ctypes.c_int
         L.salr_residual.argtypes = [_vp, _vp, _i64, _i64, _vp, _vp]
         L.salr_concat_adapters.restype = ctypes.c_int
@@ -172,6 +179,40 @@ def salr_sparse_lowrank_linear(x: torch.Tensor, bitmap: torch.Tensor, values: to
     _check(st, "salr_sparse_lowrank_linear")
 
 
+def salr_bitmap_is_2of4(bitmap: torch.Tensor, result: torch.Tensor, stream=None) -> None:
+    """Enqueue the check: result[0] (one uint32 on the device) = 1 iff every aligned group of four columns has two set bits."""
+    rows, wpr = bitmap.shape
+    st = lib().salr_bitmap_is_2of4(_ptr(bitmap, _U32_TYPES, "bitmap"), rows, wpr * 32, _ptr(result, _U32_TYPES, "result"),
+                                   _stream(stream))
+    _check(st, "salr_bitmap_is_2of4")
+
+
+def salr_linear_2of4_workspace_bytes(M: int, K: int, N: int, R: int) -> int:
+    return int(lib().salr_linear_2of4_workspace_bytes(M, K, N, R))
+
+
+def salr_sparse_lowrank_linear_2of4(x: torch.Tensor, bitmap: torch.Tensor, values: torch.Tensor,
+                                    row_offsets: torch.Tensor, a_cat: Optional[torch.Tensor],
+                                    b_cat: Optional[torch.Tensor], y: torch.Tensor,
+                                    workspace: Optional[torch.Tensor], stream=None) -> None:
+    """Enqueue Y = X What^T + (X A_cat) B_cat for a weight that passes salr_bitmap_is_2of4 (not checked here)."""
+    M, K = x.shape
+    N = y.shape[1]
+    R = 0 if a_cat is None else a_cat.shape[1]
+    if y.shape[0] != M or bitmap.shape[0] != N or row_offsets.numel() != N + 1:
+        raise ValueError("inconsistent shapes")
+    if R and (tuple(a_cat.shape) != (K, R) or tuple(b_cat.shape) != (R, N)):
+        raise ValueError("adapter shapes")
+    ws_ptr = None if workspace is None else workspace.data_ptr()
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = lib().salr_sparse_lowrank_linear_2of4(_ptr(x, _BF16_TYPES, "x"), M, K, N, _ptr(bitmap, _U32_TYPES, "bitmap"),
+                                               _ptr(values, _BF16_TYPES, "values"),
+                                               _ptr(row_offsets, _U32_TYPES, "row_offsets"),
+                                               _ptr(a_cat, _BF16_TYPES, "a_cat"), _ptr(b_cat, _BF16_TYPES, "b_cat"), R,
+                                               _ptr(y, _BF16_TYPES, "y"), ws_ptr, ws_bytes, _stream(stream))
+    _check(st, "salr_sparse_lowrank_linear_2of4")
+
+
 def salr_linear_backward_workspace_bytes(M: int, K: int, N: int, R: int, want_dx: bool, want_dadb: bool) -> int:
     return int(lib().salr_linear_backward_workspace_bytes(M, K, N, R, int(want_dx), int(want_dadb)))
 
@@ -221,7 +262,7 @@ class PreparedLinear:
     """The argument list of one salr_sparse_lowrank_linear call, marshalled once: ``run()`` is then a
     single foreign call on the stream that is current at that moment (for launch-bound loops)."""
 
-    def __init__(self, x, bitmap, values, row_offsets, a_cat, b_cat, y, workspace):
+    def __init__(self, x, bitmap, values, row_offsets, a_cat, b_cat, y, workspace, two_of_four=False):
         M, K = x.shape
         N = y.shape[1]
         R = 0 if a_cat is None else a_cat.shape[1]
@@ -236,7 +277,7 @@ class PreparedLinear:
                       _ptr(values, _BF16_TYPES, "values"), _ptr(row_offsets, _U32_TYPES, "row_offsets"),
                       _ptr(a_cat, _BF16_TYPES, "a_cat"), _ptr(b_cat, _BF16_TYPES, "b_cat"), R,
                       _ptr(y, _BF16_TYPES, "y"), ws_ptr, ws_bytes)
-        self._fn = lib().salr_sparse_lowrank_linear
+        self._fn = lib().salr_sparse_lowrank_linear_2of4 if two_of_four else lib().salr_sparse_lowrank_linear
 
     def run(self, stream_handle: Optional[int] = None) -> None:
         st = self._fn(*self._args, stream_handle)
@@ -372,6 +413,25 @@ def decode(bitmap: torch.Tensor, values: torch.Tensor, row_offsets: torch.Tensor
     out = torch.empty((rows, cols), dtype=torch.int16, device=bitmap.device)
     salr_decode(bitmap, values, row_offsets, rows, cols, out)
     return out
+
+
+def bitmap_is_2of4(bitmap: torch.Tensor) -> bool:
+    """Check a layer once (synchronises): does every aligned group of four columns hold exactly two stored values?"""
+    flag = torch.zeros(1, dtype=torch.int32, device=bitmap.device)
+    salr_bitmap_is_2of4(bitmap, flag)
+    return bool(int(flag.item()) == 1)
+
+
+def linear_2of4(x, bitmap, values, row_offsets, a_cat, b_cat, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    M, K = x.shape
+    N = bitmap.shape[0]
+    R = 0 if a_cat is None else a_cat.shape[1]
+    y = torch.empty((M, N), dtype=x.dtype, device=x.device)
+    need = salr_linear_2of4_workspace_bytes(M, K, N, R)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    salr_sparse_lowrank_linear_2of4(x, bitmap, values, row_offsets, a_cat, b_cat, y, workspace)
+    return y
 
 
 def linear(x, bitmap, values, row_offsets, a_cat, b_cat, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:

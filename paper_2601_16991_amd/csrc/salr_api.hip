@@ -153,6 +153,48 @@ salr_status_t salr_sparse_lowrank_linear(const uint16_t* x, int64_t M, int64_t K
     return e == hipSuccess ? SALR_OK : SALR_ERR_HIP;
 }
 
+size_t salr_linear_2of4_workspace_bytes(int64_t M, int64_t K, int64_t N, int64_t R) {
+    const size_t general = salr_linear_workspace_bytes(M, K, N, R);
+    if (M <= 0 || K <= 0 || N <= 0 || R < 0 || R > kMaxRank || K % 32 != 0 || !salr::uses_2of4_kernel(M, K, N)) return general;
+    const size_t fast = salr::rowtile_workspace_bytes(M, K, N, R);
+    return fast > general ? fast : general;
+}
+
+salr_status_t salr_sparse_lowrank_linear_2of4(const uint16_t* x, int64_t M, int64_t K, int64_t N, const uint32_t* bitmap,
+                                              const uint16_t* values, const uint32_t* row_offsets, const uint16_t* a_cat,
+                                              const uint16_t* b_cat, int64_t R, uint16_t* y, void* workspace,
+                                              size_t workspace_bytes, void* stream) {
+    if (M < 0 || K < 0 || N < 0 || R < 0) return SALR_ERR_INVALID_ARG;
+    if (M == 0 || N == 0) return SALR_OK;
+    if (K % 32 != 0) return SALR_ERR_SHAPE;
+    if (K == 0 || !salr::uses_2of4_kernel(M, K, N))   // shapes the sparse-MFMA kernel does not take: the general path
+        return salr_sparse_lowrank_linear(x, M, K, N, bitmap, values, row_offsets, a_cat, b_cat, R, y, workspace, workspace_bytes,
+                                          stream);
+    if (!y || !row_offsets || !x || !bitmap || !values) return SALR_ERR_INVALID_ARG;
+    if (R > 0 && (!a_cat || !b_cat)) return SALR_ERR_INVALID_ARG;
+    if (N > kMaxRows || K > kMaxCols) return SALR_ERR_SHAPE;
+    if (R > kMaxRank) return SALR_ERR_UNSUPPORTED;
+    const size_t need = salr_linear_2of4_workspace_bytes(M, K, N, R);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return SALR_ERR_CAPACITY;
+    salr::LinearArgs a;
+    a.x = x; a.M = M; a.K = K; a.N = N;
+    a.bitmap = bitmap; a.values = values; a.row_offsets = row_offsets;
+    a.a_cat = a_cat; a.b_cat = b_cat; a.R = R;
+    a.y = y;
+    a.t = static_cast<uint16_t*>(workspace);
+    hipError_t e = salr::launch_linear_2of4(a, static_cast<hipStream_t>(stream), salr::g_timing_events);
+    return e == hipSuccess ? SALR_OK : SALR_ERR_HIP;
+}
+
+salr_status_t salr_bitmap_is_2of4(const uint32_t* bitmap, int64_t rows, int64_t cols, uint32_t* result, void* stream) {
+    if (rows < 0 || cols < 0 || !result) return SALR_ERR_INVALID_ARG;
+    if (rows > 0 && cols > 0 && !bitmap) return SALR_ERR_INVALID_ARG;
+    if (cols % 32 != 0) return SALR_ERR_SHAPE;
+    if (rows > kMaxRows || cols > kMaxCols) return SALR_ERR_SHAPE;
+    hipError_t e = salr::launch_check_2of4(bitmap, rows, cols, result, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SALR_OK : SALR_ERR_HIP;
+}
+
 static salr_status_t backward_shape_check(int64_t M, int64_t K, int64_t N, int64_t R, bool want_dx, bool want_dadb) {
     if (K % 32 != 0) return SALR_ERR_SHAPE;
     if (N > kMaxSvdDim || K > kMaxCols || M > kMaxM) return SALR_ERR_SHAPE;

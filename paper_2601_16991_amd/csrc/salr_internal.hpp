@@ -155,6 +155,13 @@ inline size_t rowtile_workspace_bytes(int64_t M, int64_t K, int64_t N, int64_t R
     return rowtile_t_bytes(M, K, R) + (ks > 1 ? round_up_256((size_t)ks * (size_t)M * (size_t)N * sizeof(float)) : 0);
 }
 
+// The linear on 2:4-masked weights (sparse matrix-core instructions, no decode stage): same tiling, K split and
+// workspace as the row-tiled path; other shapes go through launch_linear.
+inline bool uses_2of4_kernel(int64_t M, int64_t K, int64_t N) {
+    return rowtile_possible(M, K) && !(N % 4 != 0 && N < 64 * 128);
+}
+hipError_t launch_check_2of4(const uint32_t* bitmap, int64_t rows, int64_t cols, uint32_t* flag, hipStream_t stream);
+
 // Workspace the linear needs: the small-batch path keeps fp32 split-K partials of T; the others see above.
 inline size_t linear_workspace_bytes(int64_t M, int64_t K, int64_t N, int64_t R) {
     if (M <= 0 || N <= 0) return 0;
@@ -181,6 +188,7 @@ hipError_t launch_linear(const LinearArgs& args, hipStream_t stream);
 hipError_t launch_linear_stream(const LinearArgs& args, hipStream_t stream, const TimingEvents& ev);
 hipError_t launch_linear_twostage(const LinearArgs& args, hipStream_t stream, const TimingEvents& ev);
 hipError_t launch_linear_rowtile(const LinearArgs& args, hipStream_t stream, const TimingEvents& ev);
+hipError_t launch_linear_2of4(const LinearArgs& args, hipStream_t stream, const TimingEvents& ev);
 // split-K partials of T = X * A_cat (small batches): fp32 [kStreamTSlices, M, Rpad] at the start of the workspace
 void launch_adapter_partial(const LinearArgs& args, hipStream_t stream);
 // T = X * A_cat in bf16 [M, Rpad] at the start of the workspace (every path with M > kStreamMaxM)
