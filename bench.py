@@ -119,8 +119,9 @@ class Layer:
         return [self.w_hat.view(torch.bfloat16).clone() for _ in range(n)]
 
 
-def time_linear(layer, M, steps, warmup, events=False):
-    """(ms per step by wall clock, list of per-launch kernel ms from HIP events or None)."""
+def time_linear(layer, M, steps, warmup, events=False, two_of_four=False):
+    """(ms per step by wall clock, list of per-launch kernel ms from HIP events or None).  two_of_four: the call is
+    salr_sparse_lowrank_linear_2of4 (the layer must be 2:4-masked)."""
     import numpy as np
     import torch
     import paper_2601_16991_amd as salr
@@ -129,10 +130,11 @@ def time_linear(layer, M, steps, warmup, events=False):
     dev = torch.device("cuda:0")
     x = torch.from_numpy(wl.activations(cfg, M).view(np.int16)).to(dev)
     y = torch.empty((M, cfg.N), dtype=torch.int16, device=dev)
-    ws_bytes = salr.salr_linear_workspace_bytes(M, cfg.K, cfg.N, layer.R)
-    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
+    ws_fn = salr.salr_linear_2of4_workspace_bytes if two_of_four else salr.salr_linear_workspace_bytes
+    ws = torch.empty(max(ws_fn(M, cfg.K, cfg.N, layer.R), 256), dtype=torch.uint8, device=dev)
 
-    calls = [salr.PreparedLinear(x, b, v, o, layer.a_cat, layer.b_cat, y, ws) for (b, v, o) in layer.enc]
+    calls = [salr.PreparedLinear(x, b, v, o, layer.a_cat, layer.b_cat, y, ws, two_of_four=two_of_four)
+             for (b, v, o) in layer.enc]
     stream = torch.cuda.current_stream().cuda_stream or None
 
     def call(i):
@@ -325,18 +327,25 @@ def load_traffic(workload_key):
 WORKLOADS = {"q_proj_M16": ("llama3_8b_q_proj", 16), "gate_up_M2048": ("llama3_8b_gate_up_proj", 2048),
              "down_proj_M4096": ("llama3_8b_down_proj", 4096), "gate_up_70b_M1": ("llama3_70b_gate_up_proj", 1),
              "gate_up_70b_M16": ("llama3_70b_gate_up_proj", 16), "gate_up_M16": ("llama3_8b_gate_up_proj", 16),
-             "gate_up_M64": ("llama3_8b_gate_up_proj", 64), "down_proj_M128": ("llama3_8b_down_proj", 128)}
+             "gate_up_M64": ("llama3_8b_gate_up_proj", 64), "down_proj_M128": ("llama3_8b_down_proj", 128),
+             # 2:4-masked layers through salr_sparse_lowrank_linear_2of4
+             "q_proj_M16_2of4": ("llama3_8b_q_proj", 16), "gate_up_M16_2of4": ("llama3_8b_gate_up_proj", 16),
+             "gate_up_70b_M1_2of4": ("llama3_70b_gate_up_proj", 1), "gate_up_70b_M16_2of4": ("llama3_70b_gate_up_proj", 16)}
 
 
-def decode_result(args, name, M):
+def decode_result(args, name, M, two_of_four=False):
     """One memory-bound layer other than the headline one as the step (the largest layer: 264 MB per call, so the
-    stream reaches steady state and the launch no longer matters)."""
+    stream reaches steady state and the launch no longer matters).  two_of_four: the layer is 2:4-masked and the call
+    is salr_sparse_lowrank_linear_2of4."""
     import numpy as np
+    import paper_2601_16991_amd as salr
     import salr_workloads as wl
     cfg = wl.CONFIGS[name]
-    layer = Layer(cfg, 500, max_copies=4)
+    layer = Layer(cfg, 500, max_copies=4, nm=(2, 4) if two_of_four else None)
+    if two_of_four:
+        assert salr.bitmap_is_2of4(layer.enc[0][0])
     steps, warmup = max(5, min(args.steps, 60)), max(2, min(args.warmup, 6))
-    w_ms, k_ms = time_linear(layer, M, steps, warmup, events=True)
+    w_ms, k_ms = time_linear(layer, M, steps, warmup, events=True, two_of_four=two_of_four)
     nbytes = wl.algorithmic_bytes(M, cfg.K, cfg.N, layer.R, layer.nnz)
     d_ms = time_dense(layer, M, steps, warmup, with_lora=False)
     k = float(np.mean(k_ms))
@@ -346,12 +355,15 @@ def decode_result(args, name, M):
         "metric": METRIC, "value": round(nbytes / (w_ms * 1e-3) / 1e9, 2), "unit": "GB/s", "n_gpus": 1, "steps": steps,
         "warmup": warmup, "ms_per_step": round(w_ms, 6), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{cfg.name} W[{cfg.N},{cfg.K}] p=0.5 R={layer.R} M={M}", "weight_copies_rotated": layer.ncopies,
+        "config": {"workload": f"{cfg.name} W[{cfg.N},{cfg.K}] {'2:4 mask' if two_of_four else 'p=0.5'} R={layer.R} M={M}",
+                   "weight_copies_rotated": layer.ncopies,
                    "algorithmic_bytes": nbytes},
         "speedup_vs_dense_gemm": round(d_ms / w_ms, 3), "dense_gemm_ms": round(d_ms, 6),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                     "kernel": "fused decode+GEMM kernel of salr_sparse_lowrank_linear", "kernel_avg_us": round(k * 1e3, 2)},
+                     "kernel": ("sparse-MFMA kernel of salr_sparse_lowrank_linear_2of4" if two_of_four
+                                else "fused decode+GEMM kernel of salr_sparse_lowrank_linear"),
+                     "kernel_avg_us": round(k * 1e3, 2)},
         "cpu_baseline": None,
     }
 
@@ -373,7 +385,8 @@ def prefill_result(args, name, M):
         "metric": METRIC, "value": round(fl / (w_ms * 1e-3) / 1e12, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": steps,
         "warmup": warmup, "ms_per_step": round(w_ms, 6), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{cfg.name} W[{cfg.N},{cfg.K}] p=0.5 R={layer.R} M={M}", "weight_copies_rotated": layer.ncopies,
+        "config": {"workload": f"{cfg.name} W[{cfg.N},{cfg.K}] {'2:4 mask' if two_of_four else 'p=0.5'} R={layer.R} M={M}",
+                   "weight_copies_rotated": layer.ncopies,
                    "algorithmic_flops": fl},
         "speedup_vs_dense_gemm": round(d_ms / w_ms, 3), "dense_gemm_ms": round(d_ms, 6),
         "dense_gemm_TFLOP/s": round(2 * M * cfg.N * cfg.K / d_ms / 1e9, 1),
@@ -395,7 +408,8 @@ def main():
                     help="q_proj_M16 (default) is the memory-bound headline; the M2048 / M4096 ones time one prefill-sized, "
                          "MFMA-bound layer as the step instead (unit TFLOP/s, roofline against the bf16 MFMA peak), the "
                          "70b ones the largest layer at decode batch sizes and the M16 / M64 / M128 ones the 8B MLP layers at "
-                         "batch sizes in between (GB/s against the HBM peak)")
+                         "batch sizes in between, the _2of4 ones 2:4-masked layers on the sparse matrix-core path (GB/s "
+                         "against the HBM peak)")
     ap.add_argument("--no-extras", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
@@ -413,7 +427,10 @@ def main():
     log("device:", torch.cuda.get_device_name(0))
     if args.workload != "q_proj_M16":
         name, m = WORKLOADS[args.workload]
-        result = decode_result(args, name, m) if m <= 128 else prefill_result(args, name, m)
+        if args.workload.endswith("_2of4"):
+            result = decode_result(args, name, m, two_of_four=True)
+        else:
+            result = decode_result(args, name, m) if m <= 128 else prefill_result(args, name, m)
         print(json.dumps(result), flush=True)
         return
 
@@ -477,12 +494,16 @@ def main():
             log(f"M={m}: {extras[f'{cfg.name}_M{m}']}")
         # second workload: the same layer under a 2:4 mask (constant popcount per nibble)
         layer24 = Layer(cfg, permille, nm=(2, 4))
-        w_ms, k_ms = time_linear(layer24, M, args.steps, args.warmup, events=True)
-        extras[f"{cfg.name}_M{M}_mask2of4"] = {
-            "ms_per_step": round(w_ms, 6), "GB/s": round(alg_bytes / w_ms / 1e6, 1),
-            "kernel_avg_us": round(float(np.mean(k_ms)) * 1e3, 3),
-            "hbm_frac_kernel": round(alg_bytes / (float(np.mean(k_ms)) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
-        log(f"2:4 mask, M={M}: {extras[f'{cfg.name}_M{M}_mask2of4']}")
+        assert salr.bitmap_is_2of4(layer24.enc[0][0])
+        for key, sparse_mfma in ((f"{cfg.name}_M{M}_mask2of4", False), (f"{cfg.name}_M{M}_mask2of4_sparse_mfma", True)):
+            # the general call, then salr_sparse_lowrank_linear_2of4 (bitmap and values straight into the sparse MFMA)
+            w_ms, k_ms = time_linear(layer24, M, args.steps, args.warmup, events=True, two_of_four=sparse_mfma)
+            extras[key] = {
+                "ms_per_step": round(w_ms, 6), "GB/s": round(alg_bytes / w_ms / 1e6, 1),
+                "kernel_avg_us": round(float(np.mean(k_ms)) * 1e3, 3),
+                "hbm_frac_kernel": round(alg_bytes / (float(np.mean(k_ms)) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                "speedup_vs_dense_gemm": round(dense_ms / w_ms, 3)}
+            log(f"2:4 mask, M={M}, sparse MFMA path {sparse_mfma}: {extras[key]}")
         del layer24
         extras["codec_" + cfg.name] = time_codec(layer, 20)
         log("codec:", extras["codec_" + cfg.name])

@@ -263,6 +263,177 @@ __global__ __launch_bounds__(kS4Threads, MT <= 4 ? 4 : 2) void linear_2of4_kerne
     }
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Up to 32 tokens: the shape of the small-batch streaming kernel.  A workgroup owns 16 weight rows for the whole
+// contraction, its 8 waves split K into contiguous slices and meet only in the final sum through LDS, so there is
+// no barrier in the stream, no split of K over workgroups and no reducing launch.  Per chunk a lane (n, g) loads
+// bitmap word g and its 16 stored values of row n (4 + 32 bytes) and, as lane (m, g) of the dense operand, the 32
+// activations X[m][32 g .. 32 g + 31] of the chunk (64 contiguous bytes, from the L2); S chunks are in flight.
+// Wave w applies rank step w of the adapters (T summed from the pre-kernel's partials into LDS).
+// ---------------------------------------------------------------------------------------------------
+template <int MT>
+struct S4WaveStage {
+    uint32_t word;
+    s4_u32x4 v0, v1;
+    s4_u32x4 xq[4 * MT];   // xq[4 mt + s]: X[16 mt + m][32 g + 8 s .. + 7] of the chunk
+};
+
+template <int MT, int S>
+__global__ __launch_bounds__(kS4Threads, 4) void linear_2of4_stream_kernel(
+    const uint16_t* __restrict__ x, int M, int64_t K, int64_t N, const uint32_t* __restrict__ bitmap,
+    const uint16_t* __restrict__ values, const uint32_t* __restrict__ row_offsets, const float* __restrict__ t_partial,
+    const uint16_t* __restrict__ b_cat, int R, int Rpad, uint16_t* __restrict__ y) {
+    constexpr int kTRows = 16 * MT;
+    __shared__ __attribute__((aligned(16))) float red[kS4Waves * MT * 256];
+    __shared__ __attribute__((aligned(16))) uint16_t t_lds[kTRows * kMaxRankPadded];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n = lane & 15;
+    const int g = lane >> 4;
+    const int64_t n0 = (int64_t)blockIdx.x * 16;
+    const int64_t row_c = n0 + n < N ? n0 + n : N - 1;   // rows past N are copies of row N-1, dropped at the store
+    const int64_t wpr = K >> 5;
+    const int64_t chunks_total = wpr >> 2;
+    const int64_t c_begin = chunks_total * wave / kS4Waves;
+    const int64_t c_end = chunks_total * (wave + 1) / kS4Waves;
+
+    const uint32_t nnz = row_offsets[N];
+    const uint32_t e_max = nnz >= 16u ? nnz - 16u : 0u;
+    const uint16_t* vsrc = nnz >= 16u ? values : x;
+    const uint32_t e_row = row_offsets[row_c] + 16u * (uint32_t)g;
+    const uint32_t* bword = bitmap + row_c * wpr + g;
+    const uint16_t* xrow[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const int m = 16 * mt + n;
+        xrow[mt] = x + (int64_t)(m < M ? m : M - 1) * K + 32 * g;   // tokens past M repeat token M-1; never stored
+    }
+
+    auto issue = [&](S4WaveStage<MT>& st, int64_t c) {
+        const int64_t cc = c < chunks_total ? c : chunks_total - 1;   // past the row: any chunk will do, it is not used
+        st.word = bword[cc * 4];
+        uint32_t e = e_row + 64u * (uint32_t)cc;
+        e = (e < e_max ? e : e_max) & ~7u;   // in bounds and 16-byte aligned whatever the offsets are
+        st.v0 = *reinterpret_cast<const s4_u32x4*>(vsrc + e);
+        st.v1 = *reinterpret_cast<const s4_u32x4*>(vsrc + e + 8);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+                st.xq[4 * mt + s] = *reinterpret_cast<const s4_u32x4*>(xrow[mt] + cc * kS4ChunkCols + 8 * s);
+    };
+
+    // first operand of this wave's rank step (Sec. 3.2): lane (n, g) holds B_cat[32 wave + 8 g + j][row], j = 0..7
+    const bool has_rank_step = R > 0 && wave * 32 < Rpad;
+    uint4 bq = make_uint4(0, 0, 0, 0);
+    if (has_rank_step) {
+        const int r0 = wave * 32 + 8 * g;
+        uint32_t e[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {  // rows past R meet the zero padding of T; clamp instead of predicating
+            const int r = r0 + j < R ? r0 + j : R - 1;
+            e[j] = (uint32_t)b_cat[(int64_t)r * N + row_c];
+        }
+        bq = make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16));
+    }
+
+    // T = sum of the pre-kernel's split-K partials, rounded once to bf16, kept in LDS
+    if (R > 0) {
+        const int groups = M * (Rpad >> 2);  // float4 groups of T
+        for (int i = tid; i < groups; i += kS4Threads) {
+            float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+            const float4* p = reinterpret_cast<const float4*>(t_partial) + i;
+#pragma unroll
+            for (int sl = 0; sl < kStreamTSlices; ++sl) {
+                const float4 v = p[(int64_t)sl * groups];
+                sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+            }
+            const int m = i / (Rpad >> 2), r4 = i % (Rpad >> 2);
+            uint2 o;
+            o.x = (uint32_t)f32_to_bf16_rne(sum.x) | ((uint32_t)f32_to_bf16_rne(sum.y) << 16);
+            o.y = (uint32_t)f32_to_bf16_rne(sum.z) | ((uint32_t)f32_to_bf16_rne(sum.w) << 16);
+            *reinterpret_cast<uint2*>(&t_lds[m * kMaxRankPadded + 4 * r4]) = o;
+        }
+    }
+
+    f32x4 acc[MT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    auto consume = [&](const S4WaveStage<MT>& st) {
+        const int idx = (int)index_codes_2of4(st.word);
+        const bf16x4 a0 = __builtin_bit_cast(bf16x4, make_uint2(st.v0.x, st.v0.y));
+        const bf16x4 a1 = __builtin_bit_cast(bf16x4, make_uint2(st.v0.z, st.v0.w));
+        const bf16x4 a2 = __builtin_bit_cast(bf16x4, make_uint2(st.v1.x, st.v1.y));
+        const bf16x4 a3 = __builtin_bit_cast(bf16x4, make_uint2(st.v1.z, st.v1.w));
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            acc[mt] = __builtin_amdgcn_smfmac_f32_16x16x32_bf16(a0, __builtin_bit_cast(bf16x8, st.xq[4 * mt + 0]), acc[mt], idx, 0, 0);
+            acc[mt] = __builtin_amdgcn_smfmac_f32_16x16x32_bf16(a1, __builtin_bit_cast(bf16x8, st.xq[4 * mt + 1]), acc[mt], idx, 0, 1);
+            acc[mt] = __builtin_amdgcn_smfmac_f32_16x16x32_bf16(a2, __builtin_bit_cast(bf16x8, st.xq[4 * mt + 2]), acc[mt], idx, 0, 2);
+            acc[mt] = __builtin_amdgcn_smfmac_f32_16x16x32_bf16(a3, __builtin_bit_cast(bf16x8, st.xq[4 * mt + 3]), acc[mt], idx, 0, 3);
+        }
+    };
+
+    if (c_begin < c_end) {
+        S4WaveStage<MT> st[S];
+#pragma unroll
+        for (int i = 0; i < S; ++i) issue(st[i], c_begin + i);   // (chunks past the slice are loaded and dropped)
+        int64_t c = c_begin;
+        for (; c + 2 * S <= c_end; c += S) {   // rounds without a condition, see the row-tiled kernel below
+#pragma unroll
+            for (int i = 0; i < S; ++i) {
+                consume(st[i]);
+                issue(st[i], c + i + S);
+            }
+        }
+        for (; c < c_end; c += S) {
+#pragma unroll
+            for (int i = 0; i < S; ++i) {
+                if (c + i < c_end) consume(st[i]);   // wave-uniform conditions
+                if (c + i + S < c_end) issue(st[i], c + i + S);
+            }
+        }
+    }
+
+    __syncthreads();  // T in LDS is complete
+
+    // ---- adapter k-step of this wave (Sec. 3.2): first operand = B_cat columns, second = T rows from LDS
+    if (has_rank_step) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            const int m = 16 * mt + n;
+            const uint4 tq = *reinterpret_cast<const uint4*>(&t_lds[(m < M ? m : M - 1) * kMaxRankPadded + wave * 32 + 8 * g]);
+            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(bq), as_bf16x8(tq), acc[mt], 0, 0, 0);
+        }
+    }
+
+    // ---- add up the waves' accumulators and store: a lane of the sum holds token 16 mt + l % 16, outputs 4 (l / 16) + e
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) red[((wave * MT + mt) * 4 + e) * 64 + lane] = acc[mt][e];
+    __syncthreads();
+    for (int idx = tid; idx < MT * 256; idx += kS4Threads) {
+        const int l = idx & 63, e = (idx >> 6) & 3, mt = idx >> 8;
+        float s = 0.f;
+#pragma unroll
+        for (int w = 0; w < kS4Waves; ++w) s += red[((w * MT + mt) * 4 + e) * 64 + l];
+        const int m = 16 * mt + (l & 15);
+        const int64_t nn = n0 + 4 * (l >> 4) + e;
+        if (m < M && nn < N) y[(int64_t)m * N + nn] = f32_to_bf16_rne(s);
+    }
+}
+
+template <int MT, int S>
+static void launch_2of4_stream_t(const LinearArgs& a, const float* t_partial, hipStream_t stream, const TimingEvents& ev) {
+    const dim3 grid((unsigned)((a.N + 15) / 16));
+    SALR_LAUNCH((linear_2of4_stream_kernel<MT, S>), grid, dim3(kS4Threads), stream, ev, a.x, (int)a.M, a.K, a.N, a.bitmap,
+                a.values, a.row_offsets, t_partial, a.b_cat, (int)a.R, (int)adapter_rank_padded(a.R), a.y);
+}
+
 template <int MT, int S>
 static void launch_2of4_t(const LinearArgs& a, const float* t_partial, int ksplit, float* y_partial, hipStream_t stream,
                           const TimingEvents& ev) {
@@ -277,6 +448,13 @@ hipError_t launch_linear_2of4(const LinearArgs& a, hipStream_t stream, const Tim
     const float* t_partial = reinterpret_cast<const float*>(base);
     if (a.R > 0) launch_adapter_partial(a, stream);   // split-K partials of T, summed inside the kernel
     float* y_partial = reinterpret_cast<float*>(base + rowtile_t_bytes(a.M, a.K, a.R));
+    // Up to 16 tokens the barrier-free kernel is ahead where the call is short (layers of up to 2^25 elements: no
+    // reducing launch, no split of K) and, on any layer, up to 4 tokens (little X to pull through the L2 per workgroup);
+    // measured on the Llama-3 shapes.
+    if (a.M <= 16 && (a.M <= 4 || a.N * a.K <= (int64_t(1) << 25))) {
+        launch_2of4_stream_t<1, 4>(a, t_partial, stream, ev);
+        return hipGetLastError();
+    }
     if (a.M <= 16) launch_2of4_t<1, 4>(a, t_partial, ksplit, y_partial, stream, ev);
     else if (a.M <= 32) launch_2of4_t<2, 4>(a, t_partial, ksplit, y_partial, stream, ev);
     else if (a.M <= 64) launch_2of4_t<4, 2>(a, t_partial, ksplit, y_partial, stream, ev);

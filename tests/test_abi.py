@@ -253,3 +253,43 @@ def test_backward_validation_and_workspace(lib):
     assert call(ws_bytes=64) == salr.SALR_ERR_CAPACITY
     assert call(dx=None, da=None, db=None) == salr.SALR_OK        # nothing asked for
     assert call(M=0) == salr.SALR_OK
+
+
+def test_two_of_four_validation_and_workspace(lib):
+    import ctypes
+    import paper_2601_16991_amd as salr
+    fake = 0x1000
+    q, g = lib.salr_linear_2of4_workspace_bytes, lib.salr_linear_workspace_bytes
+    q.restype = g.restype = ctypes.c_size_t
+    # shapes the sparse-MFMA kernels take: the row-tiled layout (16 partials of T, partials of Y where K is split),
+    # never less than the general call needs
+    assert q(16, 4096, 4096, 32) == max(_r256(16 * 16 * 32 * 4) + _r256(8 * 16 * 4096 * 4), g(16, 4096, 4096, 32))
+    assert q(128, 4096, 28672, 0) == g(128, 4096, 28672, 0) == 0
+    assert q(1, 8192, 28672, 64) >= _r256(16 * 1 * 64 * 4)
+    # shapes passed on to the general call: its workspace
+    for (M, K, N, R) in [(200, 4096, 4096, 32), (16, 96, 64, 8), (2048, 4096, 14336, 32), (20, 640, 130, 8)]:
+        assert q(M, K, N, R) == g(M, K, N, R), (M, K, N, R)
+    assert q(16, 4096, 4096, 1000) == 0 and q(0, 4096, 4096, 8) == 0
+
+    def call(M=16, K=256, N=64, R=8, x=fake, bm=fake, v=fake, ro=fake, a=fake, b=fake, y=fake, ws=fake, ws_bytes=1 << 30):
+        return lib.salr_sparse_lowrank_linear_2of4(x, M, K, N, bm, v, ro, a, b, R, y, ws, ws_bytes, None)
+
+    assert call(M=-1) == salr.SALR_ERR_INVALID_ARG
+    assert call(x=None) == salr.SALR_ERR_INVALID_ARG
+    assert call(bm=None) == salr.SALR_ERR_INVALID_ARG
+    assert call(v=None) == salr.SALR_ERR_INVALID_ARG
+    assert call(ro=None) == salr.SALR_ERR_INVALID_ARG
+    assert call(y=None) == salr.SALR_ERR_INVALID_ARG
+    assert call(a=None) == salr.SALR_ERR_INVALID_ARG
+    assert call(K=40) == salr.SALR_ERR_SHAPE
+    assert call(R=257) == salr.SALR_ERR_UNSUPPORTED
+    assert call(ws=None) == salr.SALR_ERR_CAPACITY
+    assert call(ws_bytes=64) == salr.SALR_ERR_CAPACITY
+    assert call(M=0) == salr.SALR_OK
+    assert call(M=200, y=None) == salr.SALR_ERR_INVALID_ARG       # passed on to the general call, which validates too
+
+    chk = lib.salr_bitmap_is_2of4
+    assert chk(fake, -1, 64, fake, None) == salr.SALR_ERR_INVALID_ARG
+    assert chk(fake, 4, 64, None, None) == salr.SALR_ERR_INVALID_ARG
+    assert chk(None, 4, 64, fake, None) == salr.SALR_ERR_INVALID_ARG
+    assert chk(fake, 4, 40, fake, None) == salr.SALR_ERR_SHAPE
