@@ -143,3 +143,36 @@ def test_weight_that_fails_the_check_stays_in_bounds():
     y = salr.linear_2of4(to_dev_u16(x), to_dev_u32(rb), to_dev_u16(rv), to_dev_u32(ro), None, None)
     torch.cuda.synchronize()
     assert tuple(y.shape) == (M, N)
+
+
+@pytest.mark.parametrize("M,K,N", [(8, 1024, 2048), (64, 1024, 520)])
+def test_graph_replays(M, K, N):
+    """A captured call (the barrier-free kernel; the row-tiled one with its reducing pass) is replayed with new
+    activations in place; eager work and synchronisations run between replays, and every replay is checked."""
+    salr = _salr()
+    ranks = (32, 16)
+    x0, w_hat, a_cat, b_cat = _problem(M, K, N, ranks, seed=4343)
+    rb, rv, ro = oracle.encode(w_hat)
+    bm, v, rod = to_dev_u32(rb), to_dev_u16(rv), to_dev_u32(ro)
+    a, b = to_dev_u16(a_cat), to_dev_u16(b_cat)
+    x_dev = to_dev_u16(x0)
+    y = torch.empty((M, N), dtype=x_dev.dtype, device=dev())
+    ws = torch.empty(max(salr.salr_linear_2of4_workspace_bytes(M, K, N, sum(ranks)), 256), dtype=torch.uint8, device=dev())
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):   # one eager call first, as a capture's warm-up
+        salr.salr_sparse_lowrank_linear_2of4(x_dev, bm, v, rod, a, b, y, ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        salr.salr_sparse_lowrank_linear_2of4(x_dev, bm, v, rod, a, b, y, ws)
+    for replay in range(4):
+        x = wl.gaussian_bf16((M, K), 0.5 + replay, 8200 + replay)
+        x_dev.copy_(to_dev_u16(x))
+        graph.replay()
+        torch.cuda.synchronize()
+        _assert_close(y_to_f64(y), oracle.linear(x, w_hat, a_cat, b_cat), f"graph replay {replay}")
+        eager = salr.linear_2of4(x_dev, bm, v, rod, a, b)   # eager work between the replays, on another workspace
+        torch.cuda.synchronize()
+        assert torch.equal(eager.view(torch.int16), y.view(torch.int16)), f"replay {replay} differs from eager"
