@@ -356,6 +356,7 @@ __global__ __launch_bounds__(NW * 64, (S == 2 && MT == 1) ? 4 : 1) void linear_s
 // ---------------------------------------------------------------------------------------------------
 constexpr int kTpWaves = 4;
 constexpr int kTpThreads = kTpWaves * 64;
+constexpr int kTpBatch = 4;   // k-steps a wave has in flight
 
 __global__ __launch_bounds__(kTpThreads) void adapter_partial_kernel(const uint16_t* __restrict__ x, int M, int64_t K,
                                                                      const uint16_t* __restrict__ a_cat, int R, int Rpad,
@@ -374,18 +375,33 @@ __global__ __launch_bounds__(kTpThreads) void adapter_partial_kernel(const uint1
     f32x4 acc[4];
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    for (int64_t u = u_begin + wave; u < u_end; u += kTpWaves) {
-        const int64_t k0 = (u << 5) + 8 * g;
-        uint32_t e[8];
+    // kTpBatch k-steps per trip with all their loads issued before the first MFMA: the kernel is a handful of dependent
+    // round trips long, so they are taken side by side (steps past the slice reload its last step and are skipped)
+    for (int64_t u0 = u_begin + wave; u0 < u_end; u0 += kTpWaves * kTpBatch) {
+        uint4 bq[kTpBatch], aq[kTpBatch][4];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) e[j] = a_cat[(k0 + j) * R + r_c];
-        const uint4 bq = make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16));
+        for (int t = 0; t < kTpBatch; ++t) {
+            const int64_t u = u0 + kTpWaves * t < u_end ? u0 + kTpWaves * t : u_end - 1;
+            const int64_t k0 = (u << 5) + 8 * g;
+            uint32_t e[8];
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt) {
-            if (mt < mtiles) {  // uniform
-                const int m = m_base + 16 * mt + i16;
-                const uint4 aq = *reinterpret_cast<const uint4*>(x + (int64_t)(m < M ? m : M - 1) * K + k0);
-                acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(aq), as_bf16x8(bq), acc[mt], 0, 0, 0);
+            for (int j = 0; j < 8; ++j) e[j] = a_cat[(k0 + j) * R + r_c];
+            bq[t] = make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16));
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt) {
+                if (mt < mtiles) {  // uniform
+                    const int m = m_base + 16 * mt + i16;
+                    aq[t][mt] = *reinterpret_cast<const uint4*>(x + (int64_t)(m < M ? m : M - 1) * K + k0);
+                }
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < kTpBatch; ++t) {
+            if (u0 + kTpWaves * t < u_end) {  // uniform
+#pragma unroll
+                for (int mt = 0; mt < 4; ++mt)
+                    if (mt < mtiles)
+                        acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(aq[t][mt]), as_bf16x8(bq[t]), acc[mt], 0, 0, 0);
             }
         }
     }
