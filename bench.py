@@ -544,6 +544,22 @@ def main():
                 log(f"{cfg2.name} M={mm}: {extras[f'{cfg2.name}_M{mm}']}")
             del layer2
             torch.cuda.empty_cache()
+        # 2:4-masked layers through salr_sparse_lowrank_linear_2of4 (sparse MFMA on bitmap and values as they are)
+        for name3, m3 in (("llama3_8b_gate_up_proj", 16), ("llama3_70b_gate_up_proj", 1)):
+            cfg3 = wl.CONFIGS[name3]
+            layer3 = Layer(cfg3, 500, max_copies=4, nm=(2, 4))
+            steps3 = max(5, min(args.steps, 40))
+            w_ms, k_ms = time_linear(layer3, m3, steps3, 3, events=True, two_of_four=True)
+            ab = wl.algorithmic_bytes(m3, cfg3.K, cfg3.N, layer3.R, layer3.nnz)
+            d_ms = time_dense(layer3, m3, steps3, 3, with_lora=False)
+            k3 = float(np.mean(k_ms))
+            extras[f"{cfg3.name}_M{m3}_mask2of4_sparse_mfma"] = {
+                "ms_per_step": round(w_ms, 5), "GB/s": round(ab / w_ms / 1e6, 1), "kernel_avg_us": round(k3 * 1e3, 2),
+                "hbm_frac_kernel": round(ab / (k3 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                "dense_gemm_ms": round(d_ms, 5), "speedup_vs_dense_gemm": round(d_ms / w_ms, 3)}
+            log(f"{cfg3.name} M={m3}, 2:4 mask, sparse MFMA path: {extras[f'{cfg3.name}_M{m3}_mask2of4_sparse_mfma']}")
+            del layer3
+            torch.cuda.empty_cache()
         result["extras"] = extras
 
     if not args.no_cpu_baseline:
