@@ -165,7 +165,8 @@ salr_status_t salr_sparse_lowrank_linear(const uint16_t* x, int64_t M, int64_t K
  * The layer on 2:4-masked weights (the N:M protocol of the inference-throughput table, Sec. 4).
  *
  * salr_bitmap_is_2of4 writes 1 to *result (device memory, one uint32) when every aligned group of four
- * columns of the bitmap has exactly two set bits, else 0; a layer is checked once, when it is prepared.
+ * columns of the bitmap has exactly two set bits, else 0 (also for an empty bitmap); a layer is checked once,
+ * when it is prepared.
  *   bitmap   in   [rows, cols/32] uint32;  cols % 32 == 0 (else SHAPE)
  *   result   out  one uint32 in device memory, written on the stream
  *
