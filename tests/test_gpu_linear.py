@@ -247,13 +247,14 @@ def test_row_tiled_full_size_sampled_rows(name, M):
     assert np.isfinite(y).all()
 
 
-@pytest.mark.parametrize("M,ranks", [(1, (8, 8)), (16, (32,)), (40, (64, 30)), (64, (128, 128))])
-def test_small_batch_one_workspace_many_calls(M, ranks):
-    """The small-batch path keeps split-K partial sums of T = X A_cat in the workspace.  One workspace, first filled
-    with arbitrary bytes, then used by calls in a row whose X (and so T) changes: no call may see what an earlier
-    call, or nobody, left there."""
+@pytest.mark.parametrize("M,ranks,K", [(1, (8, 8), 512), (16, (32,), 512), (40, (64, 30), 512), (64, (128, 128), 512),
+                                       (100, (64, 30), 512), (128, (32,), 2048)])
+def test_small_batch_one_workspace_many_calls(M, ranks, K):
+    """The small-batch and row-tiled paths keep split-K partial sums of T = X A_cat (and, where K is split over
+    workgroups, of Y) in the workspace.  One workspace, first filled with arbitrary bytes, then used by calls in a row
+    whose X (and so T) changes: no call may see what an earlier call, or nobody, left there."""
     salr = _salr()
-    K, N = 512, 1000
+    N = 1000
     x0, w, a_cat, b_cat = _problem(M, K, N, ranks, seed=900 + M)
     rb, rv, ro = oracle.encode(w)
     d = dict(bm=to_dev_u32(rb), v=to_dev_u16(rv), ro=to_dev_u32(ro), a=to_dev_u16(a_cat), b=to_dev_u16(b_cat))
