@@ -167,13 +167,15 @@ salr_status_t salr_sparse_lowrank_linear_2of4(const uint16_t* x, int64_t M, int6
     if (M < 0 || K < 0 || N < 0 || R < 0) return SALR_ERR_INVALID_ARG;
     if (M == 0 || N == 0) return SALR_OK;
     if (K % 32 != 0) return SALR_ERR_SHAPE;
-    if (K == 0 || !salr::uses_2of4_kernel(M, K, N))   // shapes the sparse-MFMA kernel does not take: the general path
+    const bool small = salr::uses_2of4_kernel(M, K, N);        // up to 128 tokens: the streaming kernels
+    const bool large = salr::uses_2of4_gemm(M, K, N);           // above: the tiled GEMM
+    if (K == 0 || (!small && !large))   // shapes the sparse-MFMA kernels do not take: the general path
         return salr_sparse_lowrank_linear(x, M, K, N, bitmap, values, row_offsets, a_cat, b_cat, R, y, workspace, workspace_bytes,
                                           stream);
     if (!y || !row_offsets || !x || !bitmap || !values) return SALR_ERR_INVALID_ARG;
     if (R > 0 && (!a_cat || !b_cat)) return SALR_ERR_INVALID_ARG;
     if (N > kMaxRows || K > kMaxCols) return SALR_ERR_SHAPE;
-    if (R > kMaxRank) return SALR_ERR_UNSUPPORTED;
+    if (R > kMaxRank || M > kMaxM) return SALR_ERR_UNSUPPORTED;
     const size_t need = salr_linear_2of4_workspace_bytes(M, K, N, R);
     if (need > 0 && (!workspace || workspace_bytes < need)) return SALR_ERR_CAPACITY;
     salr::LinearArgs a;
@@ -182,7 +184,8 @@ salr_status_t salr_sparse_lowrank_linear_2of4(const uint16_t* x, int64_t M, int6
     a.a_cat = a_cat; a.b_cat = b_cat; a.R = R;
     a.y = y;
     a.t = static_cast<uint16_t*>(workspace);
-    hipError_t e = salr::launch_linear_2of4(a, static_cast<hipStream_t>(stream), salr::g_timing_events);
+    hipError_t e = small ? salr::launch_linear_2of4(a, static_cast<hipStream_t>(stream), salr::g_timing_events)
+                         : salr::launch_gemm_2of4(a, static_cast<hipStream_t>(stream), salr::g_timing_events);
     return e == hipSuccess ? SALR_OK : SALR_ERR_HIP;
 }
 

@@ -160,6 +160,11 @@ inline size_t rowtile_workspace_bytes(int64_t M, int64_t K, int64_t N, int64_t R
 inline bool uses_2of4_kernel(int64_t M, int64_t K, int64_t N) {
     return rowtile_possible(M, K) && !(N % 4 != 0 && N < 64 * 128);
 }
+// above 128 tokens: a tiled GEMM on the sparse MFMA (k-steps of 64 columns, four outputs per store); its workspace is
+// the T part of the large-batch layout, which the general call's workspace contains
+inline bool uses_2of4_gemm(int64_t M, int64_t K, int64_t N) {
+    return M > kRowtileMaxM && K >= 64 && K % 64 == 0 && N % 4 == 0;
+}
 hipError_t launch_check_2of4(const uint32_t* bitmap, int64_t rows, int64_t cols, uint32_t* flag, hipStream_t stream);
 
 // Workspace the linear needs: the small-batch path keeps fp32 split-K partials of T; the others see above.
@@ -189,6 +194,7 @@ hipError_t launch_linear_stream(const LinearArgs& args, hipStream_t stream, cons
 hipError_t launch_linear_twostage(const LinearArgs& args, hipStream_t stream, const TimingEvents& ev);
 hipError_t launch_linear_rowtile(const LinearArgs& args, hipStream_t stream, const TimingEvents& ev);
 hipError_t launch_linear_2of4(const LinearArgs& args, hipStream_t stream, const TimingEvents& ev);
+hipError_t launch_gemm_2of4(const LinearArgs& args, hipStream_t stream, const TimingEvents& ev);
 // split-K partials of T = X * A_cat (small batches): fp32 [kStreamTSlices, M, Rpad] at the start of the workspace
 void launch_adapter_partial(const LinearArgs& args, hipStream_t stream);
 // T = X * A_cat in bf16 [M, Rpad] at the start of the workspace (every path with M > kStreamMaxM)

@@ -58,7 +58,15 @@ def _assert_close(y, y_ref, label):
     (48, 16384, 64, (4,)),            # K split in 16
     (20, 640, 130, (8,)),             # N % 4 != 0 with few row tiles: the general path
     (16, 96, 64, (8,)),               # K % 128 != 0: the general path
-    (200, 256, 64, (8,)),             # M > 128: the general path
+    # M > 128: the tiled GEMM on the sparse MFMA (128 x 128 tiles, k-steps of 64 columns)
+    (200, 256, 64, (8,)),             # two token tiles, half a row tile
+    (129, 64, 132, (3,)),             # one k-step; second tiles of both kinds almost empty
+    (300, 512, 300, (16, 16)),        # ragged in both tile dimensions
+    (1000, 1024, 260, (40, 60)),      # 8 x 3 tiles, four rank steps
+    (256, 128, 128, ()),              # exact tiles, no adapters
+    (130, 192, 1100, (5,)),           # 9 row tiles: more than one group of 8 (the XCD map)
+    (257, 128, 513, (7,)),            # N % 4 != 0: the general path
+    (160, 96, 64, (8,)),              # K % 64 != 0: the general path
     (128, 256, 128, (128, 128)),      # rank 256 with 128 tokens
     (40, 1280, 8320, ()),             # N % 4 == 0 but ragged last tile, no adapters
     (31, 256, 8191, (3,)),            # N % 4 != 0 with many row tiles: scalar stores
@@ -106,6 +114,20 @@ def test_full_size_sampled_rows():
         y_ref = oracle.linear(np.ascontiguousarray(x[rows]), w_hat, a_cat, b_cat)
         _assert_close(y[rows], y_ref, f"gate/up 2:4 M={M} ({len(rows)} sampled tokens)")
         assert np.isfinite(y).all()
+
+
+def test_prefill_full_size_sampled_rows():
+    """Full-size launch of the tiled GEMM (gate/up, 2048 tokens, 2:4 mask); the oracle checks a sample of tokens."""
+    cfg = wl.CONFIGS["llama3_8b_gate_up_proj"]
+    M = 2048
+    w_hat = oracle.mask_nm(wl.dense_weight(cfg), 2, 4)
+    a_cat, b_cat = wl.concat_adapters(*wl.adapters(cfg))
+    x = wl.activations(cfg, M)
+    y = _run(x, w_hat, a_cat, b_cat)
+    rows = np.array([0, 1, 63, 64, 127, 128, 777, 2047])
+    y_ref = oracle.linear(np.ascontiguousarray(x[rows]), w_hat, a_cat, b_cat)
+    _assert_close(y[rows], y_ref, "gate/up 2:4 M=2048 (8 sampled tokens)")
+    assert np.isfinite(y).all()
 
 
 def test_bitmap_check():
