@@ -25,9 +25,6 @@
 
 namespace salr {
 
-#ifndef SALR_G4_BIG_MIN
-#define SALR_G4_BIG_MIN 192
-#endif
 constexpr int kG4K = 64;
 constexpr int kG4XPitch = 72;   // bf16 elements per X tile row: 144 bytes, 16 rows x 16 bytes then cover all banks once
 constexpr int kG4WPitch = 40;   // bf16 elements per values tile row: 80 bytes
@@ -229,7 +226,7 @@ hipError_t launch_gemm_2of4(const LinearArgs& a, hipStream_t stream, const Timin
     if (a.R > 0) launch_adapter_t(a, stream);   // T = X A_cat, bf16 [M, Rpad], at the start of the workspace
     // 256 x 256 tiles (8 waves, one workgroup per CU) where they fill the chip, else 128 x 128 (4 waves, two per CU)
     const int64_t big_tiles = ((a.M + 255) / 256) * ((a.N + 255) / 256);
-    if (big_tiles >= SALR_G4_BIG_MIN) launch_gemm_2of4_t<2, 4, 8, 4>(a, stream, ev);
+    if (big_tiles >= kGemm2of4BigTilesMin) launch_gemm_2of4_t<2, 4, 8, 4>(a, stream, ev);
     else launch_gemm_2of4_t<2, 2, 4, 4>(a, stream, ev);
     return hipGetLastError();
 }

@@ -162,8 +162,18 @@ inline bool uses_2of4_kernel(int64_t M, int64_t K, int64_t N) {
 }
 // above 128 tokens: a tiled GEMM on the sparse MFMA (k-steps of 64 columns, four outputs per store); its workspace is
 // the T part of the large-batch layout, which the general call's workspace contains
+// Taken where its tiles fill the chip (measured on the Llama-3 shapes: 14 to 32 % ahead of the decode + dense GEMM
+// path there, level or behind on layers of 4096 rows below 4096 tokens, which leave it too few tiles):
+// >= 192 tiles of 256 x 256, or a layer of >= 8192 rows with >= 128 tiles of 128 x 128.
+constexpr int64_t kGemm2of4BigTilesMin = 192;
 inline bool uses_2of4_gemm(int64_t M, int64_t K, int64_t N) {
-    return M > kRowtileMaxM && K >= 64 && K % 64 == 0 && N % 4 == 0;
+    if (!(M > kRowtileMaxM && K >= 64 && K % 64 == 0 && N % 4 == 0)) return false;
+#if defined(SALR_G4_ALWAYS)
+    return true;
+#else
+    const int64_t big = ((M + 255) / 256) * ((N + 255) / 256), small = ((M + 127) / 128) * ((N + 127) / 128);
+    return big >= kGemm2of4BigTilesMin || (N >= 8192 && small >= 128);
+#endif
 }
 hipError_t launch_check_2of4(const uint32_t* bitmap, int64_t rows, int64_t cols, uint32_t* flag, hipStream_t stream);
 

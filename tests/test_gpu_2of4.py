@@ -58,13 +58,16 @@ def _assert_close(y, y_ref, label):
     (48, 16384, 64, (4,)),            # K split in 16
     (20, 640, 130, (8,)),             # N % 4 != 0 with few row tiles: the general path
     (16, 96, 64, (8,)),               # K % 128 != 0: the general path
-    # M > 128: the tiled GEMM on the sparse MFMA (128 x 128 tiles, k-steps of 64 columns)
-    (200, 256, 64, (8,)),             # two token tiles, half a row tile
-    (129, 64, 132, (3,)),             # one k-step; second tiles of both kinds almost empty
-    (300, 512, 300, (16, 16)),        # ragged in both tile dimensions
-    (1000, 1024, 260, (40, 60)),      # 8 x 3 tiles, four rank steps
-    (256, 128, 128, ()),              # exact tiles, no adapters
-    (130, 192, 1100, (5,)),           # 9 row tiles: more than one group of 8 (the XCD map)
+    # M > 128 where the tiles fill the chip: the tiled GEMM on the sparse MFMA (k-steps of 64 columns)
+    (129, 64, 8196, (3,)),            # 128 x 128 tiles: one k-step; 2 x 65 tiles, the last ones almost empty
+    (300, 256, 8400, (16, 16)),       # ragged in both tile dimensions, 3 x 66 tiles, four k-steps
+    (1000, 128, 8192, (40, 60)),      # 8 x 64 tiles, four rank steps
+    (256, 128, 8192, ()),             # exact tiles, no adapters
+    (3500, 64, 3580, (8,)),           # 256 x 256 tiles (14 x 14 of them), ragged in both dimensions
+    (3585, 128, 3588, (16, 16)),      # 256 x 256 tiles, one token and four rows in the last ones
+    # M > 128 with too few tiles: the general path
+    (200, 256, 64, (8,)),
+    (1000, 1024, 260, (40, 60)),
     (257, 128, 513, (7,)),            # N % 4 != 0: the general path
     (160, 96, 64, (8,)),              # K % 64 != 0: the general path
     (128, 256, 128, (128, 128)),      # rank 256 with 128 tokens
