@@ -330,7 +330,8 @@ WORKLOADS = {"q_proj_M16": ("llama3_8b_q_proj", 16), "gate_up_M2048": ("llama3_8
              "gate_up_M64": ("llama3_8b_gate_up_proj", 64), "down_proj_M128": ("llama3_8b_down_proj", 128),
              # 2:4-masked layers through salr_sparse_lowrank_linear_2of4
              "q_proj_M16_2of4": ("llama3_8b_q_proj", 16), "gate_up_M16_2of4": ("llama3_8b_gate_up_proj", 16),
-             "gate_up_70b_M1_2of4": ("llama3_70b_gate_up_proj", 1), "gate_up_70b_M16_2of4": ("llama3_70b_gate_up_proj", 16)}
+             "gate_up_70b_M1_2of4": ("llama3_70b_gate_up_proj", 1), "gate_up_70b_M16_2of4": ("llama3_70b_gate_up_proj", 16),
+             "gate_up_M2048_2of4": ("llama3_8b_gate_up_proj", 2048), "down_proj_M4096_2of4": ("llama3_8b_down_proj", 4096)}
 
 
 def decode_result(args, name, M, two_of_four=False):
@@ -368,14 +369,18 @@ def decode_result(args, name, M, two_of_four=False):
     }
 
 
-def prefill_result(args, name, M):
-    """One MFMA-bound layer as the step: decode stage + adapter stage + dense MFMA stage per call."""
+def prefill_result(args, name, M, two_of_four=False):
+    """One MFMA-bound layer as the step: decode stage + adapter stage + dense MFMA stage per call; with two_of_four the
+    layer is 2:4-masked and the call is salr_sparse_lowrank_linear_2of4 (adapter stage + GEMM on the sparse MFMA)."""
     import numpy as np
+    import paper_2601_16991_amd as salr
     import salr_workloads as wl
     cfg = wl.CONFIGS[name]
-    layer = Layer(cfg, 500, max_copies=4)
+    layer = Layer(cfg, 500, max_copies=4, nm=(2, 4) if two_of_four else None)
+    if two_of_four:
+        assert salr.bitmap_is_2of4(layer.enc[0][0])
     steps, warmup = max(5, min(args.steps, 50)), max(2, min(args.warmup, 5))
-    w_ms, k_ms = time_linear(layer, M, steps, warmup, events=True)
+    w_ms, k_ms = time_linear(layer, M, steps, warmup, events=True, two_of_four=two_of_four)
     fl = wl.algorithmic_flops(M, cfg.K, cfg.N, layer.R)
     d_ms = time_dense(layer, M, steps, warmup, with_lora=False)
     k = float(np.mean(k_ms))
@@ -392,8 +397,11 @@ def prefill_result(args, name, M):
         "dense_gemm_TFLOP/s": round(2 * M * cfg.N * cfg.K / d_ms / 1e9, 1),
         "roofline": {"bound": "mfma", "achieved": round(achieved, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
-                     "kernel": "dense MFMA stage (dense_gemm_kernel) of salr_sparse_lowrank_linear; the decode and "
-                               "adapter stages of the call are in `value` but not in this figure",
+                     "kernel": ("GEMM on the sparse MFMA (gemm_2of4_kernel) of salr_sparse_lowrank_linear_2of4, in "
+                                "dense-equivalent flops; the adapter stage of the call is in `value` but not in this figure"
+                                if two_of_four else
+                                "dense MFMA stage (dense_gemm_kernel) of salr_sparse_lowrank_linear; the decode and "
+                                "adapter stages of the call are in `value` but not in this figure"),
                      "kernel_avg_us": round(k * 1e3, 2)},
         "cpu_baseline": None,
     }
@@ -428,7 +436,7 @@ def main():
     if args.workload != "q_proj_M16":
         name, m = WORKLOADS[args.workload]
         if args.workload.endswith("_2of4"):
-            result = decode_result(args, name, m, two_of_four=True)
+            result = (decode_result if m <= 128 else prefill_result)(args, name, m, two_of_four=True)
         else:
             result = decode_result(args, name, m) if m <= 128 else prefill_result(args, name, m)
         print(json.dumps(result), flush=True)
@@ -545,7 +553,7 @@ def main():
             del layer2
             torch.cuda.empty_cache()
         # 2:4-masked layers through salr_sparse_lowrank_linear_2of4 (sparse MFMA on bitmap and values as they are)
-        for name3, m3 in (("llama3_8b_gate_up_proj", 16), ("llama3_70b_gate_up_proj", 1)):
+        for name3, m3 in (("llama3_8b_gate_up_proj", 16), ("llama3_8b_gate_up_proj", 2048), ("llama3_70b_gate_up_proj", 1)):
             cfg3 = wl.CONFIGS[name3]
             layer3 = Layer(cfg3, 500, max_copies=4, nm=(2, 4))
             steps3 = max(5, min(args.steps, 40))
@@ -553,9 +561,11 @@ def main():
             ab = wl.algorithmic_bytes(m3, cfg3.K, cfg3.N, layer3.R, layer3.nnz)
             d_ms = time_dense(layer3, m3, steps3, 3, with_lora=False)
             k3 = float(np.mean(k_ms))
+            fl3 = wl.algorithmic_flops(m3, cfg3.K, cfg3.N, layer3.R)
             extras[f"{cfg3.name}_M{m3}_mask2of4_sparse_mfma"] = {
                 "ms_per_step": round(w_ms, 5), "GB/s": round(ab / w_ms / 1e6, 1), "kernel_avg_us": round(k3 * 1e3, 2),
                 "hbm_frac_kernel": round(ab / (k3 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                "TFLOP/s_dense_equivalent": round(fl3 / w_ms / 1e9, 1),
                 "dense_gemm_ms": round(d_ms, 5), "speedup_vs_dense_gemm": round(d_ms / w_ms, 3)}
             log(f"{cfg3.name} M={m3}, 2:4 mask, sparse MFMA path: {extras[f'{cfg3.name}_M{m3}_mask2of4_sparse_mfma']}")
             del layer3

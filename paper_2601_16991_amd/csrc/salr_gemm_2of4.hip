@@ -83,14 +83,21 @@ __global__ __launch_bounds__(64 * kWN * kWM, kWN * kWM <= 4 ? 2 : 1) void gemm_2
     const uint32_t nnz = row_offsets[N];
     const uint32_t e_max = nnz >= 8u ? nnz - 8u : 0u;
     const uint16_t* vsrc = nnz >= 8u ? values : x;   // (a weight this small cannot meet the precondition)
+    // The values tile is stored so that a lane of the sparse operand finds its two sets of four values side by side
+    // (one 16-byte read): quad q (values 4 q .. 4 q + 3 of the row's 32) belongs to set (q / 2) % 2 of lane block
+    // q / 4 + 2 (q % 2) and goes to element 8 block + 4 set of the row.
     uint32_t wbase[kWV];
-    int wdst[kWV];
+    int wdst[kWV][2];
 #pragma unroll
     for (int j = 0; j < kWV; ++j) {
         const int idx = tid + kG4Threads * j, row = idx >> 2, seg = idx & 3;
         const int64_t n = n0 + row < N ? n0 + row : N - 1;   // rows past N repeat row N-1; never stored
         wbase[j] = row_offsets[n] + 8u * (uint32_t)seg;
-        wdst[j] = row * kG4WPitch + 8 * seg;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int q = 2 * seg + h;
+            wdst[j][h] = row * kG4WPitch + 8 * ((q >> 2) + 2 * (q & 1)) + 4 * ((q >> 1) & 1);
+        }
     }
     const int brow = tid >> 1, bw = tid & 1;
     const uint32_t* bsrc = bitmap + (n0 + brow < N ? n0 + brow : N - 1) * wpr + bw;
@@ -112,7 +119,10 @@ __global__ __launch_bounds__(64 * kWN * kWM, kWN * kWM <= 4 ? 2 : 1) void gemm_2
 #pragma unroll
         for (int j = 0; j < kXV; ++j) *reinterpret_cast<g4_u32x4*>(&xs[buf][xdst[j]]) = xr[j];
 #pragma unroll
-        for (int j = 0; j < kWV; ++j) *reinterpret_cast<g4_u32x4*>(&ws[buf][wdst[j]]) = wr[j];
+        for (int j = 0; j < kWV; ++j) {
+            *reinterpret_cast<g4_u32x2*>(&ws[buf][wdst[j][0]]) = g4_u32x2{wr[j].x, wr[j].y};
+            *reinterpret_cast<g4_u32x2*>(&ws[buf][wdst[j][1]]) = g4_u32x2{wr[j].z, wr[j].w};
+        }
         bms[buf][2 * brow + bw] = g4_index_codes(br);   // the index fields of the word's four bytes, computed once per tile
     };
 
@@ -131,16 +141,13 @@ __global__ __launch_bounds__(64 * kWN * kWM, kWN * kWM <= 4 ? 2 : 1) void gemm_2
         bf16x8 a[kNI];
         int idx[kNI];
         bf16x16 b[kMJ];
-        const int vo = 16 * (kb & 1) + 4 * (kb >> 1);   // first set: stored values vo .. vo + 3 of the row's 32
-        const int sh = 8 * (kb >> 1);                   // its bitmap byte: byte kb / 2 of word kb % 2
+        const int sh = 8 * (kb >> 1);                   // bitmap byte of the first set: byte kb / 2 of word kb % 2
 #pragma unroll
         for (int i = 0; i < kNI; ++i) {
             const int nrow = 16 * kNI * wn + 16 * i + li;
             const uint32_t cw = bms[buf][2 * nrow + (kb & 1)];
             idx[i] = (int)(((cw >> sh) & 0xFFu) | ((cw >> (sh + 8)) & 0xFF00u));
-            const g4_u32x2 lo = *reinterpret_cast<const g4_u32x2*>(&ws[buf][nrow * kG4WPitch + vo]);
-            const g4_u32x2 hi = *reinterpret_cast<const g4_u32x2*>(&ws[buf][nrow * kG4WPitch + vo + 8]);
-            a[i] = __builtin_bit_cast(bf16x8, g4_u32x4{lo.x, lo.y, hi.x, hi.y});
+            a[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const g4_u32x4*>(&ws[buf][nrow * kG4WPitch + 8 * kb]));
         }
 #pragma unroll
         for (int j = 0; j < kMJ; ++j) {
