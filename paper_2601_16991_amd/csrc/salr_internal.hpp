@@ -162,9 +162,10 @@ inline bool uses_2of4_kernel(int64_t M, int64_t K, int64_t N) {
 }
 // above 128 tokens: a tiled GEMM on the sparse MFMA (k-steps of 64 columns, four outputs per store); its workspace is
 // the T part of the large-batch layout, which the general call's workspace contains
-// Taken where its tiles fill the chip (measured on the Llama-3 shapes: 14 to 32 % ahead of the decode + dense GEMM
-// path there, level or behind on layers of 4096 rows below 4096 tokens, which leave it too few tiles):
-// >= 192 tiles of 256 x 256, or a layer of >= 8192 rows with >= 128 tiles of 128 x 128.
+// Taken where its tiles fill the chip without crowding it (measured on the Llama-3 shapes: 14 to 32 % ahead of the
+// decode + dense GEMM path there): >= 192 tiles of 256 x 256 (one workgroup per CU); on layers of >= 8192 rows from
+// 128 tiles of 128 x 128 on; on smaller layers with 192 to 320 of them (about one workgroup per CU: with two the
+// 128 x 128 tiles, which read more LDS per flop, are level with the other path, and below 192 the chip is not full).
 constexpr int64_t kGemm2of4BigTilesMin = 192;
 inline bool uses_2of4_gemm(int64_t M, int64_t K, int64_t N) {
     if (!(M > kRowtileMaxM && K >= 64 && K % 64 == 0 && N % 4 == 0)) return false;
@@ -172,7 +173,8 @@ inline bool uses_2of4_gemm(int64_t M, int64_t K, int64_t N) {
     return true;
 #else
     const int64_t big = ((M + 255) / 256) * ((N + 255) / 256), small = ((M + 127) / 128) * ((N + 127) / 128);
-    return big >= kGemm2of4BigTilesMin || (N >= 8192 && small >= 128);
+    if (big >= kGemm2of4BigTilesMin) return true;
+    return N >= 8192 ? small >= 128 : (small >= 192 && small <= 320);
 #endif
 }
 hipError_t launch_check_2of4(const uint32_t* bitmap, int64_t rows, int64_t cols, uint32_t* flag, hipStream_t stream);

@@ -63,6 +63,7 @@ def _assert_close(y, y_ref, label):
     (300, 256, 8400, (16, 16)),       # ragged in both tile dimensions, 3 x 66 tiles, four k-steps
     (1000, 128, 8192, (40, 60)),      # 8 x 64 tiles, four rank steps
     (256, 128, 8192, ()),             # exact tiles, no adapters
+    (1000, 64, 3100, (8,)),           # a layer of fewer than 8192 rows with 8 x 25 tiles of 128 x 128
     (3500, 64, 3580, (8,)),           # 256 x 256 tiles (14 x 14 of them), ragged in both dimensions
     (3585, 128, 3588, (16, 16)),      # 256 x 256 tiles, one token and four rows in the last ones
     # M > 128 with too few tiles: the general path
