@@ -49,8 +49,10 @@ __global__ __launch_bounds__(64 * kWN * kWM, kWN * kWM <= 4 ? 2 : 1) void gemm_2
     const uint16_t* __restrict__ values, const uint32_t* __restrict__ row_offsets, const uint16_t* __restrict__ t,
     const uint16_t* __restrict__ b_cat, int R, int Rpad, uint16_t* __restrict__ y, int m_tiles, int n_tiles) {
     constexpr int kG4N = 16 * kNI * kWN, kG4M = 16 * kMJ * kWM, kG4Threads = 64 * kWN * kWM;
-    constexpr int kXV = kG4M * 8 / kG4Threads, kWV = kG4N * 4 / kG4Threads;   // 16-byte vectors per thread and step
-    static_assert(kXV * kG4Threads == kG4M * 8 && kWV * kG4Threads == kG4N * 4 && kG4N * 2 == kG4Threads, "loader shape");
+    constexpr int kXV = kG4M * 8 / kG4Threads;                              // 16-byte vectors per thread and step
+    constexpr int kWV = (kG4N * 4 + kG4Threads - 1) / kG4Threads;           // (a 224-row tile leaves the last waves idle here)
+    static_assert(kXV * kG4Threads == kG4M * 8 && kG4N * 2 <= kG4Threads && (kG4N * 4) % 64 == 0 && (kG4N * 2) % 64 == 0,
+                  "loader shape: whole waves take part or sit out");
     __shared__ __attribute__((aligned(16))) uint16_t xs[2][kG4M * kG4XPitch];
     __shared__ __attribute__((aligned(16))) uint16_t ws[2][kG4N * kG4WPitch];
     __shared__ uint32_t bms[2][kG4N * 2];
@@ -90,7 +92,7 @@ __global__ __launch_bounds__(64 * kWN * kWM, kWN * kWM <= 4 ? 2 : 1) void gemm_2
     int wdst[kWV][2];
 #pragma unroll
     for (int j = 0; j < kWV; ++j) {
-        const int idx = tid + kG4Threads * j, row = idx >> 2, seg = idx & 3;
+        const int idx = tid + kG4Threads * j, row = (idx >> 2) < kG4N ? (idx >> 2) : kG4N - 1, seg = idx & 3;
         const int64_t n = n0 + row < N ? n0 + row : N - 1;   // rows past N repeat row N-1; never stored
         wbase[j] = row_offsets[n] + 8u * (uint32_t)seg;
 #pragma unroll
@@ -99,31 +101,36 @@ __global__ __launch_bounds__(64 * kWN * kWM, kWN * kWM <= 4 ? 2 : 1) void gemm_2
             wdst[j][h] = row * kG4WPitch + 8 * ((q >> 2) + 2 * (q & 1)) + 4 * ((q >> 1) & 1);
         }
     }
-    const int brow = tid >> 1, bw = tid & 1;
+    const int brow = (tid >> 1) < kG4N ? (tid >> 1) : kG4N - 1, bw = tid & 1;
+    const bool b_loader = tid < 2 * kG4N;   // wave-uniform, like the w_loader conditions below
     const uint32_t* bsrc = bitmap + (n0 + brow < N ? n0 + brow : N - 1) * wpr + bw;
 
     g4_u32x4 xr[kXV], wr[kWV];
-    uint32_t br;
+    uint32_t br = 0;
     auto load_regs = [&](int64_t s) {
 #pragma unroll
         for (int j = 0; j < kXV; ++j) xr[j] = *reinterpret_cast<const g4_u32x4*>(xsrc[j] + s * kG4K);
 #pragma unroll
         for (int j = 0; j < kWV; ++j) {
-            uint32_t e = wbase[j] + 32u * (uint32_t)s;
-            e = (e < e_max ? e : e_max) & ~7u;   // in bounds and 16-byte aligned whatever the offsets are
-            wr[j] = *reinterpret_cast<const g4_u32x4*>(vsrc + e);
+            if (tid + kG4Threads * j < kG4N * 4) {
+                uint32_t e = wbase[j] + 32u * (uint32_t)s;
+                e = (e < e_max ? e : e_max) & ~7u;   // in bounds and 16-byte aligned whatever the offsets are
+                wr[j] = *reinterpret_cast<const g4_u32x4*>(vsrc + e);
+            }
         }
-        br = bsrc[2 * s];
+        if (b_loader) br = bsrc[2 * s];
     };
     auto store_regs = [&](int buf) {
 #pragma unroll
         for (int j = 0; j < kXV; ++j) *reinterpret_cast<g4_u32x4*>(&xs[buf][xdst[j]]) = xr[j];
 #pragma unroll
         for (int j = 0; j < kWV; ++j) {
-            *reinterpret_cast<g4_u32x2*>(&ws[buf][wdst[j][0]]) = g4_u32x2{wr[j].x, wr[j].y};
-            *reinterpret_cast<g4_u32x2*>(&ws[buf][wdst[j][1]]) = g4_u32x2{wr[j].z, wr[j].w};
+            if (tid + kG4Threads * j < kG4N * 4) {
+                *reinterpret_cast<g4_u32x2*>(&ws[buf][wdst[j][0]]) = g4_u32x2{wr[j].x, wr[j].y};
+                *reinterpret_cast<g4_u32x2*>(&ws[buf][wdst[j][1]]) = g4_u32x2{wr[j].z, wr[j].w};
+            }
         }
-        bms[buf][2 * brow + bw] = g4_index_codes(br);   // the index fields of the word's four bytes, computed once per tile
+        if (b_loader) bms[buf][2 * brow + bw] = g4_index_codes(br);   // the index fields of the word's four bytes, computed once per tile
     };
 
     f32x4 acc[kNI][kMJ];
@@ -231,9 +238,13 @@ static void launch_gemm_2of4_t(const LinearArgs& a, hipStream_t stream, const Ti
 
 hipError_t launch_gemm_2of4(const LinearArgs& a, hipStream_t stream, const TimingEvents& ev) {
     if (a.R > 0) launch_adapter_t(a, stream);   // T = X A_cat, bf16 [M, Rpad], at the start of the workspace
-    // 256 x 256 tiles (8 waves, one workgroup per CU) where they fill the chip, else 128 x 128 (4 waves, two per CU)
-    const int64_t big_tiles = ((a.M + 255) / 256) * ((a.N + 255) / 256);
-    if (big_tiles >= kGemm2of4BigTilesMin) launch_gemm_2of4_t<2, 4, 8, 4>(a, stream, ev);
+    // 256 x 256 tiles (8 waves, one workgroup per CU) where they fill the chip, else 128 x 128 (4 waves, two per CU);
+    // 224 rows instead of 256 where that needs less time in whole rounds of the 256 CUs (a round costs its tile width)
+    const int64_t m_tiles = (a.M + 255) / 256;
+    const int64_t t256 = m_tiles * ((a.N + 255) / 256), t224 = m_tiles * ((a.N + 223) / 224);
+    const int64_t cost256 = (t256 + 255) / 256 * 256, cost224 = (t224 + 255) / 256 * 224;
+    if (t256 >= kGemm2of4BigTilesMin && cost224 < cost256) launch_gemm_2of4_t<2, 4, 7, 4>(a, stream, ev);
+    else if (t256 >= kGemm2of4BigTilesMin) launch_gemm_2of4_t<2, 4, 8, 4>(a, stream, ev);
     else launch_gemm_2of4_t<2, 2, 4, 4>(a, stream, ev);
     return hipGetLastError();
 }

@@ -64,8 +64,9 @@ def _assert_close(y, y_ref, label):
     (1000, 128, 8192, (40, 60)),      # 8 x 64 tiles, four rank steps
     (256, 128, 8192, ()),             # exact tiles, no adapters
     (1000, 64, 3100, (8,)),           # a layer of fewer than 8192 rows with 8 x 25 tiles of 128 x 128
-    (3500, 64, 3580, (8,)),           # 256 x 256 tiles (14 x 14 of them), ragged in both dimensions
-    (3585, 128, 3588, (16, 16)),      # 256 x 256 tiles, one token and four rows in the last ones
+    (3500, 64, 3580, (8,)),           # 256 x 224 tiles (14 x 16 of them: one round of the CUs), ragged in both dimensions
+    (3585, 128, 3588, (16, 16)),      # 256 x 224 tiles, one token and four rows in the last ones
+    (3900, 64, 3836, (8,)),           # 256 x 256 tiles (16 x 15: one round; 224-wide ones would need two), ragged
     # M > 128 with too few tiles: the general path
     (200, 256, 64, (8,)),
     (1000, 1024, 260, (40, 60)),
