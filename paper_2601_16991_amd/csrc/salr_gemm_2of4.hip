@@ -175,9 +175,9 @@ __global__ __launch_bounds__(64 * kWN * kWM, kWN * kWM <= 4 ? 2 : 1) void gemm_2
     if (steps > 1) load_regs(1);
     __syncthreads();
     for (int64_t s = 0; s < steps; ++s) {
-        compute((int)(s & 1));
         if (s + 1 < steps) store_regs((int)((s + 1) & 1));   // the buffer read one step ago: all waves are past that barrier
         if (s + 2 < steps) load_regs(s + 2);
+        compute((int)(s & 1));
         __syncthreads();                                      // publishes step s + 1, retires step s
     }
 
