@@ -174,12 +174,18 @@ __global__ __launch_bounds__(64 * kWN * kWM, kWN * kWM <= 4 ? 2 : 1) void gemm_2
     store_regs(0);
     if (steps > 1) load_regs(1);
     __syncthreads();
-    for (int64_t s = 0; s < steps; ++s) {
-        if (s + 1 < steps) store_regs((int)((s + 1) & 1));   // the buffer read one step ago: all waves are past that barrier
+    auto step = [&](int64_t s, int buf) {
+        if (s + 1 < steps) store_regs(buf ^ 1);   // the buffer read one step ago: all waves are past that barrier
         if (s + 2 < steps) load_regs(s + 2);
-        compute((int)(s & 1));
-        __syncthreads();                                      // publishes step s + 1, retires step s
+        compute(buf);
+        __syncthreads();                          // publishes step s + 1, retires step s
+    };
+    int64_t s = 0;
+    for (; s + 1 < steps; s += 2) {   // two steps per trip: the buffer indices are constants
+        step(s, 0);
+        step(s + 1, 1);
     }
+    if (s < steps) step(s, 0);
 
     // ---- adapter k-steps of 32 (Sec. 3.2): first operand = B_cat columns of the weight rows, second = T rows
     if (R > 0) {
