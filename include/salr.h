@@ -16,7 +16,8 @@
  *     enqueues kernels on `stream` (a hipStream_t passed as void*, NULL = default stream).
  *   - Arguments are validated on the host before anything is enqueued; on a non-zero status no
  *     kernel has been launched and no output has been touched.
- *   - Sizes are int64_t; a dimension of 0 is legal and makes the call a no-op (SALR_OK).
+ *   - Sizes are int64_t; a dimension of 0 is legal (SALR_OK): a call whose outputs are empty does nothing, and
+ *     an empty contraction (K == 0 in the linear layer) gives the empty sum, Y = 0.
  *
  * The sparse format (Sec. 3.3, "Mapping Sparse Weights")
  *   bitmap      [rows, ceil(cols/32)] uint32.  Bit t (least significant first) of word w of a row
@@ -152,6 +153,7 @@ size_t salr_linear_workspace_bytes(int64_t M, int64_t K, int64_t N, int64_t R);
  *                     may be NULL when that size is 0.  Contents before and after are unspecified.
  *
  * Constraints: K % 32 == 0 (else SHAPE); R <= 256 (else UNSUPPORTED); M, N < 2^31.
+ * K == 0: x, bitmap, values, a_cat may be NULL; Y is written as zeros (both products are empty sums).
  * Errors: INVALID_ARG, SHAPE, CAPACITY (workspace too small), UNSUPPORTED, HIP.
  * Calls that share a workspace must be ordered by the stream.
  */
@@ -175,8 +177,10 @@ salr_status_t salr_sparse_lowrank_linear(const uint16_t* x, int64_t M, int64_t K
  * operand of the sparse matrix-core instructions (two stored values and two 2-bit positions per group of
  * four), so for M <= 128 and K % 128 == 0 bitmap and packed values are multiplied as they are, without the
  * decode stage; other shapes are passed on to salr_sparse_lowrank_linear.  The precondition is not checked
- * by this call: on a weight that fails it the result is unspecified (no memory outside the buffers is read
- * or written).  Workspace: salr_linear_2of4_workspace_bytes(M, K, N, R) bytes.
+ * by this call (the flag that salr_bitmap_is_2of4 writes lives in device memory, and reading it here would
+ * mean a synchronisation, which no entry point of this library performs: the caller reads it once per layer
+ * and picks the entry point): on a weight that fails it the result is unspecified (no memory outside the
+ * buffers is read or written).  Workspace: salr_linear_2of4_workspace_bytes(M, K, N, R) bytes.
  * Errors of both: INVALID_ARG, SHAPE, CAPACITY, UNSUPPORTED, HIP as above.
  */
 salr_status_t salr_bitmap_is_2of4(const uint32_t* bitmap, int64_t rows, int64_t cols, uint32_t* result,

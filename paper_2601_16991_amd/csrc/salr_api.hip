@@ -135,12 +135,16 @@ salr_status_t salr_sparse_lowrank_linear(const uint16_t* x, int64_t M, int64_t K
                                          size_t workspace_bytes, void* stream) {
     if (M < 0 || K < 0 || N < 0 || R < 0) return SALR_ERR_INVALID_ARG;
     if (M == 0 || N == 0) return SALR_OK;
-    if (!y || !row_offsets) return SALR_ERR_INVALID_ARG;
-    if (K > 0 && (!x || !bitmap)) return SALR_ERR_INVALID_ARG;
-    if (R > 0 && (!a_cat || !b_cat)) return SALR_ERR_INVALID_ARG;
+    if (!y) return SALR_ERR_INVALID_ARG;
+    if (K > 0 && (!x || !bitmap || !row_offsets)) return SALR_ERR_INVALID_ARG;
+    if (K > 0 && R > 0 && (!a_cat || !b_cat)) return SALR_ERR_INVALID_ARG;
     if (K % 32 != 0) return SALR_ERR_SHAPE;
     if (N > kMaxRows || K > kMaxCols) return SALR_ERR_SHAPE;
     if (R > kMaxRank || M > kMaxM) return SALR_ERR_UNSUPPORTED;
+    if (K == 0) {   // empty contraction: X W-hat^T and X A_cat are empty sums, so Y = 0; no operand is read
+        hipError_t e0 = salr::launch_fill_zero(y, M * N, static_cast<hipStream_t>(stream));
+        return e0 == hipSuccess ? SALR_OK : SALR_ERR_HIP;
+    }
     const size_t need = salr_linear_workspace_bytes(M, K, N, R);
     if (need > 0 && (!workspace || workspace_bytes < need)) return SALR_ERR_CAPACITY;
     salr::LinearArgs a;

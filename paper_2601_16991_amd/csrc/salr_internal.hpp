@@ -122,7 +122,6 @@ inline int dense_ksplit(int64_t M, int64_t K, int64_t N) {
 // workspace.  Measured against the other paths on the Llama-3 shapes: ahead from 33 tokens on everywhere (by 15 to
 // 45 %), from 9 tokens on where the layer has thousands of rows; below that the small-batch kernel, whose waves
 // run independently of each other, is as fast or faster.
-// SALR_ROWTILE_POLICY (build-time, for experiments): 0 never, 1 whenever the shape allows it.
 constexpr int64_t kRowtileMaxM = 128;
 inline int rowtile_ksplit(int64_t M, int64_t K, int64_t N) {
     const int64_t tiles = (N + 127) / 128, chunks = K / 128;
@@ -136,14 +135,8 @@ inline int rowtile_ksplit(int64_t M, int64_t K, int64_t N) {
 inline bool rowtile_possible(int64_t M, int64_t K) { return M <= kRowtileMaxM && K >= 128 && K % 128 == 0; }
 inline bool uses_rowtile(int64_t M, int64_t K, int64_t N) {
     if (!rowtile_possible(M, K)) return false;
-#if defined(SALR_ROWTILE_POLICY) && SALR_ROWTILE_POLICY == 0
-    return false;
-#elif defined(SALR_ROWTILE_POLICY) && SALR_ROWTILE_POLICY == 1
-    return true;
-#else
     if (N % 4 != 0 && N < 64 * 128) return false;   // K cannot be split and the row tiles are few
     return M > 32 || (M > 8 && N >= 8192);
-#endif
 }
 // T of the row-tiled path: the split-K partials of the small-batch pre-kernel
 inline size_t rowtile_t_bytes(int64_t M, int64_t K, int64_t R) {
@@ -169,13 +162,9 @@ inline bool uses_2of4_kernel(int64_t M, int64_t K, int64_t N) {
 constexpr int64_t kGemm2of4BigTilesMin = 192;
 inline bool uses_2of4_gemm(int64_t M, int64_t K, int64_t N) {
     if (!(M > kRowtileMaxM && K >= 64 && K % 64 == 0 && N % 4 == 0)) return false;
-#if defined(SALR_G4_ALWAYS)
-    return true;
-#else
     const int64_t big = ((M + 255) / 256) * ((N + 255) / 256), small = ((M + 127) / 128) * ((N + 127) / 128);
     if (big >= kGemm2of4BigTilesMin) return true;
     return N >= 8192 ? small >= 128 : (small >= 192 && small <= 320);
-#endif
 }
 hipError_t launch_check_2of4(const uint32_t* bitmap, int64_t rows, int64_t cols, uint32_t* flag, hipStream_t stream);
 
@@ -202,6 +191,8 @@ hipError_t launch_linear_backward(const uint16_t* x, const uint16_t* dy, int64_t
                                   uint16_t* db, void* workspace, hipStream_t stream);
 
 hipError_t launch_linear(const LinearArgs& args, hipStream_t stream);
+// count bf16 zeros (+0.0) at out
+hipError_t launch_fill_zero(uint16_t* out, int64_t count, hipStream_t stream);
 hipError_t launch_linear_stream(const LinearArgs& args, hipStream_t stream, const TimingEvents& ev);
 hipError_t launch_linear_twostage(const LinearArgs& args, hipStream_t stream, const TimingEvents& ev);
 hipError_t launch_linear_rowtile(const LinearArgs& args, hipStream_t stream, const TimingEvents& ev);

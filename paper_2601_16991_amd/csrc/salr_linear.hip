@@ -152,6 +152,19 @@ __global__ __launch_bounds__(kGenThreads) void linear_generic_kernel(
         }
 }
 
+// +0.0 into `count` bf16 elements (the layer's output when the contraction is empty)
+__global__ __launch_bounds__(256) void fill_zero_kernel(uint16_t* __restrict__ out, int64_t count) {
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count; i += stride) out[i] = 0;
+}
+
+hipError_t launch_fill_zero(uint16_t* out, int64_t count, hipStream_t stream) {
+    if (count <= 0) return hipSuccess;
+    const int64_t blocks = (count + 255) / 256;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)(blocks < 65536 ? blocks : 65536)), dim3(256), 0, stream, out, count);
+    return hipGetLastError();
+}
+
 thread_local TimingEvents g_timing_events;
 
 hipError_t launch_linear(const LinearArgs& a, hipStream_t stream) {

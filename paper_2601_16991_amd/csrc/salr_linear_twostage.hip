@@ -92,7 +92,7 @@ __global__ __launch_bounds__(64 * (8 / kMI) * kWN, (8 / kMI) * kWN / 4) void den
         asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
                      :
                      : "v"(src), "s"(lds_off)
-                     : "memory");
+                     : "memory", "m0");
     };
     auto fetch = [&](uint16_t* xs, uint16_t* ws, int64_t s) {
         const int64_t sc = s < steps ? s : steps - 1;  // past the end: reload the last step (unused)

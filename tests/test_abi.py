@@ -171,6 +171,12 @@ def test_host_validation_rejects_before_launch(lib):
     # empty problems are no-ops
     assert lin(M=0) == salr.SALR_OK
     assert lin(N=0) == salr.SALR_OK
+    # an empty contraction (K == 0) is legal with null x / bitmap / values / adapters: it passes validation (what
+    # follows is one fill of Y with zeros, which needs a device: without one the launch reports SALR_ERR_HIP)
+    st = lib.salr_sparse_lowrank_linear(None, 4, 0, 8, None, None, None, None, None, 4, fake, None, 0, None)
+    assert st in (salr.SALR_OK, salr.SALR_ERR_HIP)
+    assert lib.salr_sparse_lowrank_linear(None, 4, 0, 8, None, None, None, None, None, 4, None, None, 0, None) \
+        == salr.SALR_ERR_INVALID_ARG     # Y is still required
     # masks: keep outside [0, cols], group sizes, null pointers, empty inputs
     assert lib.salr_magnitude_mask_rows(fake, 4, 8, 9, fake, None) == salr.SALR_ERR_INVALID_ARG
     assert lib.salr_magnitude_mask_rows(fake, 4, 8, -1, fake, None) == salr.SALR_ERR_INVALID_ARG

@@ -119,6 +119,34 @@ def test_row_tiled_random_shapes():
                       f"random {case}: M{M} K{K} N{N} R{sum(ranks)} density {density}")
 
 
+@pytest.mark.parametrize("M,K,N,ranks,density", [
+    # rows longer than 32 chunks (K > 4096, K % 128 == 0): the small-batch kernel whose waves exchange the nonzero
+    # counts of their slices through LDS before the stream starts (16-byte bitmap loads)
+    (1, 4224, 48, (8, 8), 0.5),           # 33 chunks over 8 waves: slices of 4 and 5 chunks
+    (8, 8192, 100, (32, 32), 0.5),        # 8 chunks per wave, last row group ragged
+    (16, 14336, 64, (64,), 0.3),          # K of the down_proj layer: 14 chunks per wave
+    (4, 16384, 600, (), 0.5),             # no adapters
+    (16, 5120, 48, (16,), 1.0),           # every bit set: pieces of 17 vectors, the two-chunks-in-flight loop
+    (3, 28672, 48, (64,), 0.5),           # K of the 70B down_proj layer: 28 chunks per wave
+    (2, 4352, 16, (1,), 0.05),            # sparse rows: many empty pieces
+    # ... with >= 512 row groups: two workgroups per CU, two chunks in flight
+    (1, 4224, 8200, (8, 8), 0.5),
+    (8, 8192, 8192, (64,), 0.5),
+    (5, 4480, 8300, (), 0.3),
+    (8, 4608, 8192, (16, 16), 1.0),
+    # ... with 17 to 32 tokens (two row tiles of X, three chunks in flight)
+    (24, 8192, 100, (32, 32), 0.5),
+    (32, 4224, 48, (), 0.7),
+    (17, 6144, 200, (8,), 1.0),
+    # bitmap rows that are no multiple of 16 bytes (K % 128 != 0) and many chunks: scalar bitmap loads, same exchange
+    (4, 4032, 40, (8,), 0.5), (16, 8224, 33, (32,), 0.5), (40, 4128, 50, (4,), 0.5), (64, 4192, 20, (), 1.0),
+])
+def test_small_batch_long_rows(M, K, N, ranks, density):
+    x, w, a_cat, b_cat = _problem(M, K, N, ranks, 13 * M + K + 7 * N, density=density, std_ab=0.05)
+    _assert_close(_run(x, w, a_cat, b_cat), oracle.linear(x, w, a_cat, b_cat),
+                  f"long rows M{M} K{K} N{N} R{sum(ranks)} density {density}")
+
+
 @pytest.mark.parametrize("M,N", [(4096, 3584), (4090, 3580)])
 def test_many_tiles_224_wide(M, N):
     """16 row blocks x 14 column blocks of 256 x 256 would leave the second round of the 256 CUs mostly empty;
@@ -159,6 +187,22 @@ def test_no_adapters_dense_and_empty_weight(M):
     z = np.zeros_like(w)
     y = _run(x, z, None, None)
     assert (y == 0).all()
+
+
+@pytest.mark.parametrize("M,N,R", [(1, 16, 0), (16, 100, 8), (200, 300, 32)])
+def test_empty_contraction_gives_zeros(M, N, R):
+    """K == 0: both products are empty sums, so Y = 0 whatever the other operands (which may be null) hold."""
+    salr = _salr()
+    y = torch.full((M, N), 0x3F80, dtype=torch.int16, device=dev())
+    x = torch.empty((M, 0), dtype=torch.int16, device=dev())
+    bitmap = torch.empty((N, 0), dtype=torch.int32, device=dev())
+    values = torch.empty((0,), dtype=torch.int16, device=dev())
+    offsets = torch.zeros(N + 1, dtype=torch.int32, device=dev())
+    a_cat = torch.empty((0, R), dtype=torch.int16, device=dev()) if R else None
+    b_cat = to_dev_u16(wl.gaussian_bf16((R, N), 1.0, 3)) if R else None
+    salr.salr_sparse_lowrank_linear(x, bitmap, values, offsets, a_cat, b_cat, y, None)
+    torch.cuda.synchronize()
+    assert (to_host_u16(y) == 0).all()
 
 
 @pytest.mark.parametrize("M", [4, 96])

@@ -106,7 +106,9 @@ def test_theorem1_closed_form_against_papers_worked_example():
     t = NormalDist().inv_cdf((1 + g["p"]) / 2)
     assert abs(t - g["t_p"]) < 5e-4
     assert abs(math.exp(-t * t / 2) / math.sqrt(2 * math.pi) - g["phi_t_p"]) < 5e-4
-    assert abs(NormalDist().cdf(t) - g["Phi_t_p"]) < 1e-12
+    # the printed threshold, put through the normal CDF, gives the printed (1 + p) / 2
+    assert abs(NormalDist().cdf(g["t_p"]) - g["Phi_t_p"]) < 5e-4
+    assert abs((1 + g["p"]) / 2 - g["Phi_t_p"]) < 1e-12
     # the paper's 0.072 comes from rounded intermediates (0.25 - 0.214); the exact value is 0.07133
     assert abs(oracle.pruning_mse_closed_form(g["p"]) - g["mse_over_sigma2"]) < 1e-3
     # same arithmetic as printed, with the printed roundings
