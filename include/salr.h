@@ -164,6 +164,30 @@ salr_status_t salr_sparse_lowrank_linear(const uint16_t* x, int64_t M, int64_t K
                                          size_t workspace_bytes, void* stream);
 
 /*
+ * salr_sparse_lowrank_linear_noalloc -- salr_sparse_lowrank_linear for callers that cannot allocate device memory
+ * or carry a workspace around: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Arguments, result and rounding are those of salr_sparse_lowrank_linear without `workspace`; the kernels are the
+ * same ones.  What they keep in the workspace there (split-K partial sums of T = X * A_cat and of Y) lives here in a
+ * fixed array of SALR_NOALLOC_SCRATCH_BYTES bytes of device memory inside the library's code object, which every GPU
+ * the library runs on holds from the first use until the process ends.  The call allocates and frees nothing.
+ *
+ * Limit: sizes for which salr_linear_workspace_bytes(M, K, N, R) exceeds SALR_NOALLOC_SCRATCH_BYTES are refused with
+ * SALR_ERR_CAPACITY before anything is enqueued (decode-sized batches fit; batches that decode the weight into a
+ * dense scratch matrix do not).
+ * The device that is current when the call is made must be the one `stream` belongs to; the first call on a device
+ * looks up that device's copy of the array (no allocation; make it outside a graph capture).
+ * All calls on one GPU share that GPU's array: calls that may overlap on one GPU (different streams without
+ * ordering between them) race on it and must be ordered by the caller.  Nothing in the array has to survive
+ * between calls or start at zero: every call writes what it later reads.
+ * Errors: as salr_sparse_lowrank_linear, with CAPACITY as above.
+ */
+#define SALR_NOALLOC_SCRATCH_BYTES (16u * 1024u * 1024u)
+salr_status_t salr_sparse_lowrank_linear_noalloc(const uint16_t* x, int64_t M, int64_t K, int64_t N,
+                                                 const uint32_t* bitmap, const uint16_t* values,
+                                                 const uint32_t* row_offsets, const uint16_t* a_cat,
+                                                 const uint16_t* b_cat, int64_t R, uint16_t* y, void* stream);
+
+/*
  * The layer on 2:4-masked weights (the N:M protocol of the inference-throughput table, Sec. 4).
  *
  * salr_bitmap_is_2of4 writes 1 to *result (device memory, one uint32) when every aligned group of four

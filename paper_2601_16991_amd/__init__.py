@@ -57,6 +57,8 @@ def lib() -> ctypes.CDLL:
         L.salr_sparse_lowrank_linear.restype = ctypes.c_int
         L.salr_sparse_lowrank_linear.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _vp,
                                                  ctypes.c_size_t, _vp]
+        L.salr_sparse_lowrank_linear_noalloc.restype = ctypes.c_int
+        L.salr_sparse_lowrank_linear_noalloc.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _vp]
         L.salr_bitmap_is_2of4.restype = ctypes.c_int
         L.salr_bitmap_is_2of4.argtypes = [_vp, _i64, _i64, _vp, _vp]
         L.salr_linear_2of4_workspace_bytes.restype = ctypes.c_size_t
@@ -177,6 +179,28 @@ def salr_sparse_lowrank_linear(x: torch.Tensor, bitmap: torch.Tensor, values: to
                                           _ptr(a_cat, _BF16_TYPES, "a_cat"), _ptr(b_cat, _BF16_TYPES, "b_cat"), R,
                                           _ptr(y, _BF16_TYPES, "y"), ws_ptr, ws_bytes, _stream(stream))
     _check(st, "salr_sparse_lowrank_linear")
+
+
+NOALLOC_SCRATCH_BYTES = 16 * 1024 * 1024   # SALR_NOALLOC_SCRATCH_BYTES of include/salr.h
+
+
+def salr_sparse_lowrank_linear_noalloc(x: torch.Tensor, bitmap: torch.Tensor, values: torch.Tensor,
+                                       row_offsets: torch.Tensor, a_cat: Optional[torch.Tensor],
+                                       b_cat: Optional[torch.Tensor], y: torch.Tensor, stream=None) -> None:
+    """Enqueue Y = X What^T + (X A_cat) B_cat with the library's own fixed scratch array in place of a workspace."""
+    M, K = x.shape
+    N = y.shape[1]
+    R = 0 if a_cat is None else a_cat.shape[1]
+    if y.shape[0] != M or bitmap.shape[0] != N or row_offsets.numel() != N + 1:
+        raise ValueError("inconsistent shapes")
+    if R and (tuple(a_cat.shape) != (K, R) or tuple(b_cat.shape) != (R, N)):
+        raise ValueError("adapter shapes")
+    st = lib().salr_sparse_lowrank_linear_noalloc(_ptr(x, _BF16_TYPES, "x"), M, K, N, _ptr(bitmap, _U32_TYPES, "bitmap"),
+                                                  _ptr(values, _BF16_TYPES, "values"),
+                                                  _ptr(row_offsets, _U32_TYPES, "row_offsets"),
+                                                  _ptr(a_cat, _BF16_TYPES, "a_cat"), _ptr(b_cat, _BF16_TYPES, "b_cat"), R,
+                                                  _ptr(y, _BF16_TYPES, "y"), _stream(stream))
+    _check(st, "salr_sparse_lowrank_linear_noalloc")
 
 
 def salr_bitmap_is_2of4(bitmap: torch.Tensor, result: torch.Tensor, stream=None) -> None:

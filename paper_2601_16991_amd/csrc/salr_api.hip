@@ -3,7 +3,33 @@
 
 #include "salr_internal.hpp"
 
+#include <atomic>
+
 namespace {
+
+// Scratch of salr_sparse_lowrank_linear_noalloc: part of the code object, so every GPU that loads the library holds
+// its own copy at its own address.  In host code the name stands for the symbol, not for device memory: the address
+// comes from hipGetSymbolAddress, once per device, and only that address is handed to kernels.
+static __device__ __align__(256) unsigned char scratch[SALR_NOALLOC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+// Address of the current device's copy of `scratch` (looked up on the first call on that device).
+hipError_t scratch_of_current_device(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (p == nullptr) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (p == nullptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev].store(p, std::memory_order_release);   // racing first calls store the same address
+    }
+    *out = p;
+    return hipSuccess;
+}
 
 constexpr int64_t kMaxRows = 2147483647LL;        // gridDim.x
 constexpr int64_t kMaxCols = 2147483647LL - 31;   // so that ceil(cols/32)*32 stays in int32 range
@@ -155,6 +181,21 @@ salr_status_t salr_sparse_lowrank_linear(const uint16_t* x, int64_t M, int64_t K
     a.t = static_cast<uint16_t*>(workspace);
     hipError_t e = salr::launch_linear(a, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? SALR_OK : SALR_ERR_HIP;
+}
+
+salr_status_t salr_sparse_lowrank_linear_noalloc(const uint16_t* x, int64_t M, int64_t K, int64_t N, const uint32_t* bitmap,
+                                                 const uint16_t* values, const uint32_t* row_offsets,
+                                                 const uint16_t* a_cat, const uint16_t* b_cat, int64_t R, uint16_t* y,
+                                                 void* stream) {
+    if (M < 0 || K < 0 || N < 0 || R < 0) return SALR_ERR_INVALID_ARG;
+    if (M == 0 || N == 0) return SALR_OK;
+    if (K % 32 != 0) return SALR_ERR_SHAPE;
+    if (R > kMaxRank) return SALR_ERR_UNSUPPORTED;
+    const size_t need = K > 0 ? salr::linear_workspace_bytes(M, K, N, R) : 0;
+    if (need > SALR_NOALLOC_SCRATCH_BYTES) return SALR_ERR_CAPACITY;
+    void* ws = nullptr;
+    if (need > 0 && scratch_of_current_device(&ws) != hipSuccess) return SALR_ERR_HIP;
+    return salr_sparse_lowrank_linear(x, M, K, N, bitmap, values, row_offsets, a_cat, b_cat, R, y, ws, need, stream);
 }
 
 size_t salr_linear_2of4_workspace_bytes(int64_t M, int64_t K, int64_t N, int64_t R) {
