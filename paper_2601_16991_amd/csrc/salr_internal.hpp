@@ -194,6 +194,9 @@ hipError_t launch_linear(const LinearArgs& args, hipStream_t stream);
 // count bf16 zeros (+0.0) at out
 hipError_t launch_fill_zero(uint16_t* out, int64_t count, hipStream_t stream);
 hipError_t launch_linear_stream(const LinearArgs& args, hipStream_t stream, const TimingEvents& ev);
+// decode-sized batches (M <= 16, K % 128 == 0, K <= 32768): the streaming kernel that reads every bitmap word once
+bool linear_slice_takes(int64_t M, int64_t K, int64_t N);
+hipError_t launch_linear_slice(const LinearArgs& args, hipStream_t stream, const TimingEvents& ev);
 hipError_t launch_linear_twostage(const LinearArgs& args, hipStream_t stream, const TimingEvents& ev);
 hipError_t launch_linear_rowtile(const LinearArgs& args, hipStream_t stream, const TimingEvents& ev);
 hipError_t launch_linear_2of4(const LinearArgs& args, hipStream_t stream, const TimingEvents& ev);

@@ -170,6 +170,7 @@ thread_local TimingEvents g_timing_events;
 hipError_t launch_linear(const LinearArgs& a, hipStream_t stream) {
     if (a.M == 0 || a.N == 0) return hipSuccess;
     if (uses_rowtile(a.M, a.K, a.N)) return launch_linear_rowtile(a, stream, g_timing_events);
+    if (linear_slice_takes(a.M, a.K, a.N)) return launch_linear_slice(a, stream, g_timing_events);
     if (a.M <= kStreamMaxM) return launch_linear_stream(a, stream, g_timing_events);
     if (uses_twostage(a.M, a.K)) return launch_linear_twostage(a, stream, g_timing_events);
     const int R = (int)a.R;

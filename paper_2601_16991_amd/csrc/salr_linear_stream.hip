@@ -226,9 +226,11 @@ __global__ __launch_bounds__(NW * 64, (S == 2 && MT == 1) ? 4 : 1) void linear_s
             // row tile the two registers of the hoisted pointer cost more than the address arithmetic they save)
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
-                const uint16_t* xc = xrow[mt] + c * (kChunkWords * 32);
+                if (16 * mt + n < M) {   // lanes of rows past M request nothing: their accumulator rows are never stored
+                    const uint16_t* xc = xrow[mt] + c * (kChunkWords * 32);
 #pragma unroll
-                for (int s = 0; s < kChunkWords; ++s) st.xq[s * MT + mt] = *reinterpret_cast<const uint4*>(xc + 32 * s);
+                    for (int s = 0; s < kChunkWords; ++s) st.xq[s * MT + mt] = *reinterpret_cast<const uint4*>(xc + 32 * s);
+                }
             }
         } else {
 #pragma unroll
@@ -238,7 +240,7 @@ __global__ __launch_bounds__(NW * 64, (S == 2 && MT == 1) ? 4 : 1) void linear_s
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt) {
                     const int m = 16 * mt + n;
-                    st.xq[s * MT + mt] = *reinterpret_cast<const uint4*>(x + (int64_t)(m < M ? m : M - 1) * K + k);
+                    if (m < M) st.xq[s * MT + mt] = *reinterpret_cast<const uint4*>(x + (int64_t)m * K + k);
                 }
             }
         }

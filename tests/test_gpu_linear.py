@@ -129,6 +129,12 @@ def test_row_tiled_random_shapes():
     (16, 5120, 48, (16,), 1.0),           # every bit set: pieces of 17 vectors, the two-chunks-in-flight loop
     (3, 28672, 48, (64,), 0.5),           # K of the 70B down_proj layer: 28 chunks per wave
     (2, 4352, 16, (1,), 0.05),            # sparse rows: many empty pieces
+    # from K = 12288 on: the kernel that loads every bitmap word once and takes a row's values four chunks at a time
+    (8, 12288, 40, (8,), 1.0),            # every bit set: pieces of 65 vectors, 25 of them fetched when consumed
+    (2, 16384, 32, (1,), 0.05),           # sparse rows: empty pieces
+    (16, 12416, 20, (16, 16), 0.75),      # 97 chunks over 8 waves: slices of 12 and 13 chunks, last group ragged
+    (9, 32768, 18, (), 0.5),              # the longest rows the kernel takes: 8 groups per wave
+    (5, 32896, 18, (4,), 0.5),            # one chunk more: back to the small-batch kernel
     # ... with >= 512 row groups: two workgroups per CU, two chunks in flight
     (1, 4224, 8200, (8, 8), 0.5),
     (8, 8192, 8192, (64,), 0.5),
