@@ -313,15 +313,89 @@ def cpu_baseline(cfg, permille, M, alg_bytes, budget_s=10.0, max_reps=50):
                       f"{s * 1e3:.1f} ms per call"}
 
 
-def load_traffic(workload_key):
-    """HBM traffic per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE), if a summary was committed."""
+def load_traffic(workload_key, field="bytes"):
+    """HBM traffic per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE), if a summary was committed;
+    `measured_at` names the state of the kernel sources the counters were read on."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     try:
         with open(path) as f:
             entry = json.load(f).get(workload_key)
-        return None if entry is None else entry["bytes"]
+        return None if entry is None else entry.get(field)
     except Exception:
         return None
+
+
+def config_row(layer, M, steps, warmup, two_of_four=False):
+    """One row of the table: the call on `layer` at batch M, weights rotated so that they come from HBM.  Both the whole
+    call (wall clock per step: every kernel of the call and the gaps between them) and its dominant kernel alone (HIP
+    events on its launch) are set against the roofline that bounds the shape: HBM bytes up to 128 tokens, bf16 MFMA
+    flops above (2:4 rows: dense-equivalent flops; the sparse instructions execute half of them)."""
+    import numpy as np
+    import paper_2601_16991_amd as salr
+    import salr_workloads as wl
+    cfg = layer.cfg
+    w_ms, k_ms = time_linear(layer, M, steps, warmup, events=True, two_of_four=two_of_four)
+    d_ms = time_dense(layer, M, steps, warmup, with_lora=False)
+    k = float(np.mean(k_ms))
+    nbytes = wl.algorithmic_bytes(M, cfg.K, cfg.N, layer.R, layer.nnz)
+    fl = wl.algorithmic_flops(M, cfg.K, cfg.N, layer.R)
+    ws_fn = salr.salr_linear_2of4_workspace_bytes if two_of_four else salr.salr_linear_workspace_bytes
+    row = {"ms_per_step": round(w_ms, 6), "kernel_avg_us": round(k * 1e3, 2), "dense_gemm_ms": round(d_ms, 6),
+           "speedup_vs_dense_gemm": round(d_ms / w_ms, 3), "workspace_bytes": int(ws_fn(M, cfg.K, cfg.N, layer.R))}
+    if M <= 128:
+        row.update({"bound": "hbm", "GB/s": round(nbytes / w_ms / 1e6, 1),
+                    "frac_call": round(nbytes / w_ms / 1e6 / HBM_PEAK_GBS, 4),
+                    "frac_kernel": round(nbytes / k / 1e6 / HBM_PEAK_GBS, 4)})
+    else:
+        row.update({"bound": "mfma", "TFLOP/s": round(fl / w_ms / 1e9, 1),
+                    "frac_call": round(fl / w_ms / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4),
+                    "frac_kernel": round(fl / k / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4),
+                    "dense_gemm_TFLOP/s": round(2 * M * cfg.N * cfg.K / d_ms / 1e9, 1)})
+        if two_of_four:
+            row["TFLOP/s_executed"] = round(fl / 2 / w_ms / 1e9, 1)   # the sparse MFMA multiplies the stored half only
+            row["frac_kernel_vs_sparse_mfma_peak"] = round(fl / k / 1e9 / (2 * MFMA_BF16_PEAK_TFLOPS), 4)
+    return row
+
+
+def measure_ceilings():
+    """What this machine's memory system and vendor GEMM reach in this very run, beside the nominal peaks: a device copy of
+    1 GiB (read + write, four sources rotated), a cold read stream (hipBLASLt's bf16 product of one token with a dense
+    [28672, 8192] weight, 470 MB read once per call, two weights rotated), and hipBLASLt's bf16 GEMM on two prefill shapes."""
+    import torch
+    dev = torch.device("cuda:0")
+    out = {}
+    bufs = [torch.ones(1 << 28, dtype=torch.int32, device=dev) for _ in range(4)]
+    dst = torch.empty_like(bufs[0])
+
+    def timed(fn, n):
+        for i in range(2):
+            fn(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(n):
+            fn(i)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / n
+
+    t = timed(lambda i: dst.copy_(bufs[i % 4]), 12)
+    out["copy_read_plus_write_GB/s"] = round(2 * (1 << 30) / t / 1e9, 1)
+    del bufs, dst
+    torch.cuda.empty_cache()
+    wbig = [torch.randn((28672, 8192), device=dev, dtype=torch.bfloat16) for _ in range(2)]
+    x1 = torch.randn((1, 8192), device=dev, dtype=torch.bfloat16)
+    t = timed(lambda i: torch.matmul(x1, wbig[i % 2].t()), 20)
+    out["read_stream_GB/s"] = round(wbig[0].numel() * 2 / t / 1e9, 1)
+    del wbig, x1
+    torch.cuda.empty_cache()
+    for (m, n, k) in ((2048, 14336, 4096), (4096, 4096, 14336)):
+        a = torch.randn((m, k), device=dev, dtype=torch.bfloat16)
+        ws = [torch.randn((n, k), device=dev, dtype=torch.bfloat16) for _ in range(3)]
+        t = timed(lambda i: torch.matmul(a, ws[i % 3].t()), 10)
+        out[f"hipblaslt_bf16_M{m}_N{n}_K{k}_TFLOP/s"] = round(2 * m * n * k / t / 1e12, 1)
+        del a, ws
+    torch.cuda.empty_cache()
+    out["nominal"] = {"hbm_GB/s": HBM_PEAK_GBS, "mfma_bf16_TFLOP/s": MFMA_BF16_PEAK_TFLOPS}
+    return out
 
 
 WORKLOADS = {"q_proj_M16": ("llama3_8b_q_proj", 16), "gate_up_M2048": ("llama3_8b_gate_up_proj", 2048),
@@ -362,6 +436,7 @@ def decode_result(args, name, M, two_of_four=False):
         "speedup_vs_dense_gemm": round(d_ms / w_ms, 3), "dense_gemm_ms": round(d_ms, 6),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "frac_call": round(nbytes / (w_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                      "kernel": ("sparse-MFMA kernel of salr_sparse_lowrank_linear_2of4" if two_of_four
                                 else "fused decode+GEMM kernel of salr_sparse_lowrank_linear"),
                      "kernel_avg_us": round(k * 1e3, 2)},
@@ -397,6 +472,7 @@ def prefill_result(args, name, M, two_of_four=False):
         "dense_gemm_TFLOP/s": round(2 * M * cfg.N * cfg.K / d_ms / 1e9, 1),
         "roofline": {"bound": "mfma", "achieved": round(achieved, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                     "frac_call": round(fl / (w_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
                      "kernel": ("GEMM on the sparse MFMA (gemm_2of4_kernel) of salr_sparse_lowrank_linear_2of4, in "
                                 "dense-equivalent flops; the adapter stage of the call is in `value` but not in this figure"
                                 if two_of_four else
@@ -482,6 +558,8 @@ def main():
         "dense_gemm_ms": round(dense_ms, 6),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": load_traffic(f"{cfg.name}_M{M}"),
+                     "traffic_measured_at": load_traffic(f"{cfg.name}_M{M}", "measured_at"),
+                     "frac_call": round(alg_bytes / (ms_wall * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                      "kernel": "fused decode+GEMM kernel of salr_sparse_lowrank_linear",
                      "kernel_avg_us": round(k_avg * 1e3, 3), "kernel_median_us": round(k_med * 1e3, 3),
                      "kernel_p10_us": round(float(np.percentile(kernel_ms, 10)) * 1e3, 3),
@@ -490,27 +568,16 @@ def main():
 
     if not args.no_extras:
         extras = {}
-        for m in (1, 4):
-            w_ms, k_ms = time_linear(layer, m, args.steps, args.warmup, events=True)
-            ab = wl.algorithmic_bytes(m, cfg.K, cfg.N, layer.R, layer.nnz)
-            d_ms = time_dense(layer, m, args.steps, args.warmup, with_lora=False)
-            extras[f"{cfg.name}_M{m}"] = {
-                "ms_per_step": round(w_ms, 6), "GB/s": round(ab / w_ms / 1e6, 1),
-                "kernel_avg_us": round(float(np.mean(k_ms)) * 1e3, 3),
-                "hbm_frac_kernel": round(ab / (float(np.mean(k_ms)) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                "speedup_vs_dense_gemm": round(d_ms / w_ms, 3)}
-            log(f"M={m}: {extras[f'{cfg.name}_M{m}']}")
-        # second workload: the same layer under a 2:4 mask (constant popcount per nibble)
+        result["ceilings"] = measure_ceilings()
+        log("ceilings:", result["ceilings"])
+        # every layer shape / sparsity / batch size of the workload list (the headline row is measured above with the
+        # driver's own step count; here it appears again with the short protocol, for comparison within the table)
+        extras["configs"] = {}
+        # second workload: the headline layer under a 2:4 mask (constant popcount per nibble), general call and sparse-MFMA call
         layer24 = Layer(cfg, permille, nm=(2, 4))
         assert salr.bitmap_is_2of4(layer24.enc[0][0])
         for key, sparse_mfma in ((f"{cfg.name}_M{M}_mask2of4", False), (f"{cfg.name}_M{M}_mask2of4_sparse_mfma", True)):
-            # the general call, then salr_sparse_lowrank_linear_2of4 (bitmap and values straight into the sparse MFMA)
-            w_ms, k_ms = time_linear(layer24, M, args.steps, args.warmup, events=True, two_of_four=sparse_mfma)
-            extras[key] = {
-                "ms_per_step": round(w_ms, 6), "GB/s": round(alg_bytes / w_ms / 1e6, 1),
-                "kernel_avg_us": round(float(np.mean(k_ms)) * 1e3, 3),
-                "hbm_frac_kernel": round(alg_bytes / (float(np.mean(k_ms)) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                "speedup_vs_dense_gemm": round(dense_ms / w_ms, 3)}
+            extras[key] = config_row(layer24, M, min(args.steps, 100), min(args.warmup, 10), two_of_four=sparse_mfma)
             log(f"2:4 mask, M={M}, sparse MFMA path {sparse_mfma}: {extras[key]}")
         del layer24
         extras["codec_" + cfg.name] = time_codec(layer, 20)
@@ -519,55 +586,35 @@ def main():
         log("prepare:", extras["prepare_" + cfg.name])
         extras["backward_" + cfg.name + "_M2048"] = time_backward(layer, 2048, 10)
         log("backward:", extras["backward_" + cfg.name + "_M2048"])
+        for m in cfg.Ms:
+            extras["configs"][f"{cfg.name}_p{permille}_M{m}"] = config_row(layer, m, min(args.steps, 100), min(args.warmup, 10))
+            log(f"{cfg.name} p={permille} M={m}: {extras['configs'][f'{cfg.name}_p{permille}_M{m}']}")
         del layer
         torch.cuda.empty_cache()
-        # prefill-sized, MFMA-bound layers: decode stage + T + dense MFMA stage per call (wall), and the MFMA stage alone
-        for name2 in ("llama3_8b_gate_up_proj", "llama3_8b_down_proj"):
+        for name2 in ("llama3_8b_gate_up_proj", "llama3_8b_down_proj", "llama3_70b_attn", "llama3_70b_gate_up_proj",
+                      "llama3_70b_down_proj"):
             cfg2 = wl.CONFIGS[name2]
-            m2 = max(cfg2.Ms)
-            layer2 = Layer(cfg2, 500, max_copies=4)
-            steps2 = max(5, min(args.steps, 30))
-            w_ms, k_ms = time_linear(layer2, m2, steps2, 3, events=True)
-            fl = wl.algorithmic_flops(m2, cfg2.K, cfg2.N, layer2.R)
-            d_ms = time_dense(layer2, m2, steps2, 3, with_lora=False)
-            k2 = float(np.mean(k_ms))
-            extras[f"{cfg2.name}_M{m2}"] = {
-                "ms_per_step": round(w_ms, 5), "TFLOP/s": round(fl / w_ms / 1e9, 1),
-                "mfma_frac": round(fl / w_ms / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4),
-                "mfma_stage_avg_us": round(k2 * 1e3, 2),
-                "mfma_frac_stage_alone": round(fl / (k2 * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
-                "dense_gemm_ms": round(d_ms, 5), "dense_gemm_TFLOP/s": round(2 * m2 * cfg2.N * cfg2.K / d_ms / 1e9, 1),
-                "speedup_vs_dense_gemm": round(d_ms / w_ms, 3)}
-            log(f"{cfg2.name} M={m2}: {extras[f'{cfg2.name}_M{m2}']}")
-            # the same layer at batch sizes between decode and prefill: one pass over the compressed weight
-            for mm in (16, 64, 128):
-                w_ms, k_ms = time_linear(layer2, mm, steps2, 3, events=True)
-                ab = wl.algorithmic_bytes(mm, cfg2.K, cfg2.N, layer2.R, layer2.nnz)
-                d_ms = time_dense(layer2, mm, steps2, 3, with_lora=False)
-                k2 = float(np.mean(k_ms))
-                extras[f"{cfg2.name}_M{mm}"] = {
-                    "ms_per_step": round(w_ms, 5), "GB/s": round(ab / w_ms / 1e6, 1), "kernel_avg_us": round(k2 * 1e3, 2),
-                    "hbm_frac_kernel": round(ab / (k2 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                    "dense_gemm_ms": round(d_ms, 5), "speedup_vs_dense_gemm": round(d_ms / w_ms, 3)}
-                log(f"{cfg2.name} M={mm}: {extras[f'{cfg2.name}_M{mm}']}")
-            del layer2
-            torch.cuda.empty_cache()
+            for pm in cfg2.sparsity_permille:
+                layer2 = Layer(cfg2, pm, max_copies=4)
+                ms_list = list(cfg2.Ms)
+                if name2 == "llama3_8b_gate_up_proj":
+                    ms_list = [16, 64, 128] + ms_list      # the batch sizes between decode and prefill as well
+                if name2 == "llama3_8b_down_proj" and pm == 500:
+                    ms_list = sorted(set(ms_list + [16, 128]))
+                for m2 in ms_list:
+                    steps2 = max(5, min(args.steps, 30 if m2 <= 512 else 10))
+                    key = f"{cfg2.name}_p{pm}_M{m2}"
+                    extras["configs"][key] = config_row(layer2, m2, steps2, 3)
+                    log(f"{key}: {extras['configs'][key]}")
+                del layer2
+                torch.cuda.empty_cache()
         # 2:4-masked layers through salr_sparse_lowrank_linear_2of4 (sparse MFMA on bitmap and values as they are)
         for name3, m3 in (("llama3_8b_gate_up_proj", 16), ("llama3_8b_gate_up_proj", 2048), ("llama3_70b_gate_up_proj", 1)):
             cfg3 = wl.CONFIGS[name3]
             layer3 = Layer(cfg3, 500, max_copies=4, nm=(2, 4))
-            steps3 = max(5, min(args.steps, 40))
-            w_ms, k_ms = time_linear(layer3, m3, steps3, 3, events=True, two_of_four=True)
-            ab = wl.algorithmic_bytes(m3, cfg3.K, cfg3.N, layer3.R, layer3.nnz)
-            d_ms = time_dense(layer3, m3, steps3, 3, with_lora=False)
-            k3 = float(np.mean(k_ms))
-            fl3 = wl.algorithmic_flops(m3, cfg3.K, cfg3.N, layer3.R)
-            extras[f"{cfg3.name}_M{m3}_mask2of4_sparse_mfma"] = {
-                "ms_per_step": round(w_ms, 5), "GB/s": round(ab / w_ms / 1e6, 1), "kernel_avg_us": round(k3 * 1e3, 2),
-                "hbm_frac_kernel": round(ab / (k3 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                "TFLOP/s_dense_equivalent": round(fl3 / w_ms / 1e9, 1),
-                "dense_gemm_ms": round(d_ms, 5), "speedup_vs_dense_gemm": round(d_ms / w_ms, 3)}
-            log(f"{cfg3.name} M={m3}, 2:4 mask, sparse MFMA path: {extras[f'{cfg3.name}_M{m3}_mask2of4_sparse_mfma']}")
+            key = f"{cfg3.name}_M{m3}_mask2of4_sparse_mfma"
+            extras[key] = config_row(layer3, m3, max(5, min(args.steps, 30)), 3, two_of_four=True)
+            log(f"{key}: {extras[key]}")
             del layer3
             torch.cuda.empty_cache()
         result["extras"] = extras
