@@ -16,7 +16,10 @@ byte-mask/LUT decoder, popcount identities and hand-worked masks; the linear aga
 loops, numpy fp64 matmul in the special cases that reduce to it, and the per-adapter sum; the SVD
 residual against Theorem 3's bound; the residual against W = What + E and hand-worked values; the
 concatenation against the sum over adapters on integer-valued matrices; the backward pass against the
-forward pass (C code, not numpy) through the adjoint identities and against pure-Python loops.  No function here is "parity unpinned".
+forward pass (C code, not numpy) through the adjoint identities and against pure-Python loops; the NF4
+quantiser of the packed values (QSALR) against a brute-force nearest-entry search in exact rational arithmetic,
+hand-worked blocks, its error bound, idempotence and scale invariance, and the code book against the quantile
+rule it comes from.  No function here is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -61,6 +64,10 @@ def _load():
     lib.salr_oracle_build_lut.restype = None
     lib.salr_oracle_linear.argtypes = [_u16p, _i64, _i64, _i64, _u16p, _u16p, _u16p, _i64, _f64p]
     lib.salr_oracle_adapter_accumulate.argtypes = [_u16p, _i64, _i64, _i64, _u16p, _u16p, _i64, _f64p]
+    lib.salr_oracle_nf4_codebook.argtypes = [ctypes.POINTER(ctypes.c_float)]
+    lib.salr_oracle_nf4_codebook.restype = None
+    lib.salr_oracle_nf4_quantize.argtypes = [_u16p, _i64, ctypes.POINTER(ctypes.c_uint8), _u16p]
+    lib.salr_oracle_nf4_dequantize.argtypes = [ctypes.POINTER(ctypes.c_uint8), _u16p, _i64, _u16p]
     _lib = lib
     return lib
 
@@ -290,3 +297,38 @@ def svd_residual_adapter(w: np.ndarray, w_hat: np.ndarray, r: int) -> Tuple[np.n
     U, s, Vt = np.linalg.svd(E, full_matrices=False)
     rs = np.sqrt(s[:r])
     return Vt[:r].T * rs[None, :], (U[:, :r] * rs[None, :]).T
+
+
+def nf4_codebook() -> np.ndarray:
+    """The 16 NF4 levels (fp32), ascending, as the oracle uses them."""
+    out = np.empty(16, dtype=np.float32)
+    _load().salr_oracle_nf4_codebook(out.ctypes.data_as(ctypes.POINTER(ctypes.c_float)))
+    return out
+
+
+def nf4_quantize(values: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """QSALR (Sec. 4): packed bf16 values -> (codes uint8 [ceil(n/2)], two 4-bit codes per byte, even index in the low
+    nibble; scales bf16 bits [ceil(n/64)], one per block of 64 consecutive values)."""
+    v = _c(np.asarray(values).reshape(-1), np.uint16)
+    n = v.size
+    codes = np.zeros((n + 1) // 2, dtype=np.uint8)
+    scales = np.zeros((n + 63) // 64, dtype=np.uint16)
+    rc = _load().salr_oracle_nf4_quantize(_p(v, _u16p), n, codes.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)),
+                                          _p(scales, _u16p))
+    if rc:
+        raise RuntimeError(f"nf4_quantize failed ({rc})")
+    return codes, scales
+
+
+def nf4_dequantize(codes: np.ndarray, scales: np.ndarray, count: int) -> np.ndarray:
+    """The bf16 values the codes stand for: bf16(level[code] * scale of the block), the product in fp32."""
+    c = _c(codes, np.uint8)
+    sc = _c(scales, np.uint16)
+    if c.size < (count + 1) // 2 or sc.size < (count + 63) // 64:
+        raise ValueError("codes / scales too short")
+    out = np.zeros(count, dtype=np.uint16)
+    rc = _load().salr_oracle_nf4_dequantize(c.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)), _p(sc, _u16p), count,
+                                            _p(out, _u16p))
+    if rc:
+        raise RuntimeError(f"nf4_dequantize failed ({rc})")
+    return out

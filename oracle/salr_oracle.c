@@ -269,3 +269,86 @@ int salr_oracle_mask_nm(const uint16_t* w, int64_t rows, int64_t cols, int64_t n
             }
     return 0;
 }
+
+/* ------------------------------------------------------------------------------------------------
+ * QSALR (Sec. 4, "Coupled with Quantization"; the size/accuracy table of the 20 % sparsity + NF4
+ * variant): the packed nonzero values v of the bitmap format are stored as 4-bit NormalFloat codes.
+ *
+ * The paper names the data type (NF4, from the QLoRA paper it cites) and nothing else.  Reading taken
+ * here: the 16-entry NF4 code book as that paper publishes it (quantiles of N(0,1) scaled to [-1, 1],
+ * with an exact zero); blocks of 64 CONSECUTIVE packed values (in the order of v, whatever rows they
+ * belong to; the last block may be short) share one scale = the largest magnitude of the block, which
+ * is itself one of the bf16 values and so needs no rounding; a value x gets the code of the entry
+ * nearest to x / scale, decided without a division: code = number of i in 0..14 with
+ * x > fp32(mid_i * scale), mid_i = fp32(0.5 * (c_i + c_{i+1})), all in fp32 (a value exactly on a
+ * boundary takes the lower code); two codes per byte, the even-indexed value in the low nibble.
+ * Dequantisation: v'[i] = bf16_rne(fp32(c[code] * scale)).  A block of all zeros (cannot occur for
+ * packed nonzeros, allowed for generality) has scale +0 and every code 7 (the exact zero).
+ * ---------------------------------------------------------------------------------------------- */
+static const float kNf4[16] = {
+    -1.0f, -0.6961928009986877f, -0.5250730514526367f, -0.39491748809814453f,
+    -0.28444138169288635f, -0.18477343022823334f, -0.09105003625154495f, 0.0f,
+    0.07958029955625534f, 0.16093020141124725f, 0.24611230194568634f, 0.33791524171829224f,
+    0.44070982933044434f, 0.5626170039176941f, 0.7229568362236023f, 1.0f};
+
+void salr_oracle_nf4_codebook(float* out /* [16] */) {
+    for (int i = 0; i < 16; ++i) out[i] = kNf4[i];
+}
+
+static float bf16_to_f32(uint16_t b) {
+    uint32_t u = (uint32_t)b << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return f;
+}
+
+static uint16_t f32_to_bf16_rne_bits(float f) {
+    uint32_t u;
+    memcpy(&u, &f, sizeof u);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x0040u); /* NaN stays NaN */
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+int64_t salr_oracle_nf4_blocks(int64_t count) { return (count + 63) / 64; }
+
+int salr_oracle_nf4_quantize(const uint16_t* values, int64_t count, uint8_t* codes /* [(count+1)/2] */,
+                             uint16_t* scales /* [(count+63)/64] bf16 */) {
+    if (count < 0 || (count > 0 && (!values || !codes || !scales))) return 1;
+    for (int64_t i = 0; i < (count + 1) / 2; ++i) codes[i] = 0;
+    for (int64_t b0 = 0; b0 < count; b0 += 64) {
+        const int64_t b1 = b0 + 64 < count ? b0 + 64 : count;
+        uint16_t amax = 0; /* magnitude pattern: for finite bf16 the integer order is the order of |x| */
+        for (int64_t i = b0; i < b1; ++i) {
+            const uint16_t mag = (uint16_t)(values[i] & 0x7FFFu);
+            if (mag > amax) amax = mag;
+        }
+        scales[b0 / 64] = amax;
+        const float s = bf16_to_f32(amax);
+        for (int64_t i = b0; i < b1; ++i) {
+            const float x = bf16_to_f32(values[i]);
+            int code = 0;
+            if (amax == 0) {
+                code = 7;
+            } else {
+                for (int k = 0; k < 15; ++k) {
+                    const volatile float mid = 0.5f * (kNf4[k] + kNf4[k + 1]);
+                    const volatile float edge = mid * s; /* one fp32 product, rounded once */
+                    if (x > edge) ++code;
+                }
+            }
+            codes[i / 2] |= (uint8_t)(code << (4 * (i & 1)));
+        }
+    }
+    return 0;
+}
+
+int salr_oracle_nf4_dequantize(const uint8_t* codes, const uint16_t* scales, int64_t count, uint16_t* values_out) {
+    if (count < 0 || (count > 0 && (!codes || !scales || !values_out))) return 1;
+    for (int64_t i = 0; i < count; ++i) {
+        const int code = (codes[i / 2] >> (4 * (i & 1))) & 15;
+        const volatile float p = kNf4[code] * bf16_to_f32(scales[i / 64]);
+        values_out[i] = f32_to_bf16_rne_bits(p);
+    }
+    return 0;
+}

@@ -22,6 +22,8 @@ int salr_oracle_linear(const uint16_t*, int64_t, int64_t, int64_t, const uint16_
                        int64_t, double*);
 int salr_oracle_adapter_accumulate(const uint16_t*, int64_t, int64_t, int64_t, const uint16_t*, const uint16_t*, int64_t,
                                    double*);
+int salr_oracle_nf4_quantize(const uint16_t*, int64_t, uint8_t*, uint16_t*);
+int salr_oracle_nf4_dequantize(const uint8_t*, const uint16_t*, int64_t, uint16_t*);
 
 static uint64_t rng_state = 0x2601169912345ULL;
 static uint32_t rnd(void) {
@@ -72,6 +74,16 @@ static void one_shape(int64_t rows, int64_t cols, int64_t keep) {
     CHECK(salr_oracle_mask_threshold(w, (int64_t)n, 0x3C00u, back) == 0);
     if (cols % 4 == 0) CHECK(salr_oracle_mask_nm(w, rows, cols, 2, 4, back) == 0);
     if (cols % 3 == 0) CHECK(salr_oracle_mask_nm(w, rows, cols, 1, 3, back) == 0);
+    /* the packed values as 4-bit codes and back: exactly-sized code and scale buffers, odd counts, short last block */
+    {
+        uint8_t* codes = xmalloc((size_t)((nnz + 1) / 2));
+        uint16_t* scales = xmalloc(2 * (size_t)((nnz + 63) / 64));
+        uint16_t* deq = xmalloc(2 * (size_t)nnz);
+        CHECK(salr_oracle_nf4_quantize(values, nnz, codes, scales) == 0);
+        CHECK(salr_oracle_nf4_dequantize(codes, scales, nnz, deq) == 0);
+        for (int64_t i = 0; i < nnz; ++i) CHECK((deq[i] & 0x7FFFu) <= (scales[i / 64] & 0x7FFFu));
+        free(deq); free(scales); free(codes);
+    }
     /* the layer on this weight: M = 3 rows of X, two adapters of ranks 2 and 1 stacked, and one by one */
     const int64_t M = 3, R = 3;
     uint16_t* x = xmalloc(2 * (size_t)(M * cols));
