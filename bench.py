@@ -398,6 +398,56 @@ def measure_ceilings():
     return out
 
 
+def time_qsalr(cfg, Ms, steps):
+    """QSALR on one layer shape: 20 % per-row magnitude sparsity, packed values as NF4 codes with one bf16 scale per 64
+    values.  Times the coding and decoding passes and salr_qsalr_linear (dequantisation + the layer) against the
+    format's own algorithmic bytes: bitmap + codes + scales + row offsets (+ the layer's other operands)."""
+    import numpy as np
+    import torch
+    import paper_2601_16991_amd as salr
+    import salr_workloads as wl
+    layer = Layer(cfg, 200, max_copies=2)
+    dev = layer.w_hat.device
+    bitmap, values, offsets = layer.enc[0]
+    nnz = layer.nnz
+    codes, scales = salr.nf4_quantize(values)
+    out = salr.values_alloc(nnz, dev)
+    torch.cuda.synchronize()
+    fmt_bytes = bitmap.numel() * 4 + codes.numel() + scales.numel() * 2 + offsets.numel() * 4
+    res = {"sparsity": 0.2, "nnz": nnz, "bits_per_weight": round(8 * fmt_bytes / (cfg.N * cfg.K), 3),
+           "compression_vs_bf16": round(2 * cfg.N * cfg.K / fmt_bytes, 3)}
+    for name, nbytes, fn in (("quantize", 2 * nnz + codes.numel() + scales.numel() * 2, lambda: salr.salr_nf4_quantize_values(values, codes, scales)),
+                             ("dequantize", 2 * nnz + codes.numel() + scales.numel() * 2, lambda: salr.salr_nf4_dequantize_values(codes, scales, nnz, out))):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        res[name] = {"ms": round(ms, 4), "GB/s": round(nbytes / ms / 1e6, 1)}
+    for M in Ms:
+        x = torch.from_numpy(wl.activations(cfg, M).view(np.int16)).to(dev)
+        y = torch.empty((M, cfg.N), dtype=torch.int16, device=dev)
+        ws = torch.empty(max(salr.salr_qsalr_linear_workspace_bytes(M, cfg.K, cfg.N, layer.R, nnz), 256), dtype=torch.uint8, device=dev)
+
+        def fn():
+            salr.salr_qsalr_linear(x, bitmap, codes, scales, offsets, nnz, layer.a_cat, layer.b_cat, y, ws)
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        nbytes = fmt_bytes + 2 * M * cfg.K + 2 * cfg.K * layer.R + 2 * layer.R * cfg.N + 2 * M * cfg.N
+        res[f"linear_M{M}"] = {"ms": round(ms, 4), "GB/s": round(nbytes / ms / 1e6, 1),
+                               "TFLOP/s": round(wl.algorithmic_flops(M, cfg.K, cfg.N, layer.R) / ms / 1e9, 1)}
+    return res
+
+
 WORKLOADS = {"q_proj_M16": ("llama3_8b_q_proj", 16), "gate_up_M2048": ("llama3_8b_gate_up_proj", 2048),
              "down_proj_M4096": ("llama3_8b_down_proj", 4096), "gate_up_70b_M1": ("llama3_70b_gate_up_proj", 1),
              "gate_up_70b_M16": ("llama3_70b_gate_up_proj", 16), "gate_up_M16": ("llama3_8b_gate_up_proj", 16),
@@ -586,6 +636,8 @@ def main():
         log("prepare:", extras["prepare_" + cfg.name])
         extras["backward_" + cfg.name + "_M2048"] = time_backward(layer, 2048, 10)
         log("backward:", extras["backward_" + cfg.name + "_M2048"])
+        extras["qsalr_" + cfg.name] = time_qsalr(cfg, (16, 2048), 20)
+        log("qsalr:", extras["qsalr_" + cfg.name])
         for m in cfg.Ms:
             extras["configs"][f"{cfg.name}_p{permille}_M{m}"] = config_row(layer, m, min(args.steps, 100), min(args.warmup, 10))
             log(f"{cfg.name} p={permille} M={m}: {extras['configs'][f'{cfg.name}_p{permille}_M{m}']}")

@@ -188,6 +188,43 @@ salr_status_t salr_sparse_lowrank_linear_noalloc(const uint16_t* x, int64_t M, i
                                                  const uint16_t* b_cat, int64_t R, uint16_t* y, void* stream);
 
 /*
+ * QSALR -- Sec. 4 ("Coupled with Quantization", the size/accuracy table of 20 % sparsity + NF4): the packed values
+ * of the bitmap format stored as 4-bit NormalFloat codes.  The paper names the data type and nothing else; this
+ * library's reading is
+ *   levels   the 16 NF4 levels of the QLoRA paper that the SALR paper cites (normal quantiles scaled to [-1, 1],
+ *            ascending, exact zero at index 7);
+ *   scales   [ceil(count / 64)] bf16: one per block of 64 CONSECUTIVE packed values (in the order of `values`,
+ *            whatever rows they belong to; the last block may be short), the block's largest magnitude (one of its
+ *            own values, so exact in bf16);
+ *   codes    [ceil(count / 2)] bytes, two codes per byte, the even-indexed value in the low nibble (the unused high
+ *            nibble of an odd count is 0).  A value x gets the code of the level nearest to x / scale, decided
+ *            without division: the number of k in 0..14 with x > fp32(mid_k * scale), mid_k =
+ *            fp32(0.5 * (level_k + level_{k+1})); a value on a boundary takes the lower code; an all-zero block has
+ *            scale 0 and codes 7;
+ *   value    bf16_rne(fp32(level[code] * scale)).
+ * Size: bitmap 1 bit + (1 - p) * (4 + 16 / 64) bits per weight element = 4.4 bits at p = 0.2, against 16 dense.
+ *
+ * salr_nf4_quantize_values / salr_nf4_dequantize_values convert between `values` [count] bf16 and (codes, scales);
+ * bitmap and row_offsets of the format are untouched.  values_out must be writable up to the next multiple of 8
+ * elements.  Errors: INVALID_ARG (null pointer with count > 0, negative count), SHAPE (count >= 2^32), HIP.
+ *
+ * salr_qsalr_linear is salr_sparse_lowrank_linear on such a weight: Y = X * W-hat'^T + (X * A_cat) * B_cat with
+ * W-hat' = decode(bitmap, dequantised values).  The values are dequantised once per call into the first
+ * qsalr part of the workspace (2 * nnz bytes, rounded up), then the layer runs as usual on them; arguments, rounding
+ * and errors otherwise as there.  nnz = row_offsets[N], which the caller knows from encoding (host value).
+ * Workspace: salr_qsalr_linear_workspace_bytes(M, K, N, R, nnz) bytes, 256-byte aligned.
+ */
+salr_status_t salr_nf4_quantize_values(const uint16_t* values, int64_t count, uint8_t* codes, uint16_t* scales,
+                                       void* stream);
+salr_status_t salr_nf4_dequantize_values(const uint8_t* codes, const uint16_t* scales, int64_t count,
+                                         uint16_t* values_out, void* stream);
+size_t salr_qsalr_linear_workspace_bytes(int64_t M, int64_t K, int64_t N, int64_t R, int64_t nnz);
+salr_status_t salr_qsalr_linear(const uint16_t* x, int64_t M, int64_t K, int64_t N, const uint32_t* bitmap,
+                                const uint8_t* codes, const uint16_t* scales, const uint32_t* row_offsets,
+                                int64_t nnz, const uint16_t* a_cat, const uint16_t* b_cat, int64_t R, uint16_t* y,
+                                void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * The layer on 2:4-masked weights (the N:M protocol of the inference-throughput table, Sec. 4).
  *
  * salr_bitmap_is_2of4 writes 1 to *result (device memory, one uint32) when every aligned group of four

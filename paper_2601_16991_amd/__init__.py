@@ -59,6 +59,15 @@ def lib() -> ctypes.CDLL:
                                                  ctypes.c_size_t, _vp]
         L.salr_sparse_lowrank_linear_noalloc.restype = ctypes.c_int
         L.salr_sparse_lowrank_linear_noalloc.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _vp]
+        L.salr_nf4_quantize_values.restype = ctypes.c_int
+        L.salr_nf4_quantize_values.argtypes = [_vp, _i64, _vp, _vp, _vp]
+        L.salr_nf4_dequantize_values.restype = ctypes.c_int
+        L.salr_nf4_dequantize_values.argtypes = [_vp, _vp, _i64, _vp, _vp]
+        L.salr_qsalr_linear_workspace_bytes.restype = ctypes.c_size_t
+        L.salr_qsalr_linear_workspace_bytes.argtypes = [_i64, _i64, _i64, _i64, _i64]
+        L.salr_qsalr_linear.restype = ctypes.c_int
+        L.salr_qsalr_linear.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _i64, _vp, _vp, _i64, _vp, _vp,
+                                        ctypes.c_size_t, _vp]
         L.salr_bitmap_is_2of4.restype = ctypes.c_int
         L.salr_bitmap_is_2of4.argtypes = [_vp, _i64, _i64, _vp, _vp]
         L.salr_linear_2of4_workspace_bytes.restype = ctypes.c_size_t
@@ -179,6 +188,74 @@ def salr_sparse_lowrank_linear(x: torch.Tensor, bitmap: torch.Tensor, values: to
                                           _ptr(a_cat, _BF16_TYPES, "a_cat"), _ptr(b_cat, _BF16_TYPES, "b_cat"), R,
                                           _ptr(y, _BF16_TYPES, "y"), ws_ptr, ws_bytes, _stream(stream))
     _check(st, "salr_sparse_lowrank_linear")
+
+
+def salr_nf4_quantize_values(values: torch.Tensor, codes: torch.Tensor, scales: torch.Tensor, stream=None) -> None:
+    """Enqueue QSALR's coding of the packed values: codes uint8 [ceil(n/2)], scales bf16 [ceil(n/64)]."""
+    n = values.numel()
+    if codes.dtype != torch.uint8 or codes.numel() < (n + 1) // 2 or scales.numel() < (n + 63) // 64:
+        raise ValueError("codes must be uint8 [ceil(n/2)] and scales [ceil(n/64)]")
+    _check(lib().salr_nf4_quantize_values(_ptr(values, _BF16_TYPES, "values"), n, _ptr(codes, (torch.uint8,), "codes"),
+                                          _ptr(scales, _BF16_TYPES, "scales"), _stream(stream)), "salr_nf4_quantize_values")
+
+
+def salr_nf4_dequantize_values(codes: torch.Tensor, scales: torch.Tensor, count: int, values_out: torch.Tensor,
+                               stream=None) -> None:
+    """Enqueue the inverse: values_out [count] bf16 (its storage padded to a multiple of 8 elements)."""
+    if codes.numel() < (count + 1) // 2 or scales.numel() < (count + 63) // 64 or values_out.numel() < count:
+        raise ValueError("buffers too short for count")
+    _check(lib().salr_nf4_dequantize_values(_ptr(codes, (torch.uint8,), "codes"), _ptr(scales, _BF16_TYPES, "scales"), count,
+                                            _ptr(values_out, _BF16_TYPES, "values_out"), _stream(stream)),
+           "salr_nf4_dequantize_values")
+
+
+def salr_qsalr_linear_workspace_bytes(M: int, K: int, N: int, R: int, nnz: int) -> int:
+    return int(lib().salr_qsalr_linear_workspace_bytes(M, K, N, R, nnz))
+
+
+def salr_qsalr_linear(x: torch.Tensor, bitmap: torch.Tensor, codes: torch.Tensor, scales: torch.Tensor,
+                      row_offsets: torch.Tensor, nnz: int, a_cat: Optional[torch.Tensor], b_cat: Optional[torch.Tensor],
+                      y: torch.Tensor, workspace: Optional[torch.Tensor], stream=None) -> None:
+    """Enqueue Y = X decode(bitmap, dequantised codes)^T + (X A_cat) B_cat."""
+    M, K = x.shape
+    N = y.shape[1]
+    R = 0 if a_cat is None else a_cat.shape[1]
+    if y.shape[0] != M or bitmap.shape[0] != N or row_offsets.numel() != N + 1:
+        raise ValueError("inconsistent shapes")
+    if R and (tuple(a_cat.shape) != (K, R) or tuple(b_cat.shape) != (R, N)):
+        raise ValueError("adapter shapes")
+    ws_ptr = None if workspace is None else workspace.data_ptr()
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = lib().salr_qsalr_linear(_ptr(x, _BF16_TYPES, "x"), M, K, N, _ptr(bitmap, _U32_TYPES, "bitmap"),
+                                 _ptr(codes, (torch.uint8,), "codes"), _ptr(scales, _BF16_TYPES, "scales"),
+                                 _ptr(row_offsets, _U32_TYPES, "row_offsets"), nnz, _ptr(a_cat, _BF16_TYPES, "a_cat"),
+                                 _ptr(b_cat, _BF16_TYPES, "b_cat"), R, _ptr(y, _BF16_TYPES, "y"), ws_ptr, ws_bytes,
+                                 _stream(stream))
+    _check(st, "salr_qsalr_linear")
+
+
+def nf4_quantize(values: torch.Tensor) -> Tuple[torch.Tensor, torch.Tensor]:
+    n = values.numel()
+    codes = torch.empty(max((n + 1) // 2, 1), dtype=torch.uint8, device=values.device)[:(n + 1) // 2]
+    scales = torch.empty(max((n + 63) // 64, 1), dtype=torch.int16, device=values.device)[:(n + 63) // 64]
+    salr_nf4_quantize_values(values, codes, scales)
+    return codes, scales
+
+
+def nf4_dequantize(codes: torch.Tensor, scales: torch.Tensor, count: int) -> torch.Tensor:
+    out = values_alloc(count, codes.device)
+    salr_nf4_dequantize_values(codes, scales, count, out)
+    return out
+
+
+def qsalr_linear(x, bitmap, codes, scales, row_offsets, nnz, a_cat, b_cat) -> torch.Tensor:
+    M, K = x.shape
+    N = bitmap.shape[0]
+    R = 0 if a_cat is None else a_cat.shape[1]
+    y = torch.empty((M, N), dtype=x.dtype, device=x.device)
+    ws = torch.empty(max(salr_qsalr_linear_workspace_bytes(M, K, N, R, nnz), 256), dtype=torch.uint8, device=x.device)
+    salr_qsalr_linear(x, bitmap, codes, scales, row_offsets, nnz, a_cat, b_cat, y, ws)
+    return y
 
 
 NOALLOC_SCRATCH_BYTES = 16 * 1024 * 1024   # SALR_NOALLOC_SCRATCH_BYTES of include/salr.h

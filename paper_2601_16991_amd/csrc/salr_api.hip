@@ -198,6 +198,52 @@ salr_status_t salr_sparse_lowrank_linear_noalloc(const uint16_t* x, int64_t M, i
     return salr_sparse_lowrank_linear(x, M, K, N, bitmap, values, row_offsets, a_cat, b_cat, R, y, ws, need, stream);
 }
 
+salr_status_t salr_nf4_quantize_values(const uint16_t* values, int64_t count, uint8_t* codes, uint16_t* scales, void* stream) {
+    if (count < 0) return SALR_ERR_INVALID_ARG;
+    if (count == 0) return SALR_OK;
+    if (!values || !codes || !scales) return SALR_ERR_INVALID_ARG;
+    if (count > (int64_t)0xFFFFFFFFLL) return SALR_ERR_SHAPE;
+    hipError_t e = salr::launch_nf4_quantize(values, count, codes, scales, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SALR_OK : SALR_ERR_HIP;
+}
+
+salr_status_t salr_nf4_dequantize_values(const uint8_t* codes, const uint16_t* scales, int64_t count, uint16_t* values_out,
+                                         void* stream) {
+    if (count < 0) return SALR_ERR_INVALID_ARG;
+    if (count == 0) return SALR_OK;
+    if (!codes || !scales || !values_out) return SALR_ERR_INVALID_ARG;
+    if (count > (int64_t)0xFFFFFFFFLL) return SALR_ERR_SHAPE;
+    hipError_t e = salr::launch_nf4_dequantize(codes, scales, count, values_out, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SALR_OK : SALR_ERR_HIP;
+}
+
+size_t salr_qsalr_linear_workspace_bytes(int64_t M, int64_t K, int64_t N, int64_t R, int64_t nnz) {
+    if (M <= 0 || K < 0 || N <= 0 || R < 0 || R > kMaxRank || K % 32 != 0 || nnz < 0) return 0;
+    return salr::qsalr_values_bytes(nnz) + salr::linear_workspace_bytes(M, K, N, R);
+}
+
+salr_status_t salr_qsalr_linear(const uint16_t* x, int64_t M, int64_t K, int64_t N, const uint32_t* bitmap, const uint8_t* codes,
+                                const uint16_t* scales, const uint32_t* row_offsets, int64_t nnz, const uint16_t* a_cat,
+                                const uint16_t* b_cat, int64_t R, uint16_t* y, void* workspace, size_t workspace_bytes,
+                                void* stream) {
+    if (M < 0 || K < 0 || N < 0 || R < 0 || nnz < 0) return SALR_ERR_INVALID_ARG;
+    if (M == 0 || N == 0) return SALR_OK;
+    if (nnz > 0 && (!codes || !scales)) return SALR_ERR_INVALID_ARG;
+    if (K % 32 != 0) return SALR_ERR_SHAPE;
+    if (nnz > (int64_t)0xFFFFFFFFLL || (K > 0 && nnz > N * K)) return SALR_ERR_SHAPE;
+    if (R > kMaxRank) return SALR_ERR_UNSUPPORTED;
+    const size_t vbytes = salr::qsalr_values_bytes(nnz);
+    const size_t need = vbytes + (K > 0 ? salr::linear_workspace_bytes(M, K, N, R) : 0);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return SALR_ERR_CAPACITY;
+    uint16_t* values = static_cast<uint16_t*>(workspace);
+    if (K > 0 && nnz > 0) {
+        hipError_t e = salr::launch_nf4_dequantize(codes, scales, nnz, values, static_cast<hipStream_t>(stream));
+        if (e != hipSuccess) return SALR_ERR_HIP;
+    }
+    return salr_sparse_lowrank_linear(x, M, K, N, bitmap, values, row_offsets, a_cat, b_cat, R, y,
+                                      static_cast<char*>(workspace) + vbytes, workspace_bytes - vbytes, stream);
+}
+
 size_t salr_linear_2of4_workspace_bytes(int64_t M, int64_t K, int64_t N, int64_t R) {
     const size_t general = salr_linear_workspace_bytes(M, K, N, R);
     if (M <= 0 || K <= 0 || N <= 0 || R < 0 || R > kMaxRank || K % 32 != 0 || !salr::uses_2of4_kernel(M, K, N)) return general;

@@ -190,6 +190,12 @@ hipError_t launch_linear_backward(const uint16_t* x, const uint16_t* dy, int64_t
                                   const uint16_t* a_cat, const uint16_t* b_cat, int64_t R, uint16_t* dx, uint16_t* da,
                                   uint16_t* db, void* workspace, hipStream_t stream);
 
+// QSALR: the packed values as 4-bit NormalFloat codes, one bf16 scale per 64 values
+hipError_t launch_nf4_quantize(const uint16_t* values, int64_t count, uint8_t* codes, uint16_t* scales, hipStream_t stream);
+hipError_t launch_nf4_dequantize(const uint8_t* codes, const uint16_t* scales, int64_t count, uint16_t* out, hipStream_t stream);
+// bytes of the dequantised packed values at the start of the QSALR layer's workspace (16-byte vectors, 256-byte aligned)
+inline size_t qsalr_values_bytes(int64_t nnz) { return round_up_256((size_t)((nnz + 7) / 8 * 8) * sizeof(uint16_t)); }
+
 hipError_t launch_linear(const LinearArgs& args, hipStream_t stream);
 // count bf16 zeros (+0.0) at out
 hipError_t launch_fill_zero(uint16_t* out, int64_t count, hipStream_t stream);

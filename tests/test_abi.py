@@ -299,3 +299,44 @@ def test_two_of_four_validation_and_workspace(lib):
     assert chk(fake, 4, 64, None, None) == salr.SALR_ERR_INVALID_ARG
     assert chk(None, 4, 64, fake, None) == salr.SALR_ERR_INVALID_ARG
     assert chk(fake, 4, 40, fake, None) == salr.SALR_ERR_SHAPE
+
+
+def test_qsalr_and_noalloc_validation(lib):
+    import ctypes
+    import paper_2601_16991_amd as salr
+    fake = 0x1000   # never dereferenced: every call below fails validation first (or has nothing to do)
+    assert lib.salr_nf4_quantize_values(fake, -1, fake, fake, None) == salr.SALR_ERR_INVALID_ARG
+    assert lib.salr_nf4_quantize_values(None, 8, fake, fake, None) == salr.SALR_ERR_INVALID_ARG
+    assert lib.salr_nf4_quantize_values(fake, 8, None, fake, None) == salr.SALR_ERR_INVALID_ARG
+    assert lib.salr_nf4_quantize_values(fake, 1 << 33, fake, fake, None) == salr.SALR_ERR_SHAPE
+    assert lib.salr_nf4_quantize_values(None, 0, None, None, None) == salr.SALR_OK
+    assert lib.salr_nf4_dequantize_values(fake, fake, -2, fake, None) == salr.SALR_ERR_INVALID_ARG
+    assert lib.salr_nf4_dequantize_values(fake, None, 8, fake, None) == salr.SALR_ERR_INVALID_ARG
+    assert lib.salr_nf4_dequantize_values(None, None, 0, None, None) == salr.SALR_OK
+    q = lib.salr_qsalr_linear_workspace_bytes
+    q.restype = ctypes.c_size_t
+    g = lib.salr_linear_workspace_bytes
+    # the dequantised values (2 bytes each, whole 16-byte vectors, 256-byte aligned) in front of the layer's own workspace
+    assert q(16, 4096, 4096, 32, 1000) == _r256(2 * 1000) + g(16, 4096, 4096, 32)
+    assert q(16, 4096, 4096, 32, 1001) == _r256(2 * 1008) + g(16, 4096, 4096, 32)
+    assert q(16, 4100, 4096, 32, 1000) == 0 and q(16, 4096, 4096, 32, -1) == 0
+
+    def call(M=4, K=64, N=8, R=4, nnz=100, x=fake, codes=fake, scales=fake, y=fake, ws=fake, ws_bytes=1 << 20):
+        return lib.salr_qsalr_linear(x, M, K, N, fake, codes, scales, fake, nnz, fake, fake, R, y, ws, ws_bytes, None)
+
+    assert call(nnz=-1) == salr.SALR_ERR_INVALID_ARG
+    assert call(codes=None) == salr.SALR_ERR_INVALID_ARG
+    assert call(scales=None) == salr.SALR_ERR_INVALID_ARG
+    assert call(K=40) == salr.SALR_ERR_SHAPE
+    assert call(nnz=4 * 64 * 8) == salr.SALR_ERR_SHAPE          # more stored values than the matrix has elements
+    assert call(R=300) == salr.SALR_ERR_UNSUPPORTED
+    assert call(ws=None) == salr.SALR_ERR_CAPACITY
+    assert call(ws_bytes=128) == salr.SALR_ERR_CAPACITY
+    assert call(M=0) == salr.SALR_OK
+    # the entry point without a workspace: same validation, and a size limit of its own
+    na = lib.salr_sparse_lowrank_linear_noalloc
+    assert na(fake, -1, 64, 8, fake, fake, fake, fake, fake, 4, fake, None) == salr.SALR_ERR_INVALID_ARG
+    assert na(fake, 4, 40, 8, fake, fake, fake, fake, fake, 4, fake, None) == salr.SALR_ERR_SHAPE
+    assert na(fake, 4, 64, 8, fake, fake, fake, fake, fake, 300, fake, None) == salr.SALR_ERR_UNSUPPORTED
+    assert na(fake, 2048, 4096, 14336, fake, fake, fake, fake, fake, 32, fake, None) == salr.SALR_ERR_CAPACITY
+    assert na(fake, 0, 64, 8, fake, fake, fake, fake, fake, 4, fake, None) == salr.SALR_OK
