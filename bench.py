@@ -119,9 +119,10 @@ class Layer:
         return [self.w_hat.view(torch.bfloat16).clone() for _ in range(n)]
 
 
-def time_linear(layer, M, steps, warmup, events=False, two_of_four=False):
+def time_linear(layer, M, steps, warmup, events=False, two_of_four=False, lean=False):
     """(ms per step by wall clock, list of per-launch kernel ms from HIP events or None).  two_of_four: the call is
-    salr_sparse_lowrank_linear_2of4 (the layer must be 2:4-masked)."""
+    salr_sparse_lowrank_linear_2of4 (the layer must be 2:4-masked).  lean: the call gets the least workspace it accepts
+    (large batches then run the fused kernel that keeps no decoded copy of the weight)."""
     import numpy as np
     import torch
     import paper_2601_16991_amd as salr
@@ -131,7 +132,9 @@ def time_linear(layer, M, steps, warmup, events=False, two_of_four=False):
     x = torch.from_numpy(wl.activations(cfg, M).view(np.int16)).to(dev)
     y = torch.empty((M, cfg.N), dtype=torch.int16, device=dev)
     ws_fn = salr.salr_linear_2of4_workspace_bytes if two_of_four else salr.salr_linear_workspace_bytes
-    ws = torch.empty(max(ws_fn(M, cfg.K, cfg.N, layer.R), 256), dtype=torch.uint8, device=dev)
+    if lean:
+        ws_fn = salr.salr_linear_workspace_bytes_min
+    ws = torch.empty(max(ws_fn(M, cfg.K, cfg.N, layer.R), 256), dtype=torch.uint8, device=dev)[:max(ws_fn(M, cfg.K, cfg.N, layer.R), 1)]
 
     calls = [salr.PreparedLinear(x, b, v, o, layer.a_cat, layer.b_cat, y, ws, two_of_four=two_of_four)
              for (b, v, o) in layer.enc]
@@ -325,7 +328,7 @@ def load_traffic(workload_key, field="bytes"):
         return None
 
 
-def config_row(layer, M, steps, warmup, two_of_four=False):
+def config_row(layer, M, steps, warmup, two_of_four=False, lean=False):
     """One row of the table: the call on `layer` at batch M, weights rotated so that they come from HBM.  Both the whole
     call (wall clock per step: every kernel of the call and the gaps between them) and its dominant kernel alone (HIP
     events on its launch) are set against the roofline that bounds the shape: HBM bytes up to 128 tokens, bf16 MFMA
@@ -334,12 +337,14 @@ def config_row(layer, M, steps, warmup, two_of_four=False):
     import paper_2601_16991_amd as salr
     import salr_workloads as wl
     cfg = layer.cfg
-    w_ms, k_ms = time_linear(layer, M, steps, warmup, events=True, two_of_four=two_of_four)
+    w_ms, k_ms = time_linear(layer, M, steps, warmup, events=True, two_of_four=two_of_four, lean=lean)
     d_ms = time_dense(layer, M, steps, warmup, with_lora=False)
     k = float(np.mean(k_ms))
     nbytes = wl.algorithmic_bytes(M, cfg.K, cfg.N, layer.R, layer.nnz)
     fl = wl.algorithmic_flops(M, cfg.K, cfg.N, layer.R)
     ws_fn = salr.salr_linear_2of4_workspace_bytes if two_of_four else salr.salr_linear_workspace_bytes
+    if lean:
+        ws_fn = salr.salr_linear_workspace_bytes_min
     row = {"ms_per_step": round(w_ms, 6), "kernel_avg_us": round(k * 1e3, 2), "dense_gemm_ms": round(d_ms, 6),
            "speedup_vs_dense_gemm": round(d_ms / w_ms, 3), "workspace_bytes": int(ws_fn(M, cfg.K, cfg.N, layer.R))}
     if M <= 128:
@@ -658,6 +663,12 @@ def main():
                     key = f"{cfg2.name}_p{pm}_M{m2}"
                     extras["configs"][key] = config_row(layer2, m2, steps2, 3)
                     log(f"{key}: {extras['configs'][key]}")
+                    if name2 in ("llama3_8b_gate_up_proj", "llama3_8b_down_proj") and pm == 500 and m2 >= 2048:
+                        # the same call with the least workspace: decode stage and MFMA stage in one kernel (LDS double
+                        # buffer), no decoded copy of the weight in memory
+                        key = f"{cfg2.name}_p{pm}_M{m2}_no_decoded_copy"
+                        extras["configs"][key] = config_row(layer2, m2, steps2, 3, lean=True)
+                        log(f"{key}: {extras['configs'][key]}")
                 del layer2
                 torch.cuda.empty_cache()
         # 2:4-masked layers through salr_sparse_lowrank_linear_2of4 (sparse MFMA on bitmap and values as they are)

@@ -132,6 +132,16 @@ salr_status_t salr_decode(const uint32_t* bitmap, const uint16_t* values, const 
 size_t salr_linear_workspace_bytes(int64_t M, int64_t K, int64_t N, int64_t R);
 
 /*
+ * The least workspace salr_sparse_lowrank_linear runs with.  It differs from the size above for large batches only:
+ * given at least this much but less than salr_linear_workspace_bytes, the call keeps no decoded copy of the weight
+ * and runs the pipeline of Sec. 3.3 inside one kernel instead (bitmap decode of the next weight tile into
+ * double-buffered LDS tiles while the matrix cores multiply the current one).  That is slower than decoding once
+ * into memory (every 256-row block of X decodes the weight again) but the weight never exists in dense form
+ * outside LDS, which is what the format is for when memory is short.  Returns 0 for invalid sizes.
+ */
+size_t salr_linear_workspace_bytes_min(int64_t M, int64_t K, int64_t N, int64_t R);
+
+/*
  * salr_sparse_lowrank_linear -- the layer of Sec. 3.2 / 3.3:
  *
  *     Y = X * W-hat^T + (X * A_cat) * B_cat
@@ -149,8 +159,9 @@ size_t salr_linear_workspace_bytes(int64_t M, int64_t K, int64_t N, int64_t R);
  *   a_cat        in   [K, R] bf16; may be NULL iff R == 0
  *   b_cat        in   [R, N] bf16; may be NULL iff R == 0
  *   y            out  [M, N] bf16, overwritten
- *   workspace    --   at least salr_linear_workspace_bytes(M, K, N, R) bytes, 256-byte aligned;
- *                     may be NULL when that size is 0.  Contents before and after are unspecified.
+ *   workspace    --   salr_linear_workspace_bytes(M, K, N, R) bytes, 256-byte aligned (at least
+ *                     salr_linear_workspace_bytes_min: see there for what the smaller size means); may be NULL
+ *                     when that size is 0.  Contents before and after are unspecified.
  *
  * Constraints: K % 32 == 0 (else SHAPE); R <= 256 (else UNSUPPORTED); M, N < 2^31.
  * K == 0: x, bitmap, values, a_cat may be NULL; Y is written as zeros (both products are empty sums).
@@ -171,9 +182,10 @@ salr_status_t salr_sparse_lowrank_linear(const uint16_t* x, int64_t M, int64_t K
  * fixed array of SALR_NOALLOC_SCRATCH_BYTES bytes of device memory inside the library's code object, which every GPU
  * the library runs on holds from the first use until the process ends.  The call allocates and frees nothing.
  *
- * Limit: sizes for which salr_linear_workspace_bytes(M, K, N, R) exceeds SALR_NOALLOC_SCRATCH_BYTES are refused with
- * SALR_ERR_CAPACITY before anything is enqueued (decode-sized batches fit; batches that decode the weight into a
- * dense scratch matrix do not).
+ * Limit: sizes for which neither salr_linear_workspace_bytes(M, K, N, R) nor salr_linear_workspace_bytes_min(M, K, N,
+ * R) fits SALR_NOALLOC_SCRATCH_BYTES are refused with SALR_ERR_CAPACITY before anything is enqueued.  Decode-sized
+ * batches fit; large batches, whose preferred path decodes the weight into a dense scratch matrix, run the
+ * fused kernel of salr_linear_workspace_bytes_min instead as long as their adapter intermediates fit.
  * The device that is current when the call is made must be the one `stream` belongs to; the first call on a device
  * looks up that device's copy of the array (no allocation; make it outside a graph capture).
  * All calls on one GPU share that GPU's array: calls that may overlap on one GPU (different streams without

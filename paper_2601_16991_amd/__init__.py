@@ -54,6 +54,8 @@ def lib() -> ctypes.CDLL:
         L.salr_decode.argtypes = [_vp, _vp, _vp, _i64, _i64, _vp, _vp]
         L.salr_linear_workspace_bytes.restype = ctypes.c_size_t
         L.salr_linear_workspace_bytes.argtypes = [_i64, _i64, _i64, _i64]
+        L.salr_linear_workspace_bytes_min.restype = ctypes.c_size_t
+        L.salr_linear_workspace_bytes_min.argtypes = [_i64, _i64, _i64, _i64]
         L.salr_sparse_lowrank_linear.restype = ctypes.c_int
         L.salr_sparse_lowrank_linear.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _vp,
                                                  ctypes.c_size_t, _vp]
@@ -166,6 +168,10 @@ def salr_decode(bitmap: torch.Tensor, values: torch.Tensor, row_offsets: torch.T
 
 def salr_linear_workspace_bytes(M: int, K: int, N: int, R: int) -> int:
     return int(lib().salr_linear_workspace_bytes(M, K, N, R))
+
+
+def salr_linear_workspace_bytes_min(M: int, K: int, N: int, R: int) -> int:
+    return int(lib().salr_linear_workspace_bytes_min(M, K, N, R))
 
 
 def salr_sparse_lowrank_linear(x: torch.Tensor, bitmap: torch.Tensor, values: torch.Tensor,

@@ -155,6 +155,11 @@ size_t salr_linear_workspace_bytes(int64_t M, int64_t K, int64_t N, int64_t R) {
     return salr::linear_workspace_bytes(M, K, N, R);
 }
 
+size_t salr_linear_workspace_bytes_min(int64_t M, int64_t K, int64_t N, int64_t R) {
+    if (M <= 0 || K < 0 || N <= 0 || R < 0 || R > kMaxRank || K % 32 != 0) return 0;
+    return salr::linear_workspace_bytes_lean(M, K, N, R);
+}
+
 salr_status_t salr_sparse_lowrank_linear(const uint16_t* x, int64_t M, int64_t K, int64_t N, const uint32_t* bitmap,
                                          const uint16_t* values, const uint32_t* row_offsets, const uint16_t* a_cat,
                                          const uint16_t* b_cat, int64_t R, uint16_t* y, void* workspace,
@@ -172,13 +177,16 @@ salr_status_t salr_sparse_lowrank_linear(const uint16_t* x, int64_t M, int64_t K
         return e0 == hipSuccess ? SALR_OK : SALR_ERR_HIP;
     }
     const size_t need = salr_linear_workspace_bytes(M, K, N, R);
-    if (need > 0 && (!workspace || workspace_bytes < need)) return SALR_ERR_CAPACITY;
+    const size_t least = salr::linear_workspace_bytes_lean(M, K, N, R);
+    const size_t have = workspace ? workspace_bytes : 0;
+    if (have < least) return SALR_ERR_CAPACITY;
     salr::LinearArgs a;
     a.x = x; a.M = M; a.K = K; a.N = N;
     a.bitmap = bitmap; a.values = values; a.row_offsets = row_offsets;
     a.a_cat = a_cat; a.b_cat = b_cat; a.R = R;
     a.y = y;
     a.t = static_cast<uint16_t*>(workspace);
+    a.lean = have < need;   // no room for the decoded copy: decode stage and MFMA stage in one kernel
     hipError_t e = salr::launch_linear(a, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? SALR_OK : SALR_ERR_HIP;
 }
@@ -191,7 +199,8 @@ salr_status_t salr_sparse_lowrank_linear_noalloc(const uint16_t* x, int64_t M, i
     if (M == 0 || N == 0) return SALR_OK;
     if (K % 32 != 0) return SALR_ERR_SHAPE;
     if (R > kMaxRank) return SALR_ERR_UNSUPPORTED;
-    const size_t need = K > 0 ? salr::linear_workspace_bytes(M, K, N, R) : 0;
+    size_t need = K > 0 ? salr::linear_workspace_bytes(M, K, N, R) : 0;
+    if (need > SALR_NOALLOC_SCRATCH_BYTES && K > 0) need = salr::linear_workspace_bytes_lean(M, K, N, R);   // large batches: fused kernel
     if (need > SALR_NOALLOC_SCRATCH_BYTES) return SALR_ERR_CAPACITY;
     void* ws = nullptr;
     if (need > 0 && scratch_of_current_device(&ws) != hipSuccess) return SALR_ERR_HIP;

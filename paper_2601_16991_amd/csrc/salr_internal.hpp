@@ -49,6 +49,7 @@ struct LinearArgs {
     int64_t R;
     uint16_t* y;
     uint16_t* t;  // workspace (see linear_workspace_bytes)
+    bool lean = false;  // large batches: no room for a decoded copy of the weight, take the fused kernel
 };
 
 // Optional events recorded around the fused kernel's launch (measurement hook of the boundary).
@@ -183,6 +184,14 @@ inline size_t linear_workspace_bytes(int64_t M, int64_t K, int64_t N, int64_t R)
     return b;
 }
 
+// The least the layer runs with: where the preferred path decodes the weight into the workspace (large batches), the
+// fused kernel needs the adapter part only.
+inline size_t linear_workspace_bytes_lean(int64_t M, int64_t K, int64_t N, int64_t R) {
+    if (M <= 0 || N <= 0) return 0;
+    if (!uses_rowtile(M, K, N) && M > kStreamMaxM && uses_twostage(M, K)) return twostage_dense_offset(M, K, R);
+    return linear_workspace_bytes(M, K, N, R);
+}
+
 // Backward pass of the layer: dx [M, K], da [K, R], db [R, N]; any of them may be null (not computed)
 size_t linear_backward_workspace_bytes(int64_t M, int64_t K, int64_t N, int64_t R, bool want_dx, bool want_dadb);
 hipError_t launch_linear_backward(const uint16_t* x, const uint16_t* dy, int64_t M, int64_t K, int64_t N,
@@ -204,6 +213,8 @@ hipError_t launch_linear_stream(const LinearArgs& args, hipStream_t stream, cons
 bool linear_slice_takes(int64_t M, int64_t K, int64_t N);
 hipError_t launch_linear_slice(const LinearArgs& args, hipStream_t stream, const TimingEvents& ev);
 hipError_t launch_linear_twostage(const LinearArgs& args, hipStream_t stream, const TimingEvents& ev);
+// the same shapes without a decoded copy of the weight: decode stage and MFMA stage in one kernel (K % 64 == 0)
+hipError_t launch_linear_tiled(const LinearArgs& args, hipStream_t stream, const TimingEvents& ev);
 hipError_t launch_linear_rowtile(const LinearArgs& args, hipStream_t stream, const TimingEvents& ev);
 hipError_t launch_linear_2of4(const LinearArgs& args, hipStream_t stream, const TimingEvents& ev);
 hipError_t launch_gemm_2of4(const LinearArgs& args, hipStream_t stream, const TimingEvents& ev);

@@ -172,7 +172,8 @@ hipError_t launch_linear(const LinearArgs& a, hipStream_t stream) {
     if (uses_rowtile(a.M, a.K, a.N)) return launch_linear_rowtile(a, stream, g_timing_events);
     if (linear_slice_takes(a.M, a.K, a.N)) return launch_linear_slice(a, stream, g_timing_events);
     if (a.M <= kStreamMaxM) return launch_linear_stream(a, stream, g_timing_events);
-    if (uses_twostage(a.M, a.K)) return launch_linear_twostage(a, stream, g_timing_events);
+    if (uses_twostage(a.M, a.K))
+        return a.lean ? launch_linear_tiled(a, stream, g_timing_events) : launch_linear_twostage(a, stream, g_timing_events);
     const int R = (int)a.R;
     const int Rpad = (int)adapter_rank_padded(a.R);
     if (R > 0) launch_adapter_t(a, stream);

@@ -338,5 +338,5 @@ def test_qsalr_and_noalloc_validation(lib):
     assert na(fake, -1, 64, 8, fake, fake, fake, fake, fake, 4, fake, None) == salr.SALR_ERR_INVALID_ARG
     assert na(fake, 4, 40, 8, fake, fake, fake, fake, fake, 4, fake, None) == salr.SALR_ERR_SHAPE
     assert na(fake, 4, 64, 8, fake, fake, fake, fake, fake, 300, fake, None) == salr.SALR_ERR_UNSUPPORTED
-    assert na(fake, 2048, 4096, 14336, fake, fake, fake, fake, fake, 32, fake, None) == salr.SALR_ERR_CAPACITY
+    assert na(fake, 4096, 28672, 8192, fake, fake, fake, fake, fake, 64, fake, None) == salr.SALR_ERR_CAPACITY
     assert na(fake, 0, 64, 8, fake, fake, fake, fake, fake, 4, fake, None) == salr.SALR_OK

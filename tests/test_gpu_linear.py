@@ -153,6 +153,50 @@ def test_small_batch_long_rows(M, K, N, ranks, density):
                   f"long rows M{M} K{K} N{N} R{sum(ranks)} density {density}")
 
 
+def _run_lean(x, w_hat, a_cat, b_cat):
+    """The call with the least workspace it accepts: large batches then keep no decoded copy of the weight."""
+    salr = _salr()
+    M, K = x.shape
+    N = w_hat.shape[0]
+    R = 0 if a_cat is None else a_cat.shape[1]
+    rb, rv, ro = oracle.encode(w_hat)
+    least = salr.salr_linear_workspace_bytes_min(M, K, N, R)
+    assert least < salr.salr_linear_workspace_bytes(M, K, N, R)
+    ws = torch.randint(0, 256, (max(least, 256),), dtype=torch.uint8, device=dev())[:least]
+    y = salr.linear(to_dev_u16(x), to_dev_u32(rb), to_dev_u16(rv), to_dev_u32(ro),
+                    None if a_cat is None else to_dev_u16(a_cat), None if b_cat is None else to_dev_u16(b_cat),
+                    workspace=ws if least else torch.empty(0, dtype=torch.uint8, device=dev()))
+    torch.cuda.synchronize()
+    return y_to_f64(y)
+
+
+@pytest.mark.parametrize("M,K,N,ranks,density", [
+    # M > 64 with K % 64 == 0 and a workspace without room for the decoded weight: decode stage and MFMA stage in one
+    # kernel (256 x 128 tiles, double-buffered LDS); ragged in both tile dimensions, 1 to 64 chunks of 64 columns
+    (200, 512, 300, (16, 16), 0.5), (255, 128, 513, (7,), 0.5), (70, 320, 64, (), 0.5), (65, 960, 1030, (40, 60), 0.5),
+    (1030, 64, 100, (), 0.5), (300, 1024, 260, (16,), 0.5), (600, 192, 260, (16,), 0.5), (129, 64, 129, (3,), 0.5),
+    (257, 4096, 36, (3,), 0.5), (512, 512, 100, (), 1.0), (300, 640, 140, (8,), 0.95), (260, 256, 130, (4, 4), 0.05),
+    (256, 2048, 128, (128, 128), 0.3),
+])
+def test_large_batch_without_decoded_copy(M, K, N, ranks, density):
+    x, w, a_cat, b_cat = _problem(M, K, N, ranks, 11 * M + K + 5 * N, density=density, std_ab=0.05)
+    _assert_close(_run_lean(x, w, a_cat, b_cat), oracle.linear(x, w, a_cat, b_cat),
+                  f"fused M{M} K{K} N{N} R{sum(ranks)} density {density}")
+
+
+def test_gate_up_prefill_without_decoded_copy_sampled_rows():
+    """Full-size launch of the fused kernel (M = 2048 on the gate/up layer); the oracle checks 8 rows of X across all N."""
+    cfg = wl.CONFIGS["llama3_8b_gate_up_proj"]
+    M = cfg.Ms[0]
+    w_hat = oracle.mask_topk_rows(wl.dense_weight(cfg), cfg.keep(500))
+    a_cat, b_cat = wl.concat_adapters(*wl.adapters(cfg))
+    x = wl.activations(cfg, M)
+    y = _run_lean(x, w_hat, a_cat, b_cat)
+    rows = np.array([0, 1, 255, 256, 777, 1024, 2046, 2047])
+    _assert_close(y[rows], oracle.linear(np.ascontiguousarray(x[rows]), w_hat, a_cat, b_cat), "gate/up M=2048 fused (8 sampled rows)")
+    assert np.isfinite(y).all()
+
+
 @pytest.mark.parametrize("M,N", [(4096, 3584), (4090, 3580)])
 def test_many_tiles_224_wide(M, N):
     """16 row blocks x 14 column blocks of 256 x 256 would leave the second round of the 256 CUs mostly empty;

@@ -59,10 +59,31 @@ def test_noalloc_matches_workspace_call_twice_in_a_row(first, second):
         assert err <= REL_TOL * scale
 
 
+def test_noalloc_large_batch_takes_the_kernel_without_a_decoded_copy():
+    """A large batch whose preferred workspace (a decoded copy of the weight) is beyond the fixed array runs the fused
+    kernel on the adapter intermediates alone; against the workspace call given that same least size, and the oracle."""
+    import paper_2601_16991_amd as salr
+    M, K, N, ranks = 300, 8192, 1200, (16, 16)
+    R = sum(ranks)
+    assert salr.salr_linear_workspace_bytes(M, K, N, R) > salr.NOALLOC_SCRATCH_BYTES
+    least = salr.salr_linear_workspace_bytes_min(M, K, N, R)
+    assert 0 < least <= salr.NOALLOC_SCRATCH_BYTES
+    x, w, a_cat, b_cat = _problem(M, K, N, ranks, 4321)
+    rb, rv, ro = oracle.encode(w)
+    d = (to_dev_u16(x), to_dev_u32(rb), to_dev_u16(rv), to_dev_u32(ro), to_dev_u16(a_cat), to_dev_u16(b_cat))
+    y_ws = salr.linear(*d, workspace=torch.empty(least, dtype=torch.uint8, device=dev()))
+    y_na = torch.empty_like(y_ws)
+    salr.salr_sparse_lowrank_linear_noalloc(*d, y_na)
+    torch.cuda.synchronize()
+    assert torch.equal(y_ws, y_na)
+    y_ref = oracle.linear(x, w, a_cat, b_cat)
+    assert float(np.max(np.abs(y_to_f64(y_na) - y_ref))) <= REL_TOL * float(np.max(np.abs(y_ref)))
+
+
 def test_noalloc_refuses_sizes_beyond_its_scratch():
     import paper_2601_16991_amd as salr
-    M, K, N, R = 2048, 4096, 14336, 32     # needs a dense copy of the weight: far beyond the fixed array
-    assert salr.salr_linear_workspace_bytes(M, K, N, R) > salr.NOALLOC_SCRATCH_BYTES
+    M, K, N, R = 4096, 28672, 8192, 64     # even the adapter intermediates alone are beyond the fixed array
+    assert salr.salr_linear_workspace_bytes_min(M, K, N, R) > salr.NOALLOC_SCRATCH_BYTES
     fake = 0x1000                          # never dereferenced: the call fails validation first
     st = salr.lib().salr_sparse_lowrank_linear_noalloc(fake, M, K, N, fake, fake, fake, fake, fake, R, fake, None)
     assert st == salr.SALR_ERR_CAPACITY
