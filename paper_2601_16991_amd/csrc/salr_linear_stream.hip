@@ -441,7 +441,9 @@ static void launch_stream_t(const LinearArgs& a, hipStream_t stream, const Timin
     if (wpr % kChunkWords != 0)  // bitmap rows are not multiples of 16 bytes: scalar bitmap loads
         SALR_LAUNCH((linear_stream_kernel<MT, NW, S, false, false>), dim3(grid), dim3(NW * 64), stream, ev, a.x, (int)a.M, a.K,
                     a.N, a.bitmap, a.values, a.row_offsets, (const float*)t_partial, a.b_cat, R, Rpad, a.y);
-    else if (wpr / kChunkWords <= 32)  // short rows: barrier-free start
+    else if (wpr / kChunkWords <= 32 && S != 2)  // short rows and one workgroup per CU: barrier-free start (two workgroups
+                                                 // per CU hide each other's barrier, and the bitmap words left of a slice,
+                                                 // which every wave would fetch again, are a third of the L2 reads)
         SALR_LAUNCH((linear_stream_kernel<MT, NW, S, true, true>), dim3(grid), dim3(NW * 64), stream, ev, a.x, (int)a.M, a.K,
                     a.N, a.bitmap, a.values, a.row_offsets, (const float*)t_partial, a.b_cat, R, Rpad, a.y);
     else
