@@ -457,6 +457,7 @@ WORKLOADS = {"q_proj_M16": ("llama3_8b_q_proj", 16), "gate_up_M2048": ("llama3_8
              "down_proj_M4096": ("llama3_8b_down_proj", 4096), "gate_up_70b_M1": ("llama3_70b_gate_up_proj", 1),
              "gate_up_70b_M16": ("llama3_70b_gate_up_proj", 16), "gate_up_M16": ("llama3_8b_gate_up_proj", 16),
              "gate_up_M64": ("llama3_8b_gate_up_proj", 64), "down_proj_M128": ("llama3_8b_down_proj", 128),
+             "down_proj_M8": ("llama3_8b_down_proj", 8), "down_proj_70b_M1": ("llama3_70b_down_proj", 1),
              # 2:4-masked layers through salr_sparse_lowrank_linear_2of4
              "q_proj_M16_2of4": ("llama3_8b_q_proj", 16), "gate_up_M16_2of4": ("llama3_8b_gate_up_proj", 16),
              "gate_up_70b_M1_2of4": ("llama3_70b_gate_up_proj", 1), "gate_up_70b_M16_2of4": ("llama3_70b_gate_up_proj", 16),
@@ -526,7 +527,9 @@ def prefill_result(args, name, M, two_of_four=False):
         "speedup_vs_dense_gemm": round(d_ms / w_ms, 3), "dense_gemm_ms": round(d_ms, 6),
         "dense_gemm_TFLOP/s": round(2 * M * cfg.N * cfg.K / d_ms / 1e9, 1),
         "roofline": {"bound": "mfma", "achieved": round(achieved, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                     "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
+                     "traffic": None if two_of_four else load_traffic(f"{name}_M{M}"),
+                     "traffic_measured_at": None if two_of_four else load_traffic(f"{name}_M{M}", "measured_at"),
                      "frac_call": round(fl / (w_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
                      "kernel": ("GEMM on the sparse MFMA (gemm_2of4_kernel) of salr_sparse_lowrank_linear_2of4, in "
                                 "dense-equivalent flops; the adapter stage of the call is in `value` but not in this figure"
@@ -551,6 +554,9 @@ def main():
                          "against the HBM peak)")
     ap.add_argument("--no-extras", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="run three plain copies of 64 MiB (torch copy_, int32) before the workload: under rocprofv3 --pmc "
+                         "FETCH_SIZE / WRITE_SIZE they give the factor between the counters and bytes moved")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -564,6 +570,13 @@ def main():
     salr.lib()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     log("device:", torch.cuda.get_device_name(0))
+    if args.pmc_calibration:
+        src = torch.arange(16 << 20, dtype=torch.int32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     if args.workload != "q_proj_M16":
         name, m = WORKLOADS[args.workload]
         if args.workload.endswith("_2of4"):
