@@ -112,6 +112,14 @@ class Layer:
         self.a_cat = torch.from_numpy(a_cat.view(np.int16)).to(dev)
         self.b_cat = torch.from_numpy(b_cat.view(np.int16)).to(dev)
         self.R = cfg.R
+        self._tables = None
+
+    def tables(self):
+        """The layer's slice table, one per encoded copy (built on first use)."""
+        import paper_2601_16991_amd as salr
+        if self._tables is None:
+            self._tables = [salr.build_slice_table(b, o, self.cfg.K) for (b, v, o) in self.enc]
+        return self._tables
 
     def dense_copies(self):
         import torch
@@ -119,10 +127,11 @@ class Layer:
         return [self.w_hat.view(torch.bfloat16).clone() for _ in range(n)]
 
 
-def time_linear(layer, M, steps, warmup, events=False, two_of_four=False, lean=False):
+def time_linear(layer, M, steps, warmup, events=False, two_of_four=False, lean=False, prepared=False):
     """(ms per step by wall clock, list of per-launch kernel ms from HIP events or None).  two_of_four: the call is
     salr_sparse_lowrank_linear_2of4 (the layer must be 2:4-masked).  lean: the call gets the least workspace it accepts
-    (large batches then run the fused kernel that keeps no decoded copy of the weight)."""
+    (large batches then run the fused kernel that keeps no decoded copy of the weight).  prepared: the call is
+    salr_sparse_lowrank_linear_prepared with the layer's slice table."""
     import numpy as np
     import torch
     import paper_2601_16991_amd as salr
@@ -136,8 +145,9 @@ def time_linear(layer, M, steps, warmup, events=False, two_of_four=False, lean=F
         ws_fn = salr.salr_linear_workspace_bytes_min
     ws = torch.empty(max(ws_fn(M, cfg.K, cfg.N, layer.R), 256), dtype=torch.uint8, device=dev)[:max(ws_fn(M, cfg.K, cfg.N, layer.R), 1)]
 
-    calls = [salr.PreparedLinear(x, b, v, o, layer.a_cat, layer.b_cat, y, ws, two_of_four=two_of_four)
-             for (b, v, o) in layer.enc]
+    tables = layer.tables() if prepared else [None] * len(layer.enc)
+    calls = [salr.PreparedLinear(x, b, v, o, layer.a_cat, layer.b_cat, y, ws, two_of_four=two_of_four, slice_table=t)
+             for (b, v, o), t in zip(layer.enc, tables)]
     stream = torch.cuda.current_stream().cuda_stream or None
 
     def call(i):
@@ -328,19 +338,20 @@ def load_traffic(workload_key, field="bytes"):
         return None
 
 
-def config_row(layer, M, steps, warmup, two_of_four=False, lean=False):
+def config_row(layer, M, steps, warmup, two_of_four=False, lean=False, prepared=False):
     """One row of the table: the call on `layer` at batch M, weights rotated so that they come from HBM.  Both the whole
     call (wall clock per step: every kernel of the call and the gaps between them) and its dominant kernel alone (HIP
     events on its launch) are set against the roofline that bounds the shape: HBM bytes up to 128 tokens, bf16 MFMA
-    flops above (2:4 rows: dense-equivalent flops; the sparse instructions execute half of them)."""
+    flops above (2:4 rows: dense-equivalent flops; the sparse instructions execute half of them).  prepared: the call
+    with the layer's slice table (64 more bytes per weight row, counted)."""
     import numpy as np
     import paper_2601_16991_amd as salr
     import salr_workloads as wl
     cfg = layer.cfg
-    w_ms, k_ms = time_linear(layer, M, steps, warmup, events=True, two_of_four=two_of_four, lean=lean)
+    w_ms, k_ms = time_linear(layer, M, steps, warmup, events=True, two_of_four=two_of_four, lean=lean, prepared=prepared)
     d_ms = time_dense(layer, M, steps, warmup, with_lora=False)
     k = float(np.mean(k_ms))
-    nbytes = wl.algorithmic_bytes(M, cfg.K, cfg.N, layer.R, layer.nnz)
+    nbytes = wl.algorithmic_bytes(M, cfg.K, cfg.N, layer.R, layer.nnz) + (64 * cfg.N if prepared else 0)
     fl = wl.algorithmic_flops(M, cfg.K, cfg.N, layer.R)
     ws_fn = salr.salr_linear_2of4_workspace_bytes if two_of_four else salr.salr_linear_workspace_bytes
     if lean:
@@ -659,6 +670,10 @@ def main():
         for m in cfg.Ms:
             extras["configs"][f"{cfg.name}_p{permille}_M{m}"] = config_row(layer, m, min(args.steps, 100), min(args.warmup, 10))
             log(f"{cfg.name} p={permille} M={m}: {extras['configs'][f'{cfg.name}_p{permille}_M{m}']}")
+            # the same call on the prepared layer (salr_sparse_lowrank_linear_prepared: cursors from the slice table)
+            key = f"{cfg.name}_p{permille}_M{m}_prepared"
+            extras["configs"][key] = config_row(layer, m, min(args.steps, 100), min(args.warmup, 10), prepared=True)
+            log(f"{key}: {extras['configs'][key]}")
         del layer
         torch.cuda.empty_cache()
         for name2 in ("llama3_8b_gate_up_proj", "llama3_8b_down_proj", "llama3_70b_attn", "llama3_70b_gate_up_proj",
@@ -668,7 +683,7 @@ def main():
                 layer2 = Layer(cfg2, pm, max_copies=4)
                 ms_list = list(cfg2.Ms)
                 if name2 == "llama3_8b_gate_up_proj":
-                    ms_list = [16, 64, 128] + ms_list      # the batch sizes between decode and prefill as well
+                    ms_list = [1, 8, 16, 64, 128] + ms_list      # decode sizes and the batch sizes up to prefill as well
                 if name2 == "llama3_8b_down_proj" and pm == 500:
                     ms_list = sorted(set(ms_list + [16, 128]))
                 for m2 in ms_list:
@@ -681,6 +696,12 @@ def main():
                         # buffer), no decoded copy of the weight in memory
                         key = f"{cfg2.name}_p{pm}_M{m2}_no_decoded_copy"
                         extras["configs"][key] = config_row(layer2, m2, steps2, 3, lean=True)
+                        log(f"{key}: {extras['configs'][key]}")
+                    if pm == 500 and ((name2 in ("llama3_8b_gate_up_proj", "llama3_8b_down_proj") and m2 <= 8) or
+                                      (name2.startswith("llama3_70b") and m2 == 1)):
+                        # where the small-batch streaming kernels run: also on the prepared layer (slice table)
+                        key = f"{cfg2.name}_p{pm}_M{m2}_prepared"
+                        extras["configs"][key] = config_row(layer2, m2, steps2, 3, prepared=True)
                         log(f"{key}: {extras['configs'][key]}")
                 del layer2
                 torch.cuda.empty_cache()

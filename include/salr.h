@@ -132,6 +132,31 @@ salr_status_t salr_decode(const uint32_t* bitmap, const uint16_t* values, const 
 size_t salr_linear_workspace_bytes(int64_t M, int64_t K, int64_t N, int64_t R);
 
 /*
+ * Slice table of a layer: a derived index for small batches (Sec. 3.3 reads the value array sequentially; where a
+ * row's values for a given range of columns start is otherwise found by popcounting the bitmap words before them, a
+ * round trip to memory that every workgroup of the small-batch kernel pays before it can ask for its first value).
+ * For row n and slice w = 0..7 of the row's C = ceil(K / 128) chunks of 128 columns (chunks [C w / 8, C (w + 1) / 8)):
+ *     table[(n * 8 + w) * 2 + 0] = row_offsets[n] + nonzeros of row n in the columns before the slice
+ *     table[(n * 8 + w) * 2 + 1] = the most nonzeros that any one chunk of the slice holds
+ * It follows from bitmap and row_offsets alone (the three arrays above stay the format); build it once per layer.
+ *   salr_slice_table_bytes   N * 64 bytes (0 for arguments the builder would refuse)
+ *   salr_build_slice_table   slice_table out, [N, 8, 2] uint32, at least that many bytes (else CAPACITY)
+ *   salr_sparse_lowrank_linear_prepared   salr_sparse_lowrank_linear with the table as one more input; the result is
+ *       the same bit for bit; paths that have no use for the table (larger batches, rows that are not whole chunks)
+ *       ignore it.  A table that does not belong to the weight gives unspecified values in Y and may read `values` out
+ *       of bounds: it is the caller's to keep the two together, as with row_offsets.
+ * Errors: INVALID_ARG, SHAPE, CAPACITY, HIP, and those of salr_sparse_lowrank_linear.
+ */
+size_t salr_slice_table_bytes(int64_t N, int64_t K);
+salr_status_t salr_build_slice_table(const uint32_t* bitmap, const uint32_t* row_offsets, int64_t N, int64_t K,
+                                     uint32_t* slice_table, size_t slice_table_bytes, void* stream);
+salr_status_t salr_sparse_lowrank_linear_prepared(const uint16_t* x, int64_t M, int64_t K, int64_t N, const uint32_t* bitmap,
+                                                  const uint16_t* values, const uint32_t* row_offsets,
+                                                  const uint32_t* slice_table, const uint16_t* a_cat, const uint16_t* b_cat,
+                                                  int64_t R, uint16_t* y, void* workspace, size_t workspace_bytes,
+                                                  void* stream);
+
+/*
  * The least workspace salr_sparse_lowrank_linear runs with.  It differs from the size above for large batches only:
  * given at least this much but less than salr_linear_workspace_bytes, the call keeps no decoded copy of the weight
  * and runs the pipeline of Sec. 3.3 inside one kernel instead (bitmap decode of the next weight tile into

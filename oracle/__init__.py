@@ -19,7 +19,8 @@ concatenation against the sum over adapters on integer-valued matrices; the back
 forward pass (C code, not numpy) through the adjoint identities and against pure-Python loops; the NF4
 quantiser of the packed values (QSALR) against a brute-force nearest-entry search in exact rational arithmetic,
 hand-worked blocks, its error bound, idempotence and scale invariance, and the code book against the quantile
-rule it comes from.  No function here is "parity unpinned".
+rule it comes from; the slice table (a derived index of the format) against pure-Python bit loops, the row offsets it
+must start from and end at, and the popcounts of the decoded matrix.  No function here is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -161,6 +162,30 @@ def decode(bitmap: np.ndarray, values: np.ndarray, row_offsets: np.ndarray, rows
     rc = fn(_p(bitmap, _u32p), _p(values, _u16p), _p(row_offsets, _u32p), rows, cols, _p(out, _u16p))
     if rc:
         raise RuntimeError(f"decode failed ({rc})")
+    return out
+
+
+def slice_table(bitmap: np.ndarray, row_offsets: np.ndarray, cols: int, slices: int = 8) -> np.ndarray:
+    """Where the packed values of a range of columns start (Sec. 3.3: the value array is read sequentially, so the
+    position of a column's value is the number of set bits before it).  For row n and slice w of the row's
+    C = ceil(cols / 128) chunks of 128 columns, slice w = chunks [C w / slices, C (w + 1) / slices):
+        out[n, w, 0] = row_offsets[n] + set bits of row n in the columns before the slice
+        out[n, w, 1] = the most set bits that any one chunk of the slice holds.
+    Written out on the bit matrix itself, column by column range."""
+    bitmap = _c(bitmap, np.uint32)
+    row_offsets = _c(row_offsets, np.uint32)
+    rows = bitmap.shape[0]
+    bits = np.unpackbits(bitmap.view(np.uint8).reshape(rows, -1), axis=1, bitorder="little")[:, :cols].astype(np.int64)
+    chunks = (cols + 127) // 128
+    out = np.zeros((rows, slices, 2), dtype=np.uint32)
+    for w in range(slices):
+        c0, c1 = chunks * w // slices, chunks * (w + 1) // slices
+        before = bits[:, :min(128 * c0, cols)].sum(axis=1)
+        out[:, w, 0] = (row_offsets[:rows].astype(np.int64) + before).astype(np.uint32)
+        longest = np.zeros(rows, dtype=np.int64)
+        for c in range(c0, c1):
+            longest = np.maximum(longest, bits[:, 128 * c:min(128 * (c + 1), cols)].sum(axis=1))
+        out[:, w, 1] = longest.astype(np.uint32)
     return out
 
 

@@ -59,6 +59,13 @@ def lib() -> ctypes.CDLL:
         L.salr_sparse_lowrank_linear.restype = ctypes.c_int
         L.salr_sparse_lowrank_linear.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _vp,
                                                  ctypes.c_size_t, _vp]
+        L.salr_slice_table_bytes.restype = ctypes.c_size_t
+        L.salr_slice_table_bytes.argtypes = [_i64, _i64]
+        L.salr_build_slice_table.restype = ctypes.c_int
+        L.salr_build_slice_table.argtypes = [_vp, _vp, _i64, _i64, _vp, ctypes.c_size_t, _vp]
+        L.salr_sparse_lowrank_linear_prepared.restype = ctypes.c_int
+        L.salr_sparse_lowrank_linear_prepared.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _vp,
+                                                          ctypes.c_size_t, _vp]
         L.salr_sparse_lowrank_linear_noalloc.restype = ctypes.c_int
         L.salr_sparse_lowrank_linear_noalloc.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _vp]
         L.salr_nf4_quantize_values.restype = ctypes.c_int
@@ -194,6 +201,42 @@ def salr_sparse_lowrank_linear(x: torch.Tensor, bitmap: torch.Tensor, values: to
                                           _ptr(a_cat, _BF16_TYPES, "a_cat"), _ptr(b_cat, _BF16_TYPES, "b_cat"), R,
                                           _ptr(y, _BF16_TYPES, "y"), ws_ptr, ws_bytes, _stream(stream))
     _check(st, "salr_sparse_lowrank_linear")
+
+
+def salr_slice_table_bytes(N: int, K: int) -> int:
+    return int(lib().salr_slice_table_bytes(N, K))
+
+
+def salr_build_slice_table(bitmap: torch.Tensor, row_offsets: torch.Tensor, K: int, slice_table: torch.Tensor,
+                           stream=None) -> None:
+    """Enqueue the layer's slice table: slice_table int32/uint32 [N, 8, 2] (see include/salr.h)."""
+    N = bitmap.shape[0]
+    _check(lib().salr_build_slice_table(_ptr(bitmap, _U32_TYPES, "bitmap"), _ptr(row_offsets, _U32_TYPES, "row_offsets"),
+                                        N, K, _ptr(slice_table, _U32_TYPES, "slice_table"),
+                                        slice_table.numel() * slice_table.element_size(), _stream(stream)),
+           "salr_build_slice_table")
+
+
+def salr_sparse_lowrank_linear_prepared(x: torch.Tensor, bitmap: torch.Tensor, values: torch.Tensor,
+                                        row_offsets: torch.Tensor, slice_table: torch.Tensor,
+                                        a_cat: Optional[torch.Tensor], b_cat: Optional[torch.Tensor], y: torch.Tensor,
+                                        workspace: Optional[torch.Tensor], stream=None) -> None:
+    """salr_sparse_lowrank_linear with the layer's slice table as one more input."""
+    M, K = x.shape
+    N = y.shape[1]
+    R = 0 if a_cat is None else a_cat.shape[1]
+    if y.shape[0] != M or bitmap.shape[0] != N or row_offsets.numel() != N + 1 or slice_table.numel() != N * 16:
+        raise ValueError("inconsistent shapes")
+    if R and (tuple(a_cat.shape) != (K, R) or tuple(b_cat.shape) != (R, N)):
+        raise ValueError("adapter shapes")
+    ws_ptr = None if workspace is None else workspace.data_ptr()
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = lib().salr_sparse_lowrank_linear_prepared(
+        _ptr(x, _BF16_TYPES, "x"), M, K, N, _ptr(bitmap, _U32_TYPES, "bitmap"), _ptr(values, _BF16_TYPES, "values"),
+        _ptr(row_offsets, _U32_TYPES, "row_offsets"), _ptr(slice_table, _U32_TYPES, "slice_table"),
+        _ptr(a_cat, _BF16_TYPES, "a_cat"), _ptr(b_cat, _BF16_TYPES, "b_cat"), R, _ptr(y, _BF16_TYPES, "y"), ws_ptr, ws_bytes,
+        _stream(stream))
+    _check(st, "salr_sparse_lowrank_linear_prepared")
 
 
 def salr_nf4_quantize_values(values: torch.Tensor, codes: torch.Tensor, scales: torch.Tensor, stream=None) -> None:
@@ -369,7 +412,7 @@ class PreparedLinear:
     """The argument list of one salr_sparse_lowrank_linear call, marshalled once: ``run()`` is then a
     single foreign call on the stream that is current at that moment (for launch-bound loops)."""
 
-    def __init__(self, x, bitmap, values, row_offsets, a_cat, b_cat, y, workspace, two_of_four=False):
+    def __init__(self, x, bitmap, values, row_offsets, a_cat, b_cat, y, workspace, two_of_four=False, slice_table=None):
         M, K = x.shape
         N = y.shape[1]
         R = 0 if a_cat is None else a_cat.shape[1]
@@ -377,14 +420,18 @@ class PreparedLinear:
             raise ValueError("inconsistent shapes")
         if R and (tuple(a_cat.shape) != (K, R) or tuple(b_cat.shape) != (R, N)):
             raise ValueError("adapter shapes")
-        self._keep = (x, bitmap, values, row_offsets, a_cat, b_cat, y, workspace)
+        if slice_table is not None and (two_of_four or slice_table.numel() != N * 16):
+            raise ValueError("slice table")
+        self._keep = (x, bitmap, values, row_offsets, a_cat, b_cat, y, workspace, slice_table)
         ws_ptr = None if workspace is None else workspace.data_ptr()
         ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+        table = () if slice_table is None else (_ptr(slice_table, _U32_TYPES, "slice_table"),)
         self._args = (_ptr(x, _BF16_TYPES, "x"), M, K, N, _ptr(bitmap, _U32_TYPES, "bitmap"),
-                      _ptr(values, _BF16_TYPES, "values"), _ptr(row_offsets, _U32_TYPES, "row_offsets"),
+                      _ptr(values, _BF16_TYPES, "values"), _ptr(row_offsets, _U32_TYPES, "row_offsets")) + table + (
                       _ptr(a_cat, _BF16_TYPES, "a_cat"), _ptr(b_cat, _BF16_TYPES, "b_cat"), R,
                       _ptr(y, _BF16_TYPES, "y"), ws_ptr, ws_bytes)
-        self._fn = lib().salr_sparse_lowrank_linear_2of4 if two_of_four else lib().salr_sparse_lowrank_linear
+        self._fn = (lib().salr_sparse_lowrank_linear_prepared if slice_table is not None else
+                    lib().salr_sparse_lowrank_linear_2of4 if two_of_four else lib().salr_sparse_lowrank_linear)
 
     def run(self, stream_handle: Optional[int] = None) -> None:
         st = self._fn(*self._args, stream_handle)
@@ -538,6 +585,26 @@ def linear_2of4(x, bitmap, values, row_offsets, a_cat, b_cat, workspace: Optiona
     if workspace is None and need:
         workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
     salr_sparse_lowrank_linear_2of4(x, bitmap, values, row_offsets, a_cat, b_cat, y, workspace)
+    return y
+
+
+def build_slice_table(bitmap, row_offsets, K: int) -> torch.Tensor:
+    N = bitmap.shape[0]
+    table = torch.empty((N, 8, 2), dtype=torch.int32, device=bitmap.device)
+    salr_build_slice_table(bitmap, row_offsets, K, table)
+    return table
+
+
+def linear_prepared(x, bitmap, values, row_offsets, slice_table, a_cat, b_cat,
+                    workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    M, K = x.shape
+    N = bitmap.shape[0]
+    R = 0 if a_cat is None else a_cat.shape[1]
+    y = torch.empty((M, N), dtype=x.dtype, device=x.device)
+    need = salr_linear_workspace_bytes(M, K, N, R)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    salr_sparse_lowrank_linear_prepared(x, bitmap, values, row_offsets, slice_table, a_cat, b_cat, y, workspace)
     return y
 
 

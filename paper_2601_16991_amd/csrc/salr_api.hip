@@ -160,10 +160,27 @@ size_t salr_linear_workspace_bytes_min(int64_t M, int64_t K, int64_t N, int64_t 
     return salr::linear_workspace_bytes_lean(M, K, N, R);
 }
 
-salr_status_t salr_sparse_lowrank_linear(const uint16_t* x, int64_t M, int64_t K, int64_t N, const uint32_t* bitmap,
-                                         const uint16_t* values, const uint32_t* row_offsets, const uint16_t* a_cat,
-                                         const uint16_t* b_cat, int64_t R, uint16_t* y, void* workspace,
-                                         size_t workspace_bytes, void* stream) {
+size_t salr_slice_table_bytes(int64_t N, int64_t K) {
+    if (N <= 0 || K < 0 || K % 32 != 0 || N > kMaxRows || K > kMaxCols) return 0;
+    return salr::slice_table_bytes(N);
+}
+
+salr_status_t salr_build_slice_table(const uint32_t* bitmap, const uint32_t* row_offsets, int64_t N, int64_t K,
+                                     uint32_t* slice_table, size_t slice_table_bytes, void* stream) {
+    if (N < 0 || K < 0) return SALR_ERR_INVALID_ARG;
+    if (N == 0) return SALR_OK;
+    if (!row_offsets || !slice_table || (K > 0 && !bitmap)) return SALR_ERR_INVALID_ARG;
+    if (K % 32 != 0) return SALR_ERR_SHAPE;
+    if (N > kMaxRows || K > kMaxCols) return SALR_ERR_SHAPE;
+    if (slice_table_bytes < salr::slice_table_bytes(N)) return SALR_ERR_CAPACITY;
+    hipError_t e = salr::launch_build_slice_table(bitmap, row_offsets, N, K, slice_table, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SALR_OK : SALR_ERR_HIP;
+}
+
+static salr_status_t linear_entry(const uint16_t* x, int64_t M, int64_t K, int64_t N, const uint32_t* bitmap,
+                                  const uint16_t* values, const uint32_t* row_offsets, const uint32_t* slice_table,
+                                  const uint16_t* a_cat, const uint16_t* b_cat, int64_t R, uint16_t* y, void* workspace,
+                                  size_t workspace_bytes, void* stream) {
     if (M < 0 || K < 0 || N < 0 || R < 0) return SALR_ERR_INVALID_ARG;
     if (M == 0 || N == 0) return SALR_OK;
     if (!y) return SALR_ERR_INVALID_ARG;
@@ -187,8 +204,26 @@ salr_status_t salr_sparse_lowrank_linear(const uint16_t* x, int64_t M, int64_t K
     a.y = y;
     a.t = static_cast<uint16_t*>(workspace);
     a.lean = have < need;   // no room for the decoded copy: decode stage and MFMA stage in one kernel
+    a.slice_table = slice_table;
     hipError_t e = salr::launch_linear(a, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? SALR_OK : SALR_ERR_HIP;
+}
+
+salr_status_t salr_sparse_lowrank_linear(const uint16_t* x, int64_t M, int64_t K, int64_t N, const uint32_t* bitmap,
+                                         const uint16_t* values, const uint32_t* row_offsets, const uint16_t* a_cat,
+                                         const uint16_t* b_cat, int64_t R, uint16_t* y, void* workspace,
+                                         size_t workspace_bytes, void* stream) {
+    return linear_entry(x, M, K, N, bitmap, values, row_offsets, nullptr, a_cat, b_cat, R, y, workspace, workspace_bytes, stream);
+}
+
+salr_status_t salr_sparse_lowrank_linear_prepared(const uint16_t* x, int64_t M, int64_t K, int64_t N, const uint32_t* bitmap,
+                                                  const uint16_t* values, const uint32_t* row_offsets,
+                                                  const uint32_t* slice_table, const uint16_t* a_cat, const uint16_t* b_cat,
+                                                  int64_t R, uint16_t* y, void* workspace, size_t workspace_bytes,
+                                                  void* stream) {
+    if (M > 0 && N > 0 && K > 0 && !slice_table) return SALR_ERR_INVALID_ARG;
+    return linear_entry(x, M, K, N, bitmap, values, row_offsets, slice_table, a_cat, b_cat, R, y, workspace, workspace_bytes,
+                        stream);
 }
 
 salr_status_t salr_sparse_lowrank_linear_noalloc(const uint16_t* x, int64_t M, int64_t K, int64_t N, const uint32_t* bitmap,

@@ -50,7 +50,17 @@ struct LinearArgs {
     uint16_t* y;
     uint16_t* t;  // workspace (see linear_workspace_bytes)
     bool lean = false;  // large batches: no room for a decoded copy of the weight, take the fused kernel
+    const uint32_t* slice_table = nullptr;  // optional: the layer's slice table (see kSliceTableSlices)
 };
+
+// Slice table of a layer (a derived, kernel-private index; the three arrays of the format stay what is checked): for
+// row n and slice w of the small-batch kernel's 8 wave slices (chunks [C w / 8, C (w + 1) / 8) of the row's
+// C = ceil(K / 128) chunks of 128 columns) two uint32: the index in `values` of the slice's first value, and the most
+// nonzeros any one chunk of the slice holds.
+constexpr int kSliceTableSlices = 8;
+inline size_t slice_table_bytes(int64_t N) { return (size_t)N * kSliceTableSlices * 2 * sizeof(uint32_t); }
+hipError_t launch_build_slice_table(const uint32_t* bitmap, const uint32_t* row_offsets, int64_t N, int64_t K, uint32_t* table,
+                                    hipStream_t stream);
 
 // Optional events recorded around the fused kernel's launch (measurement hook of the boundary).
 struct TimingEvents {

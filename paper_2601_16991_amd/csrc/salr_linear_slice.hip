@@ -39,12 +39,15 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ uint32_t slice_popc4(const uint4& q) { return __popc(q.x) + __popc(q.y) + __popc(q.z) + __popc(q.w); }
 
 // kMaxGroups: groups of four chunks a wave's slice may have (K <= 8 waves * kMaxGroups * 512 columns)
-template <int kMaxGroups>
+// kTable: the cursor at the start of the wave's slice comes from the layer's slice table (the slices are the same
+// eight), so the waves need not exchange their counts and the workgroup starts without a barrier.
+template <int kMaxGroups, bool kTable = false>
 __global__ __launch_bounds__(kSlThreads, 1) void linear_slice_kernel(
     const uint16_t* __restrict__ x, int M, int64_t K, int64_t N, const uint32_t* __restrict__ bitmap,
     const uint16_t* __restrict__ values, const uint32_t* __restrict__ row_offsets,
     const float* __restrict__ t_partial, const uint16_t* __restrict__ b_cat, int R, int Rpad,
-    uint16_t* __restrict__ y) {
+    uint16_t* __restrict__ y, const uint32_t* __restrict__ slice_table) {
+    static_assert(kSlWaves == kSliceTableSlices, "the table holds one entry per wave slice");
     __shared__ __attribute__((aligned(16))) uint32_t slots[kSlWaves * kSlRows * kSlSlotDwords + 8];
     __shared__ __attribute__((aligned(16))) uint16_t t_lds[16 * kMaxRankPadded];  // T = X * A_cat, bf16
     __shared__ uint32_t lut_all[kSlWaves][kNibbleLutWords];  // one copy per wave: filled and used wave-synchronously
@@ -71,7 +74,9 @@ __global__ __launch_bounds__(kSlThreads, 1) void linear_slice_kernel(
     uint32_t* lut = lut_all[wave];
 
     // ---- round trip 1: row offset and the slice's bitmap, chunk 4 b + g of the slice in lane (n, g)
-    uint32_t cur = row_offsets[row_c];  // element index in `values` of the row's next value
+    uint32_t cur;  // element index in `values` of the row's next value
+    if constexpr (kTable) cur = slice_table[((int64_t)row_c * kSliceTableSlices + wave) * 2];
+    else cur = row_offsets[row_c];
     uint4 bw[kMaxGroups];
 #pragma unroll
     for (int b = 0; b < kMaxGroups; ++b) {
@@ -118,9 +123,9 @@ __global__ __launch_bounds__(kSlThreads, 1) void linear_slice_kernel(
         glen[b] = v;
         slice_total += v;
     }
-    if (g == 0) slice_count[n][wave] = slice_total;
-    __syncthreads();
-    {
+    if constexpr (!kTable) {
+        if (g == 0) slice_count[n][wave] = slice_total;
+        __syncthreads();
         const uint4 lo = *reinterpret_cast<const uint4*>(&slice_count[n][0]);
         const uint4 hi = *reinterpret_cast<const uint4*>(&slice_count[n][4]);
         const uint32_t cnt[kSlWaves] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
@@ -265,22 +270,28 @@ bool linear_slice_takes(int64_t M, int64_t K, int64_t N) {
     return (per_wave + kSlGroup - 1) / kSlGroup <= 8;
 }
 
-hipError_t launch_linear_slice(const LinearArgs& a, hipStream_t stream, const TimingEvents& ev) {
+template <int kMaxGroups>
+static void launch_slice_t(const LinearArgs& a, const float* t_partial, unsigned grid, hipStream_t stream,
+                           const TimingEvents& ev) {
     const int R = (int)a.R, Rpad = (int)adapter_rank_padded(a.R);
+    const uint32_t* no_table = nullptr;
+    if (a.slice_table != nullptr)   // prepared layer
+        SALR_LAUNCH((linear_slice_kernel<kMaxGroups, true>), dim3(grid), dim3(kSlThreads), stream, ev, a.x, (int)a.M, a.K, a.N,
+                    a.bitmap, a.values, a.row_offsets, t_partial, a.b_cat, R, Rpad, a.y, a.slice_table);
+    else
+        SALR_LAUNCH((linear_slice_kernel<kMaxGroups, false>), dim3(grid), dim3(kSlThreads), stream, ev, a.x, (int)a.M, a.K, a.N,
+                    a.bitmap, a.values, a.row_offsets, t_partial, a.b_cat, R, Rpad, a.y, no_table);
+}
+
+hipError_t launch_linear_slice(const LinearArgs& a, hipStream_t stream, const TimingEvents& ev) {
     const float* t_partial = reinterpret_cast<const float*>(a.t);
-    if (R > 0) launch_adapter_partial(a, stream);
+    if (a.R > 0) launch_adapter_partial(a, stream);
     const unsigned grid = (unsigned)((a.N + kSlRows - 1) / kSlRows);
     const int64_t per_wave = (a.K / 128 + kSlWaves - 1) / kSlWaves;
     const int groups = (int)((per_wave + kSlGroup - 1) / kSlGroup);
-    if (groups <= 1)
-        SALR_LAUNCH((linear_slice_kernel<1>), dim3(grid), dim3(kSlThreads), stream, ev, a.x, (int)a.M, a.K, a.N, a.bitmap, a.values,
-                    a.row_offsets, t_partial, a.b_cat, R, Rpad, a.y);
-    else if (groups <= 4)
-        SALR_LAUNCH((linear_slice_kernel<4>), dim3(grid), dim3(kSlThreads), stream, ev, a.x, (int)a.M, a.K, a.N, a.bitmap, a.values,
-                    a.row_offsets, t_partial, a.b_cat, R, Rpad, a.y);
-    else
-        SALR_LAUNCH((linear_slice_kernel<8>), dim3(grid), dim3(kSlThreads), stream, ev, a.x, (int)a.M, a.K, a.N, a.bitmap, a.values,
-                    a.row_offsets, t_partial, a.b_cat, R, Rpad, a.y);
+    if (groups <= 1) launch_slice_t<1>(a, t_partial, grid, stream, ev);
+    else if (groups <= 4) launch_slice_t<4>(a, t_partial, grid, stream, ev);
+    else launch_slice_t<8>(a, t_partial, grid, stream, ev);
     return hipGetLastError();
 }
 

@@ -42,12 +42,16 @@ struct StreamStage {
 // MT m-tiles of 16 rows, NW waves per workgroup, S chunks in flight per wave.
 // kOwnPrefix: every wave popcounts the bitmap words left of its slice itself (short rows), so the
 // workgroup needs no barrier before the stream starts; otherwise the waves exchange slice counts.
-template <int MT, int NW, int S, bool kVecBitmap, bool kOwnPrefix>
+// kTable: the cursors come ready-made from the layer's slice table (salr_build_slice_table: for every row and each of
+// the 8 wave slices the index of the slice's first value and the most nonzeros any chunk of it holds): one 8-byte
+// request in place of the row offset, the rest of the slice's bitmap and the words left of it, and no barrier.
+template <int MT, int NW, int S, bool kVecBitmap, bool kOwnPrefix, bool kTable = false>
 __global__ __launch_bounds__(NW * 64, (S == 2 && MT == 1) ? 4 : 1) void linear_stream_kernel(
     const uint16_t* __restrict__ x, int M, int64_t K, int64_t N, const uint32_t* __restrict__ bitmap,
     const uint16_t* __restrict__ values, const uint32_t* __restrict__ row_offsets,
     const float* __restrict__ t_partial, const uint16_t* __restrict__ b_cat, int R, int Rpad,
-    uint16_t* __restrict__ y) {
+    uint16_t* __restrict__ y, const uint32_t* __restrict__ slice_table) {
+    static_assert(!kTable || NW == kSliceTableSlices, "the table holds one entry per wave slice");
     constexpr int kThreads = NW * 64;
     constexpr int kStageDwords = NW * kStreamRows * kSlotDwords + 8;
     constexpr int kRedFloats = NW * MT * 256;
@@ -77,7 +81,15 @@ __global__ __launch_bounds__(NW * 64, (S == 2 && MT == 1) ? 4 : 1) void linear_s
     const uint32_t* brow = bitmap + row_c * wpr;
 
     // first requests of the kernel: row offset, bitmap of the first S chunks, adapter operands
-    uint32_t cur = row_offsets[row_c];  // element index in `values` of the row's next value
+    uint32_t cur;           // element index in `values` of the row's next value
+    uint32_t longest = 0;   // most nonzeros any 128-column chunk of the slice holds (per lane)
+    if constexpr (kTable) {
+        const uint2 e = *reinterpret_cast<const uint2*>(slice_table + ((int64_t)row_c * kSliceTableSlices + wave) * 2);
+        cur = e.x;
+        longest = e.y;
+    } else {
+        cur = row_offsets[row_c];
+    }
 
     auto load_bitmap_chunk = [&](int64_t c) -> uint4 {
         uint4 q = make_uint4(0, 0, 0, 0);
@@ -142,8 +154,7 @@ __global__ __launch_bounds__(NW * 64, (S == 2 && MT == 1) ? 4 : 1) void linear_s
 
     // ---- pre-pass: nonzeros of this wave's slice per row.  The first S chunks are already in
     // registers (all 4 lanes of a row hold them); the 4 lanes split the rest.
-    uint32_t longest = 0;  // most nonzeros any 128-column chunk of the slice holds (per lane)
-    {
+    if constexpr (!kTable) {
         uint32_t head = 0, tail = 0;
 #pragma unroll
         for (int i = 0; i < S; ++i) {
@@ -180,7 +191,7 @@ __global__ __launch_bounds__(NW * 64, (S == 2 && MT == 1) ? 4 : 1) void linear_s
             if (g == 0) slice_count[wave][n] = head + tail;
         }
     }
-    if constexpr (!kOwnPrefix) {
+    if constexpr (!kOwnPrefix && !kTable) {
         __syncthreads();
         for (int w = 0; w < wave; ++w) cur += slice_count[w][n];
     }
@@ -438,17 +449,21 @@ static void launch_stream_t(const LinearArgs& a, hipStream_t stream, const Timin
     // the optional events take the kernel's own begin/end timestamps (null events = plain launch)
     const unsigned grid = (unsigned)((a.N + kStreamRows - 1) / kStreamRows);
     const int64_t wpr = a.K / 32;
-    if (wpr % kChunkWords != 0)  // bitmap rows are not multiples of 16 bytes: scalar bitmap loads
+    const uint32_t* no_table = nullptr;
+    if (a.slice_table != nullptr && wpr % kChunkWords == 0)   // prepared layer: cursors from its slice table
+        SALR_LAUNCH((linear_stream_kernel<MT, NW, S, true, false, true>), dim3(grid), dim3(NW * 64), stream, ev, a.x, (int)a.M,
+                    a.K, a.N, a.bitmap, a.values, a.row_offsets, (const float*)t_partial, a.b_cat, R, Rpad, a.y, a.slice_table);
+    else if (wpr % kChunkWords != 0)  // bitmap rows are not multiples of 16 bytes: scalar bitmap loads
         SALR_LAUNCH((linear_stream_kernel<MT, NW, S, false, false>), dim3(grid), dim3(NW * 64), stream, ev, a.x, (int)a.M, a.K,
-                    a.N, a.bitmap, a.values, a.row_offsets, (const float*)t_partial, a.b_cat, R, Rpad, a.y);
+                    a.N, a.bitmap, a.values, a.row_offsets, (const float*)t_partial, a.b_cat, R, Rpad, a.y, no_table);
     else if (wpr / kChunkWords <= 32 && S != 2)  // short rows and one workgroup per CU: barrier-free start (two workgroups
                                                  // per CU hide each other's barrier, and the bitmap words left of a slice,
                                                  // which every wave would fetch again, are a third of the L2 reads)
         SALR_LAUNCH((linear_stream_kernel<MT, NW, S, true, true>), dim3(grid), dim3(NW * 64), stream, ev, a.x, (int)a.M, a.K,
-                    a.N, a.bitmap, a.values, a.row_offsets, (const float*)t_partial, a.b_cat, R, Rpad, a.y);
+                    a.N, a.bitmap, a.values, a.row_offsets, (const float*)t_partial, a.b_cat, R, Rpad, a.y, no_table);
     else
         SALR_LAUNCH((linear_stream_kernel<MT, NW, S, true, false>), dim3(grid), dim3(NW * 64), stream, ev, a.x, (int)a.M, a.K,
-                    a.N, a.bitmap, a.values, a.row_offsets, (const float*)t_partial, a.b_cat, R, Rpad, a.y);
+                    a.N, a.bitmap, a.values, a.row_offsets, (const float*)t_partial, a.b_cat, R, Rpad, a.y, no_table);
 }
 
 hipError_t launch_linear_stream(const LinearArgs& a, hipStream_t stream, const TimingEvents& ev) {

@@ -340,3 +340,28 @@ def test_qsalr_and_noalloc_validation(lib):
     assert na(fake, 4, 64, 8, fake, fake, fake, fake, fake, 300, fake, None) == salr.SALR_ERR_UNSUPPORTED
     assert na(fake, 4096, 28672, 8192, fake, fake, fake, fake, fake, 64, fake, None) == salr.SALR_ERR_CAPACITY
     assert na(fake, 0, 64, 8, fake, fake, fake, fake, fake, 4, fake, None) == salr.SALR_OK
+
+
+def test_slice_table_validation(lib):
+    import ctypes
+    import paper_2601_16991_amd as salr
+    fake = 0x1000   # never dereferenced: every call below fails validation first (or has nothing to do)
+    q = lib.salr_slice_table_bytes
+    q.restype = ctypes.c_size_t
+    assert q(4096, 4096) == 4096 * 8 * 2 * 4
+    assert q(0, 4096) == 0 and q(16, 40) == 0 and q(-1, 64) == 0
+    b = lib.salr_build_slice_table
+    assert b(fake, fake, -1, 64, fake, 1 << 20, None) == salr.SALR_ERR_INVALID_ARG
+    assert b(None, fake, 4, 64, fake, 1 << 20, None) == salr.SALR_ERR_INVALID_ARG
+    assert b(fake, None, 4, 64, fake, 1 << 20, None) == salr.SALR_ERR_INVALID_ARG
+    assert b(fake, fake, 4, 64, None, 1 << 20, None) == salr.SALR_ERR_INVALID_ARG
+    assert b(fake, fake, 4, 40, fake, 1 << 20, None) == salr.SALR_ERR_SHAPE
+    assert b(fake, fake, 4, 64, fake, 4 * 64 - 1, None) == salr.SALR_ERR_CAPACITY
+    assert b(None, None, 0, 64, None, 0, None) == salr.SALR_OK
+    p = lib.salr_sparse_lowrank_linear_prepared
+    # the table is an input of the prepared call: NULL is refused; otherwise the validation of the plain call
+    assert p(fake, 4, 64, 8, fake, fake, fake, None, fake, fake, 4, fake, fake, 1 << 20, None) == salr.SALR_ERR_INVALID_ARG
+    assert p(fake, 4, 40, 8, fake, fake, fake, fake, fake, fake, 4, fake, fake, 1 << 20, None) == salr.SALR_ERR_SHAPE
+    assert p(fake, 4, 64, 8, fake, fake, fake, fake, fake, fake, 300, fake, fake, 1 << 20, None) == salr.SALR_ERR_UNSUPPORTED
+    assert p(fake, 4, 64, 8, fake, fake, fake, fake, fake, fake, 4, fake, None, 0, None) == salr.SALR_ERR_CAPACITY
+    assert p(fake, 0, 64, 8, fake, fake, fake, None, fake, fake, 4, fake, None, 0, None) == salr.SALR_OK
