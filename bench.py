@@ -697,9 +697,9 @@ def main():
                         key = f"{cfg2.name}_p{pm}_M{m2}_no_decoded_copy"
                         extras["configs"][key] = config_row(layer2, m2, steps2, 3, lean=True)
                         log(f"{key}: {extras['configs'][key]}")
-                    if pm == 500 and ((name2 in ("llama3_8b_gate_up_proj", "llama3_8b_down_proj") and m2 <= 8) or
-                                      (name2.startswith("llama3_70b") and m2 == 1)):
-                        # where the small-batch streaming kernels run: also on the prepared layer (slice table)
+                    if pm == 500 and m2 <= 128:
+                        # up to 128 tokens the kernels can take their cursors from the layer's slice table: the same call
+                        # on the prepared layer
                         key = f"{cfg2.name}_p{pm}_M{m2}_prepared"
                         extras["configs"][key] = config_row(layer2, m2, steps2, 3, prepared=True)
                         log(f"{key}: {extras['configs'][key]}")

@@ -59,7 +59,8 @@ template <int MT, int S>
 __global__ __launch_bounds__(kRtThreads, MT <= 4 ? 4 : 2) void linear_rowtile_kernel(
     const uint16_t* __restrict__ x, int M, int64_t K, int64_t N, const uint32_t* __restrict__ bitmap,
     const uint16_t* __restrict__ values, const uint32_t* __restrict__ row_offsets, const float* __restrict__ t_partial,
-    const uint16_t* __restrict__ b_cat, int R, int Rpad, int ksplit, uint16_t* __restrict__ y, float* __restrict__ y_partial) {
+    const uint16_t* __restrict__ b_cat, int R, int Rpad, int ksplit, uint16_t* __restrict__ y, float* __restrict__ y_partial,
+    const uint32_t* __restrict__ slice_table) {
     constexpr int kRows = 16 * MT;                                    // X rows of the tile (M padded)
     constexpr int kXsElems = kRows * kRtChunkCols;                    // bf16 elements of one X tile
     __shared__ __attribute__((aligned(16))) uint16_t xs[2 * kXsElems];
@@ -154,8 +155,12 @@ __global__ __launch_bounds__(kRtThreads, MT <= 4 ? 4 : 2) void linear_rowtile_ke
     }
     __builtin_amdgcn_wave_barrier();
 
-    // ---- nonzeros of the row left of the slice: the 4 lanes of a row share the words, 8 loads in flight each
-    {
+    // ---- nonzeros of the row left of the slice: from the layer's slice table when the call has one and the slice
+    // starts where one of the table's eight does (K split 1, 2, 4 or 8 ways); else the 4 lanes of a row share the words,
+    // 8 loads in flight each
+    if (slice_table != nullptr && kSliceTableSlices % ksplit == 0) {   // the same for the whole grid
+        cur = slice_table[((int64_t)row_c * kSliceTableSlices + z * (kSliceTableSlices / ksplit)) * 2];
+    } else {
         uint32_t before = 0;
         for (int64_t c0 = 0; c0 < c_begin; c0 += 32) {
             uint4 q[8];
@@ -322,7 +327,7 @@ static void launch_rowtile_t(const LinearArgs& a, const float* t_partial, int ks
                              const TimingEvents& ev) {
     const dim3 grid((unsigned)((a.N + 16 * kRtWaves - 1) / (16 * kRtWaves)), (unsigned)ksplit);
     SALR_LAUNCH((linear_rowtile_kernel<MT, S>), grid, dim3(kRtThreads), stream, ev, a.x, (int)a.M, a.K, a.N, a.bitmap, a.values,
-                a.row_offsets, t_partial, a.b_cat, (int)a.R, (int)adapter_rank_padded(a.R), ksplit, a.y, y_partial);
+                a.row_offsets, t_partial, a.b_cat, (int)a.R, (int)adapter_rank_padded(a.R), ksplit, a.y, y_partial, a.slice_table);
 }
 
 hipError_t launch_linear_rowtile(const LinearArgs& a, hipStream_t stream, const TimingEvents& ev) {

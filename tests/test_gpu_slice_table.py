@@ -50,7 +50,10 @@ def test_slice_table_bit_exact(N, K, density):
     (130, 256, 70, (8,), 0.5),
     # long rows (the kernel for K >= 12288): one, four and eight groups of chunks per wave, dense and nearly empty rows
     (1, 28672, 40, (64,), 0.5), (16, 12288, 48, (8,), 0.5), (3, 16384, 33, (), 1.0), (8, 32768, 20, (16,), 0.05),
-    (16, 14336, 130, (32, 32), 0.7)])
+    (16, 14336, 130, (32, 32), 0.7),
+    # the row-tiled kernel takes its cursors from the table when K is split 1, 2, 4 or 8 ways (and not when 16 ways)
+    (16, 2048, 8200, (8,), 0.5), (128, 4096, 520, (32,), 0.5), (40, 14336, 256, (16,), 0.5), (100, 1024, 2048, (4,), 0.3),
+    (33, 8192, 1024, (64,), 0.5)])
 def test_prepared_linear(M, K, N, ranks, density):
     salr = _salr()
     seed = 9000 + M + K + N
@@ -89,7 +92,7 @@ def test_prepared_full_size_q_proj_sampled_against_unprepared():
     table = salr.build_slice_table(bm, rod, cfg.K)
     torch.cuda.synchronize()
     assert np.array_equal(table.cpu().numpy().view(np.uint32), oracle.slice_table(rb, ro, cfg.K))
-    for M in (1, 4, 16):
+    for M in (1, 4, 16, 64):
         x = to_dev_u16(wl.activations(cfg, M))
         y_t = salr.linear_prepared(x, bm, v, rod, table, a, b)
         y_0 = salr.linear(x, bm, v, rod, a, b)
