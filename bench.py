@@ -475,10 +475,10 @@ WORKLOADS = {"q_proj_M16": ("llama3_8b_q_proj", 16), "gate_up_M2048": ("llama3_8
              "gate_up_M2048_2of4": ("llama3_8b_gate_up_proj", 2048), "down_proj_M4096_2of4": ("llama3_8b_down_proj", 4096)}
 
 
-def decode_result(args, name, M, two_of_four=False):
+def decode_result(args, name, M, two_of_four=False, prepared=False):
     """One memory-bound layer other than the headline one as the step (the largest layer: 264 MB per call, so the
     stream reaches steady state and the launch no longer matters).  two_of_four: the layer is 2:4-masked and the call
-    is salr_sparse_lowrank_linear_2of4."""
+    is salr_sparse_lowrank_linear_2of4.  prepared: the call is salr_sparse_lowrank_linear_prepared (slice table)."""
     import numpy as np
     import paper_2601_16991_amd as salr
     import salr_workloads as wl
@@ -487,8 +487,8 @@ def decode_result(args, name, M, two_of_four=False):
     if two_of_four:
         assert salr.bitmap_is_2of4(layer.enc[0][0])
     steps, warmup = max(5, min(args.steps, 60)), max(2, min(args.warmup, 6))
-    w_ms, k_ms = time_linear(layer, M, steps, warmup, events=True, two_of_four=two_of_four)
-    nbytes = wl.algorithmic_bytes(M, cfg.K, cfg.N, layer.R, layer.nnz)
+    w_ms, k_ms = time_linear(layer, M, steps, warmup, events=True, two_of_four=two_of_four, prepared=prepared)
+    nbytes = wl.algorithmic_bytes(M, cfg.K, cfg.N, layer.R, layer.nnz) + (64 * cfg.N if prepared else 0)
     d_ms = time_dense(layer, M, steps, warmup, with_lora=False)
     k = float(np.mean(k_ms))
     log(f"{name} M={M}: wall {w_ms * 1e3:.1f} us, fused kernel {k * 1e3:.1f} us, dense GEMM {d_ms * 1e3:.1f} us")
@@ -497,7 +497,8 @@ def decode_result(args, name, M, two_of_four=False):
         "metric": METRIC, "value": round(nbytes / (w_ms * 1e-3) / 1e9, 2), "unit": "GB/s", "n_gpus": 1, "steps": steps,
         "warmup": warmup, "ms_per_step": round(w_ms, 6), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{cfg.name} W[{cfg.N},{cfg.K}] {'2:4 mask' if two_of_four else 'p=0.5'} R={layer.R} M={M}",
+        "config": {"workload": f"{cfg.name} W[{cfg.N},{cfg.K}] {'2:4 mask' if two_of_four else 'p=0.5'} R={layer.R} M={M}"
+                               + (" (prepared layer: slice table)" if prepared else ""),
                    "weight_copies_rotated": layer.ncopies,
                    "algorithmic_bytes": nbytes},
         "speedup_vs_dense_gemm": round(d_ms / w_ms, 3), "dense_gemm_ms": round(d_ms, 6),
@@ -505,6 +506,7 @@ def decode_result(args, name, M, two_of_four=False):
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
                      "frac_call": round(nbytes / (w_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                      "kernel": ("sparse-MFMA kernel of salr_sparse_lowrank_linear_2of4" if two_of_four
+                                else "fused decode+GEMM kernel of salr_sparse_lowrank_linear_prepared" if prepared
                                 else "fused decode+GEMM kernel of salr_sparse_lowrank_linear"),
                      "kernel_avg_us": round(k * 1e3, 2)},
         "cpu_baseline": None,
@@ -563,6 +565,8 @@ def main():
                          "70b ones the largest layer at decode batch sizes and the M16 / M64 / M128 ones the 8B MLP layers at "
                          "batch sizes in between, the _2of4 ones 2:4-masked layers on the sparse matrix-core path (GB/s "
                          "against the HBM peak)")
+    ap.add_argument("--prepared", action="store_true",
+                    help="with a --workload of up to 128 tokens: call salr_sparse_lowrank_linear_prepared (the layer's slice table)")
     ap.add_argument("--no-extras", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pmc-calibration", action="store_true",
@@ -593,7 +597,7 @@ def main():
         if args.workload.endswith("_2of4"):
             result = (decode_result if m <= 128 else prefill_result)(args, name, m, two_of_four=True)
         else:
-            result = decode_result(args, name, m) if m <= 128 else prefill_result(args, name, m)
+            result = decode_result(args, name, m, prepared=args.prepared) if m <= 128 else prefill_result(args, name, m)
         print(json.dumps(result), flush=True)
         return
 
