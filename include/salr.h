@@ -126,8 +126,9 @@ salr_status_t salr_decode(const uint32_t* bitmap, const uint16_t* values, const 
  * It holds T = X * A_cat and fp32 partial results of contractions that are split over K; for large
  * batches (M > 128, or M > 64 where K is no multiple of 128), where the weight is decoded once per
  * call into a dense scratch matrix that the matrix-core stage then reads, also a transposed copy of
- * A_cat and N * K bf16 elements of decoded weight.  Nothing in it outlives the call.  Returns 0 for
- * invalid sizes.
+ * A_cat and N * K bf16 elements of decoded weight; for batches of up to 128 tokens with adapters on rows of whole
+ * 128-column chunks, a slice table (64 bytes per weight row, see below) that the call builds for itself beside the
+ * first adapter product when it is not handed one.  Nothing in it outlives the call.  Returns 0 for invalid sizes.
  */
 size_t salr_linear_workspace_bytes(int64_t M, int64_t K, int64_t N, int64_t R);
 
@@ -143,7 +144,9 @@ size_t salr_linear_workspace_bytes(int64_t M, int64_t K, int64_t N, int64_t R);
  *   salr_build_slice_table   slice_table out, [N, 8, 2] uint32, at least that many bytes (else CAPACITY)
  *   salr_sparse_lowrank_linear_prepared   salr_sparse_lowrank_linear with the table as one more input; the result is
  *       the same bit for bit; paths that have no use for the table (larger batches, rows that are not whole chunks)
- *       ignore it.  A table that does not belong to the weight gives unspecified values in Y and may read `values` out
+ *       ignore it.  (The plain call builds the same table in its workspace on every call that has adapters, inside the
+ *       launch that computes X * A_cat; handing it over saves that pass over the bitmap, 2 to 10 us on the larger
+ *       layers, and serves calls without adapters too.)  A table that does not belong to the weight gives unspecified values in Y and may read `values` out
  *       of bounds: it is the caller's to keep the two together, as with row_offsets.
  * Errors: INVALID_ARG, SHAPE, CAPACITY, HIP, and those of salr_sparse_lowrank_linear.
  */

@@ -205,6 +205,11 @@ static salr_status_t linear_entry(const uint16_t* x, int64_t M, int64_t K, int64
     a.t = static_cast<uint16_t*>(workspace);
     a.lean = have < need;   // no room for the decoded copy: decode stage and MFMA stage in one kernel
     a.slice_table = slice_table;
+    if (!slice_table && have >= need && salr::builds_slice_table(M, K, N, R)) {   // none of the caller's: this call's own
+        a.slice_table = reinterpret_cast<const uint32_t*>(static_cast<char*>(workspace) +
+                                                          salr::linear_workspace_bytes_without_table(M, K, N, R));
+        a.build_table = true;
+    }
     hipError_t e = salr::launch_linear(a, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? SALR_OK : SALR_ERR_HIP;
 }

@@ -8,6 +8,7 @@
 // dense matrix (2 B/element) against bitmap + values (1/8 + 2(1-p) B/element).
 #include "salr_device.hpp"
 #include "salr_internal.hpp"
+#include "salr_linear_common.hpp"
 
 namespace salr {
 
@@ -260,46 +261,20 @@ hipError_t launch_decode(const uint32_t* bitmap, const uint16_t* values, const u
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Slice table (see salr_internal.hpp): 8 lanes per row, one per slice; a lane walks the words of its slice's chunks,
-// then an exclusive scan over the row's 8 lanes turns slice counts into value indices.  Runs once per layer.
+// Slice table (see salr_internal.hpp; the block's work is slice_table_block in salr_linear_common.hpp).  Runs once per
+// layer.
 // ---------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void slice_table_kernel(const uint32_t* __restrict__ bitmap,
                                                           const uint32_t* __restrict__ row_offsets, int64_t N, int64_t K,
                                                           uint32_t* __restrict__ table) {
-    const int64_t n = (int64_t)blockIdx.x * 32 + (threadIdx.x >> 3);
-    const int w = threadIdx.x & 7;
-    const int64_t wpr = K >> 5;
-    const int64_t chunks = (wpr + 3) / 4;
-    const int64_t c_begin = chunks * w / kSliceTableSlices, c_end = chunks * (w + 1) / kSliceTableSlices;
-    uint32_t count = 0, longest = 0;
-    if (n < N) {
-        const uint32_t* brow = bitmap + n * wpr;
-        for (int64_t c = c_begin; c < c_end; ++c) {
-            uint32_t len = 0;
-            for (int64_t q = 4 * c; q < 4 * c + 4 && q < wpr; ++q) len += __popc(brow[q]);
-            count += len;
-            longest = len > longest ? len : longest;
-        }
-    }
-    // exclusive prefix over the 8 lanes of the row (lanes of a row are consecutive)
-    uint32_t incl = count;
-#pragma unroll
-    for (int o = 1; o < kSliceTableSlices; o <<= 1) {
-        const uint32_t up = __shfl_up(incl, o, kSliceTableSlices);
-        if (w >= o) incl += up;
-    }
-    if (n < N) {
-        uint2 e;
-        e.x = row_offsets[n] + (incl - count);
-        e.y = longest;
-        *reinterpret_cast<uint2*>(table + (n * kSliceTableSlices + w) * 2) = e;
-    }
+    slice_table_block(bitmap, row_offsets, N, K, table, (int64_t)blockIdx.x, (int)threadIdx.x);
 }
 
 hipError_t launch_build_slice_table(const uint32_t* bitmap, const uint32_t* row_offsets, int64_t N, int64_t K, uint32_t* table,
                                     hipStream_t stream) {
     if (N <= 0) return hipSuccess;
-    hipLaunchKernelGGL(slice_table_kernel, dim3((unsigned)((N + 31) / 32)), dim3(256), 0, stream, bitmap, row_offsets, N, K, table);
+    hipLaunchKernelGGL(slice_table_kernel, dim3((unsigned)((N + kSliceTableRowsPerBlock - 1) / kSliceTableRowsPerBlock)),
+                       dim3(256), 0, stream, bitmap, row_offsets, N, K, table);
     return hipGetLastError();
 }
 

@@ -51,6 +51,7 @@ struct LinearArgs {
     uint16_t* t;  // workspace (see linear_workspace_bytes)
     bool lean = false;  // large batches: no room for a decoded copy of the weight, take the fused kernel
     const uint32_t* slice_table = nullptr;  // optional: the layer's slice table (see kSliceTableSlices)
+    bool build_table = false;  // slice_table points into the workspace and the adapter pre-kernel fills it in this call
 };
 
 // Slice table of a layer (a derived, kernel-private index; the three arrays of the format stay what is checked): for
@@ -179,8 +180,21 @@ inline bool uses_2of4_gemm(int64_t M, int64_t K, int64_t N) {
 }
 hipError_t launch_check_2of4(const uint32_t* bitmap, int64_t rows, int64_t cols, uint32_t* flag, hipStream_t stream);
 
+// A call without a slice table of the caller's builds one for itself where the adapter pre-kernel runs anyway (R > 0)
+// and a kernel that reads it follows: small batches on rows of whole chunks, and the row-tiled kernel when its split of
+// K starts where table slices do.  The table sits behind the rest of the workspace.
+inline bool builds_slice_table(int64_t M, int64_t K, int64_t N, int64_t R) {
+    if (R <= 0 || M <= 0 || N <= 0 || K < 128 || K % 128 != 0) return false;
+    if (uses_rowtile(M, K, N)) return kSliceTableSlices % rowtile_ksplit(M, K, N) == 0;
+    return M <= kStreamMaxM;
+}
+inline size_t linear_workspace_bytes_without_table(int64_t M, int64_t K, int64_t N, int64_t R);
 // Workspace the linear needs: the small-batch path keeps fp32 split-K partials of T; the others see above.
 inline size_t linear_workspace_bytes(int64_t M, int64_t K, int64_t N, int64_t R) {
+    const size_t b = linear_workspace_bytes_without_table(M, K, N, R);
+    return builds_slice_table(M, K, N, R) ? b + round_up_256(slice_table_bytes(N)) : b;
+}
+inline size_t linear_workspace_bytes_without_table(int64_t M, int64_t K, int64_t N, int64_t R) {
     if (M <= 0 || N <= 0) return 0;
     if (uses_rowtile(M, K, N)) return rowtile_workspace_bytes(M, K, N, R);
     if (M <= kStreamMaxM)

@@ -371,19 +371,32 @@ constexpr int kTpWaves = 4;
 constexpr int kTpThreads = kTpWaves * 64;
 constexpr int kTpBatch = 4;   // k-steps a wave has in flight
 
+// Blocks past the product's (a one-dimensional grid: product blocks first) build the layer's slice table for this call when
+// the caller brought none: the bitmap is read once here, in the shadow of the product's round trips, and the main kernel
+// starts from ready cursors (see kTable).
 __global__ __launch_bounds__(kTpThreads) void adapter_partial_kernel(const uint16_t* __restrict__ x, int M, int64_t K,
                                                                      const uint16_t* __restrict__ a_cat, int R, int Rpad,
-                                                                     int slices, float* __restrict__ t_partial) {
+                                                                     int slices, float* __restrict__ t_partial,
+                                                                     int product_blocks, const uint32_t* __restrict__ bitmap,
+                                                                     const uint32_t* __restrict__ row_offsets, int64_t N,
+                                                                     uint32_t* __restrict__ table_out) {
     __shared__ float red[kTpWaves][4][4][64];
+    static_assert(kTpThreads == 256, "slice_table_block is written for 256 threads");
+    if ((int)blockIdx.x >= product_blocks) {   // the same for the whole workgroup
+        slice_table_block(bitmap, row_offsets, N, K, table_out, (int64_t)blockIdx.x - product_blocks, (int)threadIdx.x);
+        return;
+    }
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int i16 = lane & 15, g = lane >> 4;
-    const int b = blockIdx.x, rt = blockIdx.y;
+    const int rank_tiles = Rpad >> 4;
+    const int b = (int)blockIdx.x % slices, rt = ((int)blockIdx.x / slices) % rank_tiles;
+    const int row_block = (int)blockIdx.x / (slices * rank_tiles);
     const int64_t units = K >> 5;  // k-steps of 32 columns
     const int64_t u_begin = units * b / slices, u_end = units * (b + 1) / slices;
     const int r = 16 * rt + i16;
     const int r_c = r < R ? r : R - 1;  // padded columns read a valid column and are zeroed at the store
-    const int m_base = 64 * blockIdx.z;  // 64 rows of X per workgroup
+    const int m_base = 64 * row_block;  // 64 rows of X per workgroup
     const int mtiles = ((M - m_base < 64 ? M - m_base : 64) + 15) >> 4;
     f32x4 acc[4];
 #pragma unroll
@@ -437,8 +450,11 @@ __global__ __launch_bounds__(kTpThreads) void adapter_partial_kernel(const uint1
 
 void launch_adapter_partial(const LinearArgs& a, hipStream_t stream) {
     const int R = (int)a.R, Rpad = (int)adapter_rank_padded(a.R);
-    hipLaunchKernelGGL(adapter_partial_kernel, dim3(kStreamTSlices, Rpad / 16, (unsigned)((a.M + 63) / 64)), dim3(kTpThreads), 0,
-                       stream, a.x, (int)a.M, a.K, a.a_cat, R, Rpad, kStreamTSlices, reinterpret_cast<float*>(a.t));
+    const int product_blocks = kStreamTSlices * (Rpad / 16) * (int)((a.M + 63) / 64);
+    const int table_blocks = a.build_table ? (int)((a.N + kSliceTableRowsPerBlock - 1) / kSliceTableRowsPerBlock) : 0;
+    hipLaunchKernelGGL(adapter_partial_kernel, dim3((unsigned)(product_blocks + table_blocks)), dim3(kTpThreads), 0, stream, a.x,
+                       (int)a.M, a.K, a.a_cat, R, Rpad, kStreamTSlices, reinterpret_cast<float*>(a.t), product_blocks, a.bitmap,
+                       a.row_offsets, a.N, const_cast<uint32_t*>(a.build_table ? a.slice_table : nullptr));
 }
 
 template <int MT, int NW, int S>

@@ -93,17 +93,28 @@ def _rowtile_ksplit(M, K, N):
     return s
 
 
+def _own_table(M, K, N, R):
+    """A call with adapters whose kernel starts from cursors keeps a slice table of its own (64 bytes per weight row)
+    behind the rest: rows of whole chunks, up to 64 tokens, or the row-tiled kernel with K split 1, 2, 4 or 8 ways."""
+    if R <= 0 or K < 128 or K % 128:
+        return 0
+    if _rowtile(M, K, N):
+        return _r256(64 * N) if 8 % _rowtile_ksplit(M, K, N) == 0 else 0
+    return _r256(64 * N) if M <= 64 else 0
+
+
 def _expected_workspace(M, K, N, R):
     """The documented layout, restated.  Row-tiled path: sixteen fp32 split-K partials of T, then fp32 split-K
     partials of Y when K is split.  Else M <= 64: sixteen fp32 split-K partials of T.  Larger M: T [M, Rpad] bf16,
     transposed padded A_cat [Rpad, K] bf16, fp32 split-K partials of T; for K % 64 == 0 also the decoded weight [N, K]
-    bf16 and, when the output has few tiles, fp32 split-K partials of Y.  Each part rounded to 256 B."""
+    bf16 and, when the output has few tiles, fp32 split-K partials of Y.  Each part rounded to 256 B.  Last, the call's
+    own slice table where it keeps one."""
     rp = (R + 31) // 32 * 32
     if _rowtile(M, K, N):
         ks = _rowtile_ksplit(M, K, N)
-        return (_r256(16 * M * rp * 4) if R else 0) + (_r256(ks * M * N * 4) if ks > 1 else 0)
+        return (_r256(16 * M * rp * 4) if R else 0) + (_r256(ks * M * N * 4) if ks > 1 else 0) + _own_table(M, K, N, R)
     if M <= 64:
-        return _r256(16 * M * rp * 4) if R else 0
+        return (_r256(16 * M * rp * 4) if R else 0) + _own_table(M, K, N, R)
     b = 0
     if R:
         b += _r256(M * rp * 2) + _r256(K * rp * 2)
@@ -121,14 +132,15 @@ def _expected_workspace(M, K, N, R):
 def test_workspace_bytes(lib):
     assert lib.salr_linear_workspace_bytes(16, 4096, 4096, 0) == 0
     assert lib.salr_linear_workspace_bytes(0, 4096, 4096, 32) == 0
-    assert lib.salr_linear_workspace_bytes(16, 4096, 4096, 32) == 16 * 16 * 32 * 4
-    assert lib.salr_linear_workspace_bytes(1, 4096, 4096, 64) == 16 * 64 * 4
+    assert lib.salr_linear_workspace_bytes(16, 4096, 4096, 32) == 16 * 16 * 32 * 4 + 64 * 4096   # T partials + slice table
+    assert lib.salr_linear_workspace_bytes(1, 4096, 4096, 64) == 16 * 64 * 4 + 64 * 4096
+    assert lib.salr_linear_workspace_bytes(16, 4000, 4096, 32) == 16 * 16 * 32 * 4               # ragged rows: no table
     assert lib.salr_linear_workspace_bytes(32, 4096, 4096, 0) == 0
     assert lib.salr_linear_workspace_bytes(128, 4096, 28672, 0) == 0           # 224 row tiles: K is not split
     assert lib.salr_linear_workspace_bytes(64, 4096, 28672, 0) == 2 * 64 * 28672 * 4   # up to 64 tokens: 448 workgroups wanted
     assert lib.salr_linear_workspace_bytes(64, 4096, 20480, 0) == 4 * 64 * 20480 * 4   # 160 row tiles, up to 64 tokens: 448 workgroups wanted
     assert lib.salr_linear_workspace_bytes(64, 4096, 4096, 0) == 8 * 64 * 4096 * 4     # 32 row tiles: K split 8 ways (4 chunks each)
-    assert lib.salr_linear_workspace_bytes(24, 4096, 8192, 16) == 16 * 24 * 32 * 4 + 8 * 24 * 8192 * 4   # 64 row tiles: K split 8 ways
+    assert lib.salr_linear_workspace_bytes(24, 4096, 8192, 16) == 16 * 24 * 32 * 4 + 8 * 24 * 8192 * 4 + 64 * 8192   # 64 row tiles: K split 8 ways
     assert lib.salr_linear_workspace_bytes(128, 4000, 4096, 0) == 0            # K % 64 != 0: no dense scratch
     assert lib.salr_linear_workspace_bytes(16, 4096, 4096, 1000) == 0          # rank not supported
     assert lib.salr_linear_workspace_bytes(2048, 4096, 14336, 0) == 14336 * 4096 * 2
