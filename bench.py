@@ -443,24 +443,49 @@ def time_qsalr(cfg, Ms, steps):
         torch.cuda.synchronize()
         ms = (time.perf_counter() - t0) * 1e3 / steps
         res[name] = {"ms": round(ms, 4), "GB/s": round(nbytes / ms / 1e6, 1)}
+    # the layer: encoded copies at different addresses are rotated so that no call finds its weight in a cache
+    ncopies = int(min(64, max(2, -(-ROTATE_BYTES // fmt_bytes))))
+    copies = []
+    for _ in range(ncopies):
+        c = salr.codes_alloc(nnz, dev)
+        c.copy_(codes)
+        copies.append((bitmap.clone(), c, scales.clone(), offsets.clone()))
+    res["weight_copies_rotated"] = ncopies
+    stream = torch.cuda.current_stream().cuda_stream or None
     for M in Ms:
         x = torch.from_numpy(wl.activations(cfg, M).view(np.int16)).to(dev)
         y = torch.empty((M, cfg.N), dtype=torch.int16, device=dev)
-        ws = torch.empty(max(salr.salr_qsalr_linear_workspace_bytes(M, cfg.K, cfg.N, layer.R, nnz), 256), dtype=torch.uint8, device=dev)
-
-        def fn():
-            salr.salr_qsalr_linear(x, bitmap, codes, scales, offsets, nnz, layer.a_cat, layer.b_cat, y, ws)
-        for _ in range(3):
-            fn()
+        ws_bytes = salr.salr_qsalr_linear_workspace_bytes(M, cfg.K, cfg.N, layer.R, nnz)
+        ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
+        calls = [salr.PreparedQsalrLinear(x, b, c, sc, o, nnz, layer.a_cat, layer.b_cat, y, ws) for (b, c, sc, o) in copies]
+        n_steps = steps if M > 64 else 10 * steps
+        for i in range(5):
+            calls[i % ncopies].run(stream)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for _ in range(steps):
-            fn()
+        for i in range(n_steps):
+            calls[i % ncopies].run(stream)
         torch.cuda.synchronize()
-        ms = (time.perf_counter() - t0) * 1e3 / steps
+        ms = (time.perf_counter() - t0) * 1e3 / n_steps
+        ev = HipEvents(n_steps)
+        for i in range(n_steps):
+            e0, e1 = ev.pairs[i]
+            salr.salr_set_kernel_timing_events(e0, e1)
+            calls[i % ncopies].run(stream)
+        salr.salr_set_kernel_timing_events(None, None)
+        torch.cuda.synchronize()
+        k_us = float(np.mean(ev.elapsed_ms())) * 1e3
+        ev.close()
+        dense_ms = time_dense(layer, M, max(n_steps // 2, 10), 5, with_lora=False)
         nbytes = fmt_bytes + 2 * M * cfg.K + 2 * cfg.K * layer.R + 2 * layer.R * cfg.N + 2 * M * cfg.N
-        res[f"linear_M{M}"] = {"ms": round(ms, 4), "GB/s": round(nbytes / ms / 1e6, 1),
-                               "TFLOP/s": round(wl.algorithmic_flops(M, cfg.K, cfg.N, layer.R) / ms / 1e9, 1)}
+        res[f"linear_M{M}"] = {"ms": round(ms, 4), "kernel_avg_us": round(k_us, 2), "GB/s": round(nbytes / ms / 1e6, 1),
+                               "frac_call": round(nbytes / ms / 1e6 / HBM_PEAK_GBS, 4),
+                               "frac_kernel": round(nbytes / k_us / 1e3 / HBM_PEAK_GBS, 4),
+                               "TFLOP/s": round(wl.algorithmic_flops(M, cfg.K, cfg.N, layer.R) / ms / 1e9, 1),
+                               "dense_gemm_ms": round(dense_ms, 4), "speedup_vs_dense_gemm": round(dense_ms / ms, 3),
+                               "workspace_bytes": int(ws_bytes),
+                               "path": "one kernel on the 4-bit codes" if (M <= 64 and cfg.K % 128 == 0) else "dequantise, then the layer"}
+        del calls, ws
     return res
 
 
@@ -469,6 +494,9 @@ WORKLOADS = {"q_proj_M16": ("llama3_8b_q_proj", 16), "gate_up_M2048": ("llama3_8
              "gate_up_70b_M16": ("llama3_70b_gate_up_proj", 16), "gate_up_M16": ("llama3_8b_gate_up_proj", 16),
              "gate_up_M64": ("llama3_8b_gate_up_proj", 64), "down_proj_M128": ("llama3_8b_down_proj", 128),
              "down_proj_M8": ("llama3_8b_down_proj", 8), "down_proj_70b_M1": ("llama3_70b_down_proj", 1),
+             # QSALR (20 % sparsity, NF4 values) through salr_qsalr_linear: the whole sweep of batch sizes of one layer
+             "qsalr_q_proj": ("llama3_8b_q_proj", 0), "qsalr_gate_up": ("llama3_8b_gate_up_proj", 0),
+             "qsalr_70b_gate_up": ("llama3_70b_gate_up_proj", 0),
              # 2:4-masked layers through salr_sparse_lowrank_linear_2of4
              "q_proj_M16_2of4": ("llama3_8b_q_proj", 16), "gate_up_M16_2of4": ("llama3_8b_gate_up_proj", 16),
              "gate_up_70b_M1_2of4": ("llama3_70b_gate_up_proj", 1), "gate_up_70b_M16_2of4": ("llama3_70b_gate_up_proj", 16),
@@ -594,6 +622,10 @@ def main():
         del src, dst
     if args.workload != "q_proj_M16":
         name, m = WORKLOADS[args.workload]
+        if args.workload.startswith("qsalr_"):
+            res = time_qsalr(wl.CONFIGS[name], (1, 16, 32, 64, 2048), 20)
+            print(json.dumps({"workload": args.workload, "qsalr": res}), flush=True)
+            return
         if args.workload.endswith("_2of4"):
             result = (decode_result if m <= 128 else prefill_result)(args, name, m, two_of_four=True)
         else:
@@ -669,7 +701,7 @@ def main():
         log("prepare:", extras["prepare_" + cfg.name])
         extras["backward_" + cfg.name + "_M2048"] = time_backward(layer, 2048, 10)
         log("backward:", extras["backward_" + cfg.name + "_M2048"])
-        extras["qsalr_" + cfg.name] = time_qsalr(cfg, (16, 2048), 20)
+        extras["qsalr_" + cfg.name] = time_qsalr(cfg, (1, 16, 64, 2048), 20)
         log("qsalr:", extras["qsalr_" + cfg.name])
         for m in cfg.Ms:
             extras["configs"][f"{cfg.name}_p{permille}_M{m}"] = config_row(layer, m, min(args.steps, 100), min(args.warmup, 10))

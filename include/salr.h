@@ -144,10 +144,11 @@ size_t salr_linear_workspace_bytes(int64_t M, int64_t K, int64_t N, int64_t R);
  *   salr_build_slice_table   slice_table out, [N, 8, 2] uint32, at least that many bytes (else CAPACITY)
  *   salr_sparse_lowrank_linear_prepared   salr_sparse_lowrank_linear with the table as one more input; the result is
  *       the same bit for bit; paths that have no use for the table (larger batches, rows that are not whole chunks)
- *       ignore it.  (The plain call builds the same table in its workspace on every call that has adapters, inside the
- *       launch that computes X * A_cat; handing it over saves that pass over the bitmap, 2 to 10 us on the larger
- *       layers, and serves calls without adapters too.)  A table that does not belong to the weight gives unspecified values in Y and may read `values` out
- *       of bounds: it is the caller's to keep the two together, as with row_offsets.
+ *       ignore it.  (The plain call builds the same table in its workspace on calls with adapters, inside the launch
+ *       that computes X * A_cat, except for up to 16 tokens on rows of 12288 columns and more; handing it over saves
+ *       that pass over the bitmap, 2 to 10 us on the larger layers, and serves calls without adapters and those long
+ *       rows too.)  A table that does not belong to the weight gives unspecified values in Y and may read `values`
+ *       out of bounds: it is the caller's to keep the two together, as with row_offsets.
  * Errors: INVALID_ARG, SHAPE, CAPACITY, HIP, and those of salr_sparse_lowrank_linear.
  */
 size_t salr_slice_table_bytes(int64_t N, int64_t K);
@@ -249,9 +250,17 @@ salr_status_t salr_sparse_lowrank_linear_noalloc(const uint16_t* x, int64_t M, i
  * elements.  Errors: INVALID_ARG (null pointer with count > 0, negative count), SHAPE (count >= 2^32), HIP.
  *
  * salr_qsalr_linear is salr_sparse_lowrank_linear on such a weight: Y = X * W-hat'^T + (X * A_cat) * B_cat with
- * W-hat' = decode(bitmap, dequantised values).  The values are dequantised once per call into the first
- * qsalr part of the workspace (2 * nnz bytes, rounded up), then the layer runs as usual on them; arguments, rounding
- * and errors otherwise as there.  nnz = row_offsets[N], which the caller knows from encoding (host value).
+ * W-hat' = decode(bitmap, dequantised values); arguments, rounding and errors otherwise as there.  nnz =
+ * row_offsets[N], which the caller knows from encoding (host value).
+ *   - Up to 64 tokens on rows of whole 128-column chunks (K % 128 == 0, nnz > 0) one kernel reads bitmap, codes and
+ *     scales and dequantises inside its decode stage: the weight crosses the memory system at 1 + 4.25 (1 - p) bits
+ *     per element and no bf16 copy of the values exists.  Workspace: the layer's partial sums of X * A_cat and a
+ *     slice table built per call (64 bytes per weight row).  As an INPUT to this call `codes` must be readable up to
+ *     the next multiple of 16 bytes (vector reads; the padding is never used).
+ *   - Otherwise the values are dequantised once per call into the first part of the workspace (2 * nnz bytes,
+ *     rounded up), then the layer runs as usual on them.
+ * Both compute the same products; where the plain layer would take its small-batch streaming kernels Y is the same
+ * bit for bit (finite scales).
  * Workspace: salr_qsalr_linear_workspace_bytes(M, K, N, R, nnz) bytes, 256-byte aligned.
  */
 salr_status_t salr_nf4_quantize_values(const uint16_t* values, int64_t count, uint8_t* codes, uint16_t* scales,

@@ -283,9 +283,16 @@ def salr_qsalr_linear(x: torch.Tensor, bitmap: torch.Tensor, codes: torch.Tensor
     _check(st, "salr_qsalr_linear")
 
 
+def codes_alloc(count: int, device) -> torch.Tensor:
+    """A buffer for the 4-bit codes of `count` values whose storage is whole 16-byte vectors (salr_qsalr_linear reads
+    the codes with vector loads)."""
+    nbytes = (count + 1) // 2
+    return torch.empty(max((nbytes + 15) // 16 * 16, 16), dtype=torch.uint8, device=device)[:nbytes]
+
+
 def nf4_quantize(values: torch.Tensor) -> Tuple[torch.Tensor, torch.Tensor]:
     n = values.numel()
-    codes = torch.empty(max((n + 1) // 2, 1), dtype=torch.uint8, device=values.device)[:(n + 1) // 2]
+    codes = codes_alloc(n, values.device)
     scales = torch.empty(max((n + 63) // 64, 1), dtype=torch.int16, device=values.device)[:(n + 63) // 64]
     salr_nf4_quantize_values(values, codes, scales)
     return codes, scales
@@ -437,6 +444,33 @@ class PreparedLinear:
         st = self._fn(*self._args, stream_handle)
         if st != SALR_OK:
             raise SalrError(st, "salr_sparse_lowrank_linear")
+
+
+class PreparedQsalrLinear:
+    """The argument list of one salr_qsalr_linear call, marshalled once (see PreparedLinear)."""
+
+    def __init__(self, x, bitmap, codes, scales, row_offsets, nnz, a_cat, b_cat, y, workspace):
+        M, K = x.shape
+        N = y.shape[1]
+        R = 0 if a_cat is None else a_cat.shape[1]
+        if y.shape[0] != M or bitmap.shape[0] != N or row_offsets.numel() != N + 1:
+            raise ValueError("inconsistent shapes")
+        if R and (tuple(a_cat.shape) != (K, R) or tuple(b_cat.shape) != (R, N)):
+            raise ValueError("adapter shapes")
+        if codes.numel() != (nnz + 1) // 2 or scales.numel() != (nnz + 63) // 64:
+            raise ValueError("codes / scales do not match nnz")
+        self._keep = (x, bitmap, codes, scales, row_offsets, a_cat, b_cat, y, workspace)
+        ws_ptr = None if workspace is None else workspace.data_ptr()
+        ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+        self._args = (_ptr(x, _BF16_TYPES, "x"), M, K, N, _ptr(bitmap, _U32_TYPES, "bitmap"),
+                      _ptr(codes, (torch.uint8,), "codes"), _ptr(scales, _BF16_TYPES, "scales"),
+                      _ptr(row_offsets, _U32_TYPES, "row_offsets"), nnz, _ptr(a_cat, _BF16_TYPES, "a_cat"),
+                      _ptr(b_cat, _BF16_TYPES, "b_cat"), R, _ptr(y, _BF16_TYPES, "y"), ws_ptr, ws_bytes)
+
+    def run(self, stream_handle: Optional[int] = None) -> None:
+        st = lib().salr_qsalr_linear(*self._args, stream_handle)
+        if st != SALR_OK:
+            raise SalrError(st, "salr_qsalr_linear")
 
 
 def salr_set_kernel_timing_events(start_event: Optional[int], stop_event: Optional[int]) -> None:

@@ -268,6 +268,7 @@ salr_status_t salr_nf4_dequantize_values(const uint8_t* codes, const uint16_t* s
 
 size_t salr_qsalr_linear_workspace_bytes(int64_t M, int64_t K, int64_t N, int64_t R, int64_t nnz) {
     if (M <= 0 || K < 0 || N <= 0 || R < 0 || R > kMaxRank || K % 32 != 0 || nnz < 0) return 0;
+    if (salr::linear_nf4_takes(M, K, N, nnz)) return salr::linear_nf4_workspace_bytes(M, N, R);   // no bf16 copy of the values
     return salr::qsalr_values_bytes(nnz) + salr::linear_workspace_bytes(M, K, N, R);
 }
 
@@ -281,6 +282,22 @@ salr_status_t salr_qsalr_linear(const uint16_t* x, int64_t M, int64_t K, int64_t
     if (K % 32 != 0) return SALR_ERR_SHAPE;
     if (nnz > (int64_t)0xFFFFFFFFLL || (K > 0 && nnz > N * K)) return SALR_ERR_SHAPE;
     if (R > kMaxRank) return SALR_ERR_UNSUPPORTED;
+    if (salr::linear_nf4_takes(M, K, N, nnz)) {   // small batches: the kernel that reads the codes itself
+        if (!y || !x || !bitmap || !row_offsets) return SALR_ERR_INVALID_ARG;
+        if (R > 0 && (!a_cat || !b_cat)) return SALR_ERR_INVALID_ARG;
+        if (N > kMaxRows || K > kMaxCols) return SALR_ERR_SHAPE;
+        const size_t fused = salr::linear_nf4_workspace_bytes(M, N, R);
+        if (!workspace || workspace_bytes < fused) return SALR_ERR_CAPACITY;
+        salr::LinearArgs a;
+        a.x = x; a.M = M; a.K = K; a.N = N;
+        a.bitmap = bitmap; a.values = nullptr; a.row_offsets = row_offsets;
+        a.a_cat = a_cat; a.b_cat = b_cat; a.R = R;
+        a.y = y;
+        a.t = static_cast<uint16_t*>(workspace);
+        a.slice_table = reinterpret_cast<const uint32_t*>(static_cast<char*>(workspace) + salr::linear_nf4_table_offset(M, R));
+        hipError_t e = salr::launch_linear_nf4(a, codes, scales, nnz, static_cast<hipStream_t>(stream), salr::g_timing_events);
+        return e == hipSuccess ? SALR_OK : SALR_ERR_HIP;
+    }
     const size_t vbytes = salr::qsalr_values_bytes(nnz);
     const size_t need = vbytes + (K > 0 ? salr::linear_workspace_bytes(M, K, N, R) : 0);
     if (need > 0 && (!workspace || workspace_bytes < need)) return SALR_ERR_CAPACITY;

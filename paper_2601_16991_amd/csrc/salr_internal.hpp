@@ -180,12 +180,17 @@ inline bool uses_2of4_gemm(int64_t M, int64_t K, int64_t N) {
 }
 hipError_t launch_check_2of4(const uint32_t* bitmap, int64_t rows, int64_t cols, uint32_t* flag, hipStream_t stream);
 
+// decode-sized batches (M <= 16, K % 128 == 0, 12288 <= K <= 32768): the streaming kernel that reads every bitmap word once
+bool linear_slice_takes(int64_t M, int64_t K, int64_t N);
 // A call without a slice table of the caller's builds one for itself where the adapter pre-kernel runs anyway (R > 0)
-// and a kernel that reads it follows: small batches on rows of whole chunks, and the row-tiled kernel when its split of
-// K starts where table slices do.  The table sits behind the rest of the workspace.
+// and a kernel that gains more from it than the build costs follows: the small-batch streaming kernel on rows of whole
+// chunks, and the row-tiled kernel when its split of K starts where table slices do.  (The long-row kernel reads a
+// caller's table but gains less from it than reading the bitmap a second time costs: 70B down_proj M = 1, kernel +
+// pre-kernel 87.3 us without, 89.3 us with.)  The table sits behind the rest of the workspace.
 inline bool builds_slice_table(int64_t M, int64_t K, int64_t N, int64_t R) {
     if (R <= 0 || M <= 0 || N <= 0 || K < 128 || K % 128 != 0) return false;
     if (uses_rowtile(M, K, N)) return kSliceTableSlices % rowtile_ksplit(M, K, N) == 0;
+    if (linear_slice_takes(M, K, N)) return false;
     return M <= kStreamMaxM;
 }
 inline size_t linear_workspace_bytes_without_table(int64_t M, int64_t K, int64_t N, int64_t R);
@@ -228,13 +233,19 @@ hipError_t launch_nf4_quantize(const uint16_t* values, int64_t count, uint8_t* c
 hipError_t launch_nf4_dequantize(const uint8_t* codes, const uint16_t* scales, int64_t count, uint16_t* out, hipStream_t stream);
 // bytes of the dequantised packed values at the start of the QSALR layer's workspace (16-byte vectors, 256-byte aligned)
 inline size_t qsalr_values_bytes(int64_t nnz) { return round_up_256((size_t)((nnz + 7) / 8 * 8) * sizeof(uint16_t)); }
+// QSALR at small batches (M <= 64, K a multiple of 128, nnz > 0): the streaming kernel that reads the 4-bit codes itself.
+// Its workspace: the split-K partials of T (with adapters), then the call's slice table; args.t and args.slice_table
+// point at the two, args.values is not used.
+bool linear_nf4_takes(int64_t M, int64_t K, int64_t N, int64_t nnz);
+size_t linear_nf4_table_offset(int64_t M, int64_t R);
+size_t linear_nf4_workspace_bytes(int64_t M, int64_t N, int64_t R);
+hipError_t launch_linear_nf4(const LinearArgs& args, const uint8_t* codes, const uint16_t* scales, int64_t nnz,
+                             hipStream_t stream, const TimingEvents& ev);
 
 hipError_t launch_linear(const LinearArgs& args, hipStream_t stream);
 // count bf16 zeros (+0.0) at out
 hipError_t launch_fill_zero(uint16_t* out, int64_t count, hipStream_t stream);
 hipError_t launch_linear_stream(const LinearArgs& args, hipStream_t stream, const TimingEvents& ev);
-// decode-sized batches (M <= 16, K % 128 == 0, K <= 32768): the streaming kernel that reads every bitmap word once
-bool linear_slice_takes(int64_t M, int64_t K, int64_t N);
 hipError_t launch_linear_slice(const LinearArgs& args, hipStream_t stream, const TimingEvents& ev);
 hipError_t launch_linear_twostage(const LinearArgs& args, hipStream_t stream, const TimingEvents& ev);
 // the same shapes without a decoded copy of the weight: decode stage and MFMA stage in one kernel (K % 64 == 0)

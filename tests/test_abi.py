@@ -95,11 +95,13 @@ def _rowtile_ksplit(M, K, N):
 
 def _own_table(M, K, N, R):
     """A call with adapters whose kernel starts from cursors keeps a slice table of its own (64 bytes per weight row)
-    behind the rest: rows of whole chunks, up to 64 tokens, or the row-tiled kernel with K split 1, 2, 4 or 8 ways."""
+    behind the rest: rows of whole chunks, up to 64 tokens (not the long-row kernel's shapes), or the row-tiled kernel with K split 1, 2, 4 or 8 ways."""
     if R <= 0 or K < 128 or K % 128:
         return 0
     if _rowtile(M, K, N):
         return _r256(64 * N) if 8 % _rowtile_ksplit(M, K, N) == 0 else 0
+    if M <= 16 and 12288 <= K <= 32768:   # the long-row kernel: reads a caller's table, builds none
+        return 0
     return _r256(64 * N) if M <= 64 else 0
 
 
@@ -150,7 +152,7 @@ def test_workspace_bytes(lib):
                          (20, 1024, 8192, 8), (20, 1024, 8190, 8), (70, 4000, 4096, 8), (9, 1024, 8192, 8), (8, 1024, 8192, 8),
                          (16, 4096, 28672, 32), (40, 1152, 28672, 32), (100, 4096, 28672, 32),
                          (256, 4096, 4096, 0), (256, 4096, 4096, 32), (512, 14336, 4096, 64), (2048, 4096, 14336, 32),
-                         (4096, 14336, 4096, 64), (1024, 96, 8, 32), (1024, 64, 8, 0), (300, 1024, 262, 5)]:
+                         (4096, 14336, 4096, 64), (8, 14336, 4096, 64), (1, 28672, 8192, 64), (16, 12160, 512, 8), (1024, 96, 8, 32), (1024, 64, 8, 0), (300, 1024, 262, 5)]:
         assert lib.salr_linear_workspace_bytes(M, K, N, R) == _expected_workspace(M, K, N, R), (M, K, N, R)
 
 
@@ -328,9 +330,17 @@ def test_qsalr_and_noalloc_validation(lib):
     q = lib.salr_qsalr_linear_workspace_bytes
     q.restype = ctypes.c_size_t
     g = lib.salr_linear_workspace_bytes
-    # the dequantised values (2 bytes each, whole 16-byte vectors, 256-byte aligned) in front of the layer's own workspace
-    assert q(16, 4096, 4096, 32, 1000) == _r256(2 * 1000) + g(16, 4096, 4096, 32)
-    assert q(16, 4096, 4096, 32, 1001) == _r256(2 * 1008) + g(16, 4096, 4096, 32)
+    # larger batches: the dequantised values (2 bytes each, whole 16-byte vectors, 256-byte aligned) in front of the
+    # layer's own workspace
+    assert q(65, 4096, 4096, 32, 1000) == _r256(2 * 1000) + g(65, 4096, 4096, 32)
+    assert q(65, 4096, 4096, 32, 1001) == _r256(2 * 1008) + g(65, 4096, 4096, 32)
+    assert q(16, 4128, 4096, 32, 1000) == _r256(2 * 1000) + g(16, 4128, 4096, 32)    # rows that are not whole chunks
+    # up to 64 tokens on rows of whole 128-column chunks: no bf16 copy of the values, only the sixteen fp32 partials
+    # of T and the call's slice table (64 bytes per weight row)
+    assert q(16, 4096, 4096, 32, 1000) == 16 * 16 * 32 * 4 + 64 * 4096
+    assert q(64, 4096, 14336, 0, 10 ** 7) == 64 * 14336
+    assert q(1, 128, 3, 5, 7) == _r256(16 * 1 * 32 * 4) + _r256(64 * 3)
+    assert q(16, 4096, 4096, 32, 0) == g(16, 4096, 4096, 32)       # no stored values: the plain layer
     assert q(16, 4100, 4096, 32, 1000) == 0 and q(16, 4096, 4096, 32, -1) == 0
 
     def call(M=4, K=64, N=8, R=4, nnz=100, x=fake, codes=fake, scales=fake, y=fake, ws=fake, ws_bytes=1 << 20):
@@ -345,6 +355,15 @@ def test_qsalr_and_noalloc_validation(lib):
     assert call(ws=None) == salr.SALR_ERR_CAPACITY
     assert call(ws_bytes=128) == salr.SALR_ERR_CAPACITY
     assert call(M=0) == salr.SALR_OK
+    # the small-batch kernel's shapes (K a multiple of 128, up to 64 tokens) validate the same way
+    assert call(K=128, nnz=-1) == salr.SALR_ERR_INVALID_ARG
+    assert call(K=128, codes=None) == salr.SALR_ERR_INVALID_ARG
+    assert call(K=128, x=None) == salr.SALR_ERR_INVALID_ARG
+    assert call(K=128, y=None) == salr.SALR_ERR_INVALID_ARG
+    assert call(K=128, R=300) == salr.SALR_ERR_UNSUPPORTED
+    assert call(K=128, nnz=4 * 128 * 8) == salr.SALR_ERR_SHAPE
+    assert call(K=128, ws=None) == salr.SALR_ERR_CAPACITY
+    assert call(K=128, ws_bytes=256) == salr.SALR_ERR_CAPACITY
     # the entry point without a workspace: same validation, and a size limit of its own
     na = lib.salr_sparse_lowrank_linear_noalloc
     assert na(fake, -1, 64, 8, fake, fake, fake, fake, fake, 4, fake, None) == salr.SALR_ERR_INVALID_ARG
