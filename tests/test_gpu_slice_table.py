@@ -53,7 +53,11 @@ def test_slice_table_bit_exact(N, K, density):
     (16, 14336, 130, (32, 32), 0.7),
     # the row-tiled kernel takes its cursors from the table when K is split 1, 2, 4 or 8 ways (and not when 16 ways)
     (16, 2048, 8200, (8,), 0.5), (128, 4096, 520, (32,), 0.5), (40, 14336, 256, (16,), 0.5), (100, 1024, 2048, (4,), 0.3),
-    (33, 8192, 1024, (64,), 0.5)])
+    (33, 8192, 1024, (64,), 0.5),
+    # more row groups than CUs on rows of 4096 / 8192 columns, up to 16 tokens, ragged last group; without adapters the
+    # plain call has no table, so the bit comparison below is between the table-fed and the plain variant of the kernel
+    (1, 4096, 4117, (32,), 0.5), (16, 4096, 4200, (), 0.5), (7, 8192, 4128, (64,), 0.5), (16, 8192, 4113, (), 0.3),
+    (3, 4096, 8200, (8,), 0.9), (5, 4096, 12000, (), 1.0), (16, 4096, 6000, (16, 16), 0.5)])
 def test_prepared_linear(M, K, N, ranks, density):
     salr = _salr()
     seed = 9000 + M + K + N
