@@ -393,3 +393,32 @@ def test_graph_replays(M, K, N):
         eager = salr.linear(x_dev, bm, v, rod, a, b)   # eager work between the replays, on another workspace
         torch.cuda.synchronize()
         assert torch.equal(eager.view(torch.int16), y.view(torch.int16)), f"replay {replay} differs from eager"
+
+
+def test_large_batch_calls_back_to_back_share_a_workspace():
+    """Calls queued back to back on one stream with ONE workspace and alternating inputs must each give what the same
+    call gives alone: nothing of a call may overtake the previous call's MFMA stage, which still reads the workspace."""
+    salr = _salr()
+    M, K, N = 300, 1024, 520
+    xs, ws_, outs = [], [], []
+    probs = [_problem(M, K, N, (16, 16), 4200 + i) for i in range(2)]
+    enc = []
+    for x, w, a_cat, b_cat in probs:
+        rb, rv, ro = oracle.encode(w)
+        enc.append((to_dev_u16(x), to_dev_u32(rb), to_dev_u16(rv), to_dev_u32(ro), to_dev_u16(a_cat), to_dev_u16(b_cat)))
+    need = salr.salr_linear_workspace_bytes(M, K, N, 32)
+    ws = torch.empty(need, dtype=torch.uint8, device=dev())
+    alone = []
+    for e in enc:
+        alone.append(salr.linear(e[0], e[1], e[2], e[3], e[4], e[5], workspace=ws).clone())
+        torch.cuda.synchronize()
+    ys = [torch.empty((M, N), dtype=torch.int16, device=dev()) for _ in range(24)]
+    for i, y in enumerate(ys):   # no synchronisation in between
+        e = enc[i % 2]
+        salr.salr_sparse_lowrank_linear(e[0], e[1], e[2], e[3], e[4], e[5], y, ws)
+    torch.cuda.synchronize()
+    for i, y in enumerate(ys):
+        assert torch.equal(y, alone[i % 2].view(torch.int16)), f"call {i}"
+    # and against the oracle once
+    x, w, a_cat, b_cat = probs[0]
+    _assert_close(y_to_f64(ys[0]), oracle.linear(x, w, a_cat, b_cat), "back to back, call 0")
