@@ -5,7 +5,8 @@
 //     dB = (X A_cat)^T dY                        [R, N]
 // Everything is a product this library already has a kernel for, on operands laid out so that the contraction
 // index is the contiguous one:
-//     dX  the dense MFMA stage on dY and the TRANSPOSED decoded weight [K, N] (decode, then a bf16 transpose), with
+//     dX  the dense MFMA stage on dY and the TRANSPOSED decoded weight [K, N] (decoded straight into that layout when
+//         K is a multiple of 128, else decode and a bf16 transpose), with
 //         T' = dY B_cat^T [M, Rpad] and A_cat^T [Rpad, K] riding along as its adapter steps;
 //     T' and T = X A_cat: the tall-product kernel of the adapter stage (B_cat's rows already run along N);
 //     dA, dB: the same kernel on X^T [K, M] and dY^T [N, M] against T'^T and T^T [Rpad, M].
@@ -110,9 +111,15 @@ hipError_t launch_linear_backward(const uint16_t* x, const uint16_t* dy, int64_t
         launch_adapter_transpose(a_cat, K, R, Rpad, at, stream);
     }
     if (want_dx) {
-        hipError_t e = launch_decode(bitmap, values, row_offsets, N, K, wd, stream);
-        if (e != hipSuccess) return e;
-        launch_transpose_bf16(wd, N, K, wt, stream);
+        hipError_t e;
+        if (decode_transposed_takes(N, K, values, wt)) {   // straight into the transposed dense weight
+            e = launch_decode_transposed(bitmap, values, row_offsets, N, K, wt, stream);
+            if (e != hipSuccess) return e;
+        } else {
+            e = launch_decode(bitmap, values, row_offsets, N, K, wd, stream);
+            if (e != hipSuccess) return e;
+            launch_transpose_bf16(wd, N, K, wt, stream);
+        }
         const TimingEvents none;
         launch_dense_stage(dy, M, N, K, wt, tp, at, R, Rpad, dx, ypart, none, stream);
     }

@@ -261,6 +261,157 @@ hipError_t launch_decode(const uint32_t* bitmap, const uint16_t* values, const u
 }
 
 // ---------------------------------------------------------------------------------------------------
+// Decode into the TRANSPOSED dense matrix, out_t [cols, rows] (the backward pass contracts over the weight's rows and
+// wants them contiguous): the reconstruction rule of Sec. 3.3 as in the kernels above, with the transposition done in
+// LDS on the way out, so that the dense matrix crosses memory once instead of three times (decode, then read and
+// write again to transpose).  cols % 128 == 0, rows % 64 == 0.
+//   workgroup (b, z): rows 64 b .. 64 b + 63 (wave w the 16 rows 16 w ..), chunks [C z / ksl, C (z + 1) / ksl) of the
+//   C = cols / 128 chunks of 128 columns.  Per chunk lane (n = lane%16, g = lane/16) expands byte g of the four bitmap
+//   words of row n, as in the small-batch linear, and writes its 32 values into an LDS tile [128 columns][64 rows];
+//   after a barrier the 256 threads store the tile's rows, 128 bytes each, with 16-byte stores.
+//   The packed values of the next chunk are in flight while this one is expanded.
+// ---------------------------------------------------------------------------------------------------
+constexpr int kDtWaves = 4;
+constexpr int kDtThreads = kDtWaves * 64;
+constexpr int kDtRows = 16 * kDtWaves;
+constexpr int kDtPitch = kDtRows + 8;     // bf16 elements per tile row: 144 bytes, 16-byte aligned, banks spread
+constexpr int kDtSlotDwords = 68;         // per row and chunk: 17 vectors of 16 B (128 values + misalignment)
+
+struct DtStage {
+    uint4 bm;
+    uint4 vq[3];
+    uint32_t off, nv, vbase;
+};
+
+__global__ __launch_bounds__(kDtThreads) void decode_transposed_kernel(const uint32_t* __restrict__ bitmap,
+                                                                       const uint16_t* __restrict__ values,
+                                                                       const uint32_t* __restrict__ row_offsets, int64_t rows,
+                                                                       int64_t cols, int ksl, uint16_t* __restrict__ out_t) {
+    __shared__ __attribute__((aligned(16))) uint16_t tile[128 * kDtPitch];
+    __shared__ __attribute__((aligned(16))) uint32_t slots[kDtWaves * 16 * kDtSlotDwords + 8];
+    __shared__ uint32_t lut[kNibbleLutWords];
+    nibble_lut_init(lut);
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n = lane & 15, g = lane >> 4;
+    const int64_t n0 = (int64_t)blockIdx.x * kDtRows;
+    const int64_t row = n0 + 16 * wave + n;
+    const int64_t row_c = row;   // rows % 64 == 0: every row of the block exists
+    const int64_t wpr = cols >> 5;
+    const int64_t chunks = wpr >> 2;
+    const int z = blockIdx.y;
+    const int64_t c_begin = chunks * z / ksl, c_end = chunks * (z + 1) / ksl;   // the same for the whole workgroup
+    const uint32_t* brow = bitmap + row_c * wpr;
+    // nonzeros of the row left of the slice: the 4 lanes of a row share the words, 8 loads in flight each
+    uint32_t cur = row_offsets[row_c];
+    {
+        uint32_t before = 0;
+        for (int64_t c0 = 0; c0 < c_begin; c0 += 32) {
+            uint4 q[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int64_t c = c0 + g + 4 * i;
+                q[i] = *reinterpret_cast<const uint4*>(brow + (c < c_begin ? c : 0) * 4);
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                before += (c0 + g + 4 * i < c_begin) ? __popc(q[i].x) + __popc(q[i].y) + __popc(q[i].z) + __popc(q[i].w) : 0u;
+        }
+        before += __shfl_xor(before, 16, 64);
+        before += __shfl_xor(before, 32, 64);
+        cur += before;
+    }
+    const uint4* values128 = reinterpret_cast<const uint4*>(values);
+    uint32_t* slot = slots + (wave * 16 + n) * kDtSlotDwords;
+    // chunks past the slice read its last chunk and count as empty (no conditional load in the stream)
+    auto issue = [&](DtStage& st, int64_t c) {
+        uint4 bm = *reinterpret_cast<const uint4*>(brow + (c < c_end ? c : c_end - 1) * 4);
+        const uint32_t keep = c < c_end ? 0xFFFFFFFFu : 0u;
+        bm.x &= keep; bm.y &= keep; bm.z &= keep; bm.w &= keep;
+        st.bm = bm;
+        const uint32_t len = __popc(bm.x) + __popc(bm.y) + __popc(bm.z) + __popc(bm.w);
+        st.off = cur & 7u;
+        st.nv = len ? (st.off + len + 7u) >> 3 : 0u;
+        st.vbase = cur >> 3;
+        const uint32_t last = st.nv ? st.nv - 1u : 0u;
+        // an empty piece reads the bitmap instead (always mapped: cols >= 128 gives every row 16 bytes)
+        const uint4* vb = st.nv ? values128 + st.vbase : reinterpret_cast<const uint4*>(brow);
+        cur += len;
+#pragma unroll
+        for (int i = 0; i < 3; ++i) {
+            const uint32_t v = g + 4 * i;
+            st.vq[i] = vb[v < last ? v : last];
+        }
+    };
+    __syncthreads();   // the lookup table
+    if (c_begin >= c_end) return;   // the same for the whole workgroup
+    DtStage st[2];
+    issue(st[0], c_begin);
+    issue(st[1], c_begin + 1);
+    for (int64_t c = c_begin; c < c_end; c += 2) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            if (c + i < c_end) {   // the same for the whole workgroup
+                const DtStage& s0 = st[i];
+#pragma unroll
+                for (int v = 0; v < 3; ++v) *reinterpret_cast<uint4*>(slot + 4 * (g + 4 * v)) = s0.vq[v];
+                if (s0.nv > 12u) {   // a piece of more than 89 values: fetch the rest now
+#pragma unroll
+                    for (int v3 = 3; v3 < 5; ++v3) {
+                        const uint32_t v = g + 4 * v3;
+                        if (v < 17u) *reinterpret_cast<uint4*>(slot + 4 * v) = values128[s0.vbase + (v < s0.nv - 1u ? v : s0.nv - 1u)];
+                    }
+                }
+                __builtin_amdgcn_wave_barrier();
+                const uint32_t words[4] = {s0.bm.x, s0.bm.y, s0.bm.z, s0.bm.w};
+                uint32_t c_local = s0.off;
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    const uint32_t word = words[s];
+                    const uint32_t m8 = (word >> (8 * g)) & 0xFFu;
+                    const uint32_t cb = c_local + __popc(word & ((1u << (8 * g)) - 1u));
+                    const uint4 wq = expand_byte(slot, lut, cb, m8);
+                    c_local += __popc(word);
+                    const uint32_t e[4] = {wq.x, wq.y, wq.z, wq.w};
+                    uint16_t* col = tile + (32 * s + 8 * g) * kDtPitch + 16 * wave + n;   // column 32 s + 8 g of the chunk
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) col[j * kDtPitch] = (uint16_t)(e[j >> 1] >> (16 * (j & 1)));
+                }
+                issue(st[i], c + i + 2);
+                // barriers that wait for LDS traffic only: the requests of the next chunks stay in flight
+                asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // the tile is complete
+                const int64_t k0 = (c + i) * 128;
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const int idx = tid + kDtThreads * t;
+                    const int kr = idx >> 3, v = idx & 7;
+                    *reinterpret_cast<uint4*>(out_t + (k0 + kr) * rows + n0 + 8 * v) =
+                        *reinterpret_cast<const uint4*>(tile + kr * kDtPitch + 8 * v);
+                }
+                asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // the tile may be overwritten
+            }
+        }
+    }
+}
+
+bool decode_transposed_takes(int64_t rows, int64_t cols, const void* values, const void* out_t) {
+    return rows > 0 && rows % kDtRows == 0 && cols >= 128 && cols % 128 == 0 && (reinterpret_cast<uintptr_t>(values) & 15u) == 0 &&
+           (reinterpret_cast<uintptr_t>(out_t) & 15u) == 0;
+}
+
+hipError_t launch_decode_transposed(const uint32_t* bitmap, const uint16_t* values, const uint32_t* row_offsets, int64_t rows,
+                                    int64_t cols, uint16_t* out_t, hipStream_t stream) {
+    const int64_t blocks = (rows + kDtRows - 1) / kDtRows, chunks = cols / 128;
+    int64_t ksl = (1024 + blocks - 1) / blocks;   // about four workgroups per CU
+    ksl = ksl < 1 ? 1 : (ksl > chunks ? chunks : ksl);
+    if (ksl > 65535) ksl = 65535;
+    hipLaunchKernelGGL(decode_transposed_kernel, dim3((unsigned)blocks, (unsigned)ksl), dim3(kDtThreads), 0, stream, bitmap, values,
+                       row_offsets, rows, cols, (int)ksl, out_t);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------------
 // Slice table (see salr_internal.hpp; the block's work is slice_table_block in salr_linear_common.hpp).  Runs once per
 // layer.
 // ---------------------------------------------------------------------------------------------------

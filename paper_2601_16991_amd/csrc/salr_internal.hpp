@@ -242,6 +242,10 @@ size_t linear_nf4_workspace_bytes(int64_t M, int64_t N, int64_t R);
 hipError_t launch_linear_nf4(const LinearArgs& args, const uint8_t* codes, const uint16_t* scales, int64_t nnz,
                              hipStream_t stream, const TimingEvents& ev);
 
+// decode into the transposed dense matrix out_t [cols, rows] (cols a multiple of 128, 16-byte aligned buffers)
+bool decode_transposed_takes(int64_t rows, int64_t cols, const void* values, const void* out_t);
+hipError_t launch_decode_transposed(const uint32_t* bitmap, const uint16_t* values, const uint32_t* row_offsets, int64_t rows,
+                                    int64_t cols, uint16_t* out_t, hipStream_t stream);
 hipError_t launch_linear(const LinearArgs& args, hipStream_t stream);
 // count bf16 zeros (+0.0) at out
 hipError_t launch_fill_zero(uint16_t* out, int64_t count, hipStream_t stream);

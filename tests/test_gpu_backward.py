@@ -50,7 +50,11 @@ def _run(x, dy, w_hat, a_cat, b_cat, need_dx=True, need_dadb=True):
 
 
 @pytest.mark.parametrize("M,K,N,ranks", [(32, 64, 64, (8,)), (96, 256, 192, (16, 8)), (256, 512, 320, (40,)),
-                                        (64, 1024, 128, (32, 32, 64)), (320, 96, 704, (5, 3)), (2048, 512, 512, (16,))])
+                                        (64, 1024, 128, (32, 32, 64)), (320, 96, 704, (5, 3)), (2048, 512, 512, (16,)),
+                                        # K a multiple of 128: the weight is decoded straight into its transpose; one chunk per
+                                        # row, one slice of many chunks, many slices
+                                        (128, 384, 128, (8,)), (64, 256, 192, (4,)), (96, 4096, 320, (16,)), (160, 128, 64, (2,)),
+                                        (64, 2048, 4160, (8,))])
 def test_backward_all_gradients(M, K, N, ranks):
     x, dy, w_hat, a_cat, b_cat = _problem(M, K, N, ranks, 1000 + M + K + N)
     dx, da, db = _run(x, dy, w_hat, a_cat, b_cat)
