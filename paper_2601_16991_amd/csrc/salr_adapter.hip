@@ -134,6 +134,104 @@ void launch_adapter_transpose(const uint16_t* a_cat, int64_t K, int R, int Rpad,
                        Rpad, a_t);
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Products that contract over the ROWS of a large row-major matrix (the adapter gradients of the backward pass,
+// dA = X^T T' and dB^T = dY^T T): partial[z][c][r] = sum over the rows m of slice z of in[m][c] * s_t[r][m], with
+// in [M, C] bf16 and the small factor given transposed, s_t [Rpad, M].  The large matrix is read once, row-wise and
+// coalesced, and transposed on the way into the MFMA operand by an LDS tile: no transposed copy of it in memory.
+//   workgroup (b, z): columns 64 b .. 64 b + 63 (wave w the 16 columns 16 w ..), row slice z (whole steps of 32 rows);
+//   per step the 256 threads copy the tile [32 rows x 64 columns] into one of two LDS buffers (the next tile's request
+//   is in flight while this one is multiplied); lane (i, g) gathers in[8 g .. 8 g + 7][16 w + i] from it as the A
+//   operand of 16x16x32 bf16 MFMAs, the B operand s_t[16 rt + i][8 g ..] is a plain 16-byte load; kRT rank tiles per
+//   pass over the slice.  fp32 partials [ksplit][C][Rpad]; padding columns of Rpad come out as zeros (s_t is zero there).
+// M % 32 == 0.
+// ---------------------------------------------------------------------------------------------------
+constexpr int kTnPitch = 64 + 8;   // bf16 elements per tile row
+
+template <int kRT>
+__global__ __launch_bounds__(256) void tall_tn_kernel(const uint16_t* __restrict__ in, int64_t M, int64_t C,
+                                                      const uint16_t* __restrict__ s_t, int Rpad, int ksplit,
+                                                      float* __restrict__ partial) {
+    __shared__ __attribute__((aligned(16))) uint16_t tile[2][32 * kTnPitch];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int i16 = lane & 15, g = lane >> 4;
+    const int64_t c0 = (int64_t)blockIdx.x * 64;
+    const int z = blockIdx.y;
+    const int64_t steps = M >> 5;
+    const int64_t per_slice = (steps + ksplit - 1) / ksplit;
+    const int64_t s_begin = z * per_slice < steps ? z * per_slice : steps;
+    const int64_t s_end = (z + 1) * per_slice < steps ? (z + 1) * per_slice : steps;
+    // this thread's 16 bytes of a tile: row tid / 8, columns 8 (tid % 8) ..; columns past C are clamped (never stored)
+    const int trow = tid >> 3, tvec = tid & 7;
+    const bool vec_ok = (C & 7) == 0;
+    auto load_tile = [&](int64_t step) -> uint4 {
+        const int64_t m = (step << 5) + trow;
+        const int64_t c = c0 + 8 * tvec;
+        if (vec_ok) {
+            const int64_t cc = c + 8 <= C ? c : C - 8;   // a clamped vector holds other columns: they are not stored
+            return *reinterpret_cast<const uint4*>(in + m * C + cc);
+        }
+        uint32_t e[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) e[j] = in[m * C + (c + j < C ? c + j : C - 1)];
+        return make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16));
+    };
+    for (int rb = 0; rb < Rpad; rb += 16 * kRT) {
+        f32x4 acc[kRT];
+#pragma unroll
+        for (int rt = 0; rt < kRT; ++rt) acc[rt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        const uint16_t* srow[kRT];
+#pragma unroll
+        for (int rt = 0; rt < kRT; ++rt) {
+            const int r = rb + 16 * rt + i16;
+            srow[rt] = s_t + (int64_t)(r < Rpad ? r : Rpad - 1) * M + 8 * g;
+        }
+        if (s_begin < s_end) {
+            uint4 next = load_tile(s_begin);
+            int buf = 0;
+            for (int64_t step = s_begin; step < s_end; ++step) {
+                *reinterpret_cast<uint4*>(&tile[buf][trow * kTnPitch + 8 * tvec]) = next;
+                if (step + 1 < s_end) next = load_tile(step + 1);
+                uint4 bq[kRT];
+#pragma unroll
+                for (int rt = 0; rt < kRT; ++rt) bq[rt] = *reinterpret_cast<const uint4*>(srow[rt] + (step << 5));
+                __syncthreads();   // the tile is complete; the buffer written two steps ago has been read by everyone
+                const uint16_t* col = &tile[buf][(8 * g) * kTnPitch + 16 * wave + i16];
+                uint32_t e[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) e[j] = col[j * kTnPitch];
+                const uint4 aq = make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16));
+#pragma unroll
+                for (int rt = 0; rt < kRT; ++rt)
+                    acc[rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(aq), as_bf16x8(bq[rt]), acc[rt], 0, 0, 0);
+                buf ^= 1;
+            }
+        }
+        __syncthreads();   // before the next pass writes buffer 0 again
+        // accumulator layout of the 16x16 MFMA: lane holds column lane % 16 (rank), rows 4 (lane / 16) + e (matrix column)
+#pragma unroll
+        for (int rt = 0; rt < kRT; ++rt) {
+            const int r = rb + 16 * rt + i16;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int64_t c = c0 + 16 * wave + 4 * g + e;
+                if (c < C && r < Rpad) partial[((int64_t)z * C + c) * Rpad + r] = acc[rt][e];
+            }
+        }
+    }
+}
+
+// partial [ksplit][C][Rpad] fp32 = slices of in^T [C, M] * s_t^T [M, Rpad]
+void launch_tall_tn(const uint16_t* in, int64_t M, int64_t C, const uint16_t* s_t, int Rpad, int ksplit, float* partial,
+                    hipStream_t stream) {
+    const dim3 grid((unsigned)((C + 63) / 64), (unsigned)ksplit);
+    const int tiles = Rpad / 16;
+    if (tiles % 4 == 0) hipLaunchKernelGGL(tall_tn_kernel<4>, grid, dim3(256), 0, stream, in, M, C, s_t, Rpad, ksplit, partial);
+    else hipLaunchKernelGGL(tall_tn_kernel<2>, grid, dim3(256), 0, stream, in, M, C, s_t, Rpad, ksplit, partial);
+}
+
 template <int kMB, int kDepth>
 static void launch_tall_product_rt(int rank_tiles, dim3 grid, hipStream_t stream, const uint16_t* x, int64_t M, int64_t K,
                                    const uint16_t* a_t, int Rpad, int ksplit, uint16_t* t, float* partial, int keep) {

@@ -9,7 +9,8 @@
 //         K is a multiple of 128, else decode and a bf16 transpose), with
 //         T' = dY B_cat^T [M, Rpad] and A_cat^T [Rpad, K] riding along as its adapter steps;
 //     T' and T = X A_cat: the tall-product kernel of the adapter stage (B_cat's rows already run along N);
-//     dA, dB: the same kernel on X^T [K, M] and dY^T [N, M] against T'^T and T^T [Rpad, M].
+//     dA, dB: products that contract over the rows of X and dY: the row-contracting tall product (tall_tn_kernel), which
+//         transposes its tiles of the large operand in LDS, against T'^T and T^T [Rpad, M].
 // As in the forward pass T and T' are rounded to bf16 once; sums are fp32; outputs bf16.
 #include "salr_device.hpp"
 #include "salr_internal.hpp"
@@ -42,7 +43,7 @@ __global__ __launch_bounds__(256) void reduce_columns_kernel(const float* __rest
 
 struct BackwardPlan {
     int Rpad, ks_tp, ks_t, ks_da, ks_db, ks_y;
-    size_t off_wd, off_wt, off_tp, off_at, off_bpad, off_tt, off_xt, off_dyt, off_small_t, off_tpart, off_ypart, total;
+    size_t off_wd, off_wt, off_tp, off_at, off_bpad, off_tt, off_small_t, off_tpart, off_ypart, total;
 };
 
 static BackwardPlan backward_plan(int64_t M, int64_t K, int64_t N, int64_t R, bool want_dx, bool want_dadb) {
@@ -50,8 +51,8 @@ static BackwardPlan backward_plan(int64_t M, int64_t K, int64_t N, int64_t R, bo
     p.Rpad = (int)adapter_rank_padded(R);
     p.ks_tp = adapter_ksplit(M, N);   // T' = dY B^T: rows M, contraction N
     p.ks_t = adapter_ksplit(M, K);    // T  = X A:     rows M, contraction K
-    p.ks_da = adapter_ksplit(K, M);   // dA: rows K, contraction M
-    p.ks_db = adapter_ksplit(N, M);   // dB: rows N, contraction M
+    p.ks_da = tn_ksplit(K, M);        // dA: rows K, contraction M
+    p.ks_db = tn_ksplit(N, M);        // dB: rows N, contraction M
     p.ks_y = want_dx ? dense_ksplit(M, N, K) : 1;
     size_t o = 0;
     auto take = [&](size_t bytes) { const size_t at = o; o += round_up_256(bytes); return at; };
@@ -62,8 +63,6 @@ static BackwardPlan backward_plan(int64_t M, int64_t K, int64_t N, int64_t R, bo
     p.off_bpad = take(R > 0 ? (size_t)N * p.Rpad * 2 : 0);
     const bool grads = want_dadb && R > 0;
     p.off_tt = take(grads ? (size_t)M * p.Rpad * 2 : 0);
-    p.off_xt = take(grads ? (size_t)M * K * 2 : 0);
-    p.off_dyt = take(grads ? (size_t)M * N * 2 : 0);
     p.off_small_t = take(grads ? (size_t)2 * M * p.Rpad * 2 : 0);   // T^T and T'^T
     size_t part = 0;
     if (R > 0) {
@@ -97,8 +96,6 @@ hipError_t launch_linear_backward(const uint16_t* x, const uint16_t* dy, int64_t
     uint16_t* at = reinterpret_cast<uint16_t*>(ws + p.off_at);
     uint16_t* bpad = reinterpret_cast<uint16_t*>(ws + p.off_bpad);
     uint16_t* tt = reinterpret_cast<uint16_t*>(ws + p.off_tt);
-    uint16_t* xt = reinterpret_cast<uint16_t*>(ws + p.off_xt);
-    uint16_t* dyt = reinterpret_cast<uint16_t*>(ws + p.off_dyt);
     uint16_t* tt_t = reinterpret_cast<uint16_t*>(ws + p.off_small_t);
     uint16_t* tp_t = tt_t + (size_t)M * Rpad;
     float* tpart = reinterpret_cast<float*>(ws + p.off_tpart);
@@ -125,9 +122,8 @@ hipError_t launch_linear_backward(const uint16_t* x, const uint16_t* dy, int64_t
     }
     if (want_dadb && R > 0) {
         if (da != nullptr) {   // dA = X^T T'
-            launch_transpose_bf16(x, M, K, xt, stream);
             launch_transpose_bf16(tp, M, Rpad, tp_t, stream);
-            launch_tall_product(xt, K, M, tp_t, Rpad, p.ks_da, nullptr, tpart, true, stream);
+            launch_tall_tn(x, M, K, tp_t, Rpad, p.ks_da, tpart, stream);
             hipLaunchKernelGGL(reduce_columns_kernel, dim3((unsigned)((K * R + 255) / 256)), dim3(256), 0, stream, tpart, K, Rpad,
                                p.ks_da, R, 0, da);
         }
@@ -135,8 +131,7 @@ hipError_t launch_linear_backward(const uint16_t* x, const uint16_t* dy, int64_t
             launch_tall_product(x, M, K, at, Rpad, p.ks_t, tt, tpart, false, stream);
             if (p.ks_t > 1) launch_splitk_reduce(tpart, M * Rpad, p.ks_t, tt, stream);
             launch_transpose_bf16(tt, M, Rpad, tt_t, stream);
-            launch_transpose_bf16(dy, M, N, dyt, stream);
-            launch_tall_product(dyt, N, M, tt_t, Rpad, p.ks_db, nullptr, tpart, true, stream);
+            launch_tall_tn(dy, M, N, tt_t, Rpad, p.ks_db, tpart, stream);
             hipLaunchKernelGGL(reduce_columns_kernel, dim3((unsigned)((N * R + 255) / 256)), dim3(256), 0, stream, tpart, N, Rpad,
                                p.ks_db, R, 1, db);
         }

@@ -263,6 +263,16 @@ void launch_adapter_partial(const LinearArgs& args, hipStream_t stream);
 void launch_adapter_t(const LinearArgs& args, hipStream_t stream);
 // x [M, K] bf16 times the transpose of a_t [Rpad, K] bf16 (Rpad % 32 == 0, K % 32 == 0), K split over `ksplit`
 // slices: bf16 t [M, Rpad] (one slice, !keep_fp32) or fp32 partial [ksplit, M, Rpad]
+// Products that contract over the rows of in [M, C] (M % 32 == 0): partial [ksplit][C][Rpad] fp32; tn_ksplit picks the
+// split of M (about four workgroups per CU, at least two steps of 32 rows each)
+inline int tn_ksplit(int64_t C, int64_t M) {
+    const int64_t blocks = (C + 63) / 64, steps = M / 32;
+    int s = 1;
+    while (s < 64 && blocks * s * 2 <= 1024 && steps / (s * 2) >= 2) s *= 2;
+    return s;
+}
+void launch_tall_tn(const uint16_t* in, int64_t M, int64_t C, const uint16_t* s_t, int Rpad, int ksplit, float* partial,
+                    hipStream_t stream);
 void launch_tall_product(const uint16_t* x, int64_t M, int64_t K, const uint16_t* a_t, int Rpad, int ksplit, uint16_t* t,
                          float* partial, bool keep_fp32, hipStream_t stream);
 // a_t [Rpad, K] = A_cat [K, R]^T, rows R .. Rpad - 1 zero

@@ -54,7 +54,11 @@ def _run(x, dy, w_hat, a_cat, b_cat, need_dx=True, need_dadb=True):
                                         # K a multiple of 128: the weight is decoded straight into its transpose; one chunk per
                                         # row, one slice of many chunks, many slices
                                         (128, 384, 128, (8,)), (64, 256, 192, (4,)), (96, 4096, 320, (16,)), (160, 128, 64, (2,)),
-                                        (64, 2048, 4160, (8,))])
+                                        (64, 2048, 4160, (8,)),
+                                        # adapter gradients: column counts of X / dY that are not whole 64-column blocks or not a
+                                        # multiple of 8, ranks of one and of many 16-column tiles, a single 32-row step
+                                        (32, 96, 64, (3,)), (96, 160, 192, (16, 16, 16)), (64, 1056, 128, (64, 64, 64, 64)),
+                                        (1024, 4096, 4096, (32,))])
 def test_backward_all_gradients(M, K, N, ranks):
     x, dy, w_hat, a_cat, b_cat = _problem(M, K, N, ranks, 1000 + M + K + N)
     dx, da, db = _run(x, dy, w_hat, a_cat, b_cat)
