@@ -484,7 +484,9 @@ def time_qsalr(cfg, Ms, steps):
                                "TFLOP/s": round(wl.algorithmic_flops(M, cfg.K, cfg.N, layer.R) / ms / 1e9, 1),
                                "dense_gemm_ms": round(dense_ms, 4), "speedup_vs_dense_gemm": round(dense_ms / ms, 3),
                                "workspace_bytes": int(ws_bytes),
-                               "path": "one kernel on the 4-bit codes" if (M <= 64 and cfg.K % 128 == 0) else "dequantise, then the layer"}
+                               "path": "one kernel on the 4-bit codes" if (M <= 64 and cfg.K % 128 == 0) else
+                                       "decode stage on the 4-bit codes, then the dense MFMA stage" if (M > 128 and cfg.K % 64 == 0)
+                                       else "dequantise, then the layer"}
         del calls, ws
     return res
 

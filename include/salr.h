@@ -255,8 +255,11 @@ salr_status_t salr_sparse_lowrank_linear_noalloc(const uint16_t* x, int64_t M, i
  *   - Up to 64 tokens on rows of whole 128-column chunks (K % 128 == 0, nnz > 0) one kernel reads bitmap, codes and
  *     scales and dequantises inside its decode stage: the weight crosses the memory system at 1 + 4.25 (1 - p) bits
  *     per element and no bf16 copy of the values exists.  Workspace: the layer's partial sums of X * A_cat and a
- *     slice table built per call (64 bytes per weight row).  As an INPUT to this call `codes` must be readable up to
- *     the next multiple of 16 bytes (vector reads; the padding is never used).
+ *     slice table built per call (64 bytes per weight row).
+ *   As an INPUT to salr_qsalr_linear `codes` must be readable up to the next multiple of 16 bytes (vector reads; the
+ *   padding is never used).
+ *   - Large batches that take the two-stage path (more than 128 tokens, or more than 64 where the row-tiled kernel
+ *     does not apply; K % 64 == 0): its decode stage reads the codes; workspace as for the plain layer.
  *   - Otherwise the values are dequantised once per call into the first part of the workspace (2 * nnz bytes,
  *     rounded up), then the layer runs as usual on them.
  * Both compute the same products; where the plain layer would take its small-batch streaming kernels Y is the same

@@ -37,6 +37,12 @@ constexpr int64_t kMaxRank = 256;
 constexpr int64_t kMaxM = 65535LL * 64;           // gridDim.y of the generic kernel
 constexpr int64_t kMaxSvdDim = 65535LL * 32;      // gridDim.y of the transposing kernel
 
+// QSALR calls whose decode stage reads the 4-bit codes itself: the two-stage path (large batches, K % 64 == 0) within the
+// row decode kernel's limits (rows of at most 524288 columns); the workspace is then the plain layer's.
+bool qsalr_decodes_codes(int64_t M, int64_t K, int64_t N, int64_t nnz) {
+    return nnz > 0 && K > 0 && salr::linear_takes_twostage(M, K, N) && (K / 32 + 15) / 16 <= 1024;
+}
+
 }  // namespace
 
 extern "C" {
@@ -180,7 +186,8 @@ salr_status_t salr_build_slice_table(const uint32_t* bitmap, const uint32_t* row
 static salr_status_t linear_entry(const uint16_t* x, int64_t M, int64_t K, int64_t N, const uint32_t* bitmap,
                                   const uint16_t* values, const uint32_t* row_offsets, const uint32_t* slice_table,
                                   const uint16_t* a_cat, const uint16_t* b_cat, int64_t R, uint16_t* y, void* workspace,
-                                  size_t workspace_bytes, void* stream) {
+                                  size_t workspace_bytes, void* stream, const uint8_t* codes = nullptr,
+                                  const uint16_t* scales = nullptr, int64_t nnz = 0) {
     if (M < 0 || K < 0 || N < 0 || R < 0) return SALR_ERR_INVALID_ARG;
     if (M == 0 || N == 0) return SALR_OK;
     if (!y) return SALR_ERR_INVALID_ARG;
@@ -205,6 +212,10 @@ static salr_status_t linear_entry(const uint16_t* x, int64_t M, int64_t K, int64
     a.t = static_cast<uint16_t*>(workspace);
     a.lean = have < need;   // no room for the decoded copy: decode stage and MFMA stage in one kernel
     a.slice_table = slice_table;
+    if (codes != nullptr) {   // QSALR on the two-stage path (the caller has checked that this call takes it)
+        if (!salr::linear_takes_twostage(M, K, N) || a.lean) return SALR_ERR_UNSUPPORTED;
+        a.values = nullptr; a.codes = codes; a.scales = scales; a.nnz = nnz;
+    }
     if (!slice_table && have >= need && salr::builds_slice_table(M, K, N, R)) {   // none of the caller's: this call's own
         a.slice_table = reinterpret_cast<const uint32_t*>(static_cast<char*>(workspace) +
                                                           salr::linear_workspace_bytes_without_table(M, K, N, R));
@@ -269,6 +280,7 @@ salr_status_t salr_nf4_dequantize_values(const uint8_t* codes, const uint16_t* s
 size_t salr_qsalr_linear_workspace_bytes(int64_t M, int64_t K, int64_t N, int64_t R, int64_t nnz) {
     if (M <= 0 || K < 0 || N <= 0 || R < 0 || R > kMaxRank || K % 32 != 0 || nnz < 0) return 0;
     if (salr::linear_nf4_takes(M, K, N, nnz)) return salr::linear_nf4_workspace_bytes(M, N, R);   // no bf16 copy of the values
+    if (qsalr_decodes_codes(M, K, N, nnz)) return salr::linear_workspace_bytes(M, K, N, R);      // nor here
     return salr::qsalr_values_bytes(nnz) + salr::linear_workspace_bytes(M, K, N, R);
 }
 
@@ -297,6 +309,12 @@ salr_status_t salr_qsalr_linear(const uint16_t* x, int64_t M, int64_t K, int64_t
         a.slice_table = reinterpret_cast<const uint32_t*>(static_cast<char*>(workspace) + salr::linear_nf4_table_offset(M, R));
         hipError_t e = salr::launch_linear_nf4(a, codes, scales, nnz, static_cast<hipStream_t>(stream), salr::g_timing_events);
         return e == hipSuccess ? SALR_OK : SALR_ERR_HIP;
+    }
+    if (qsalr_decodes_codes(M, K, N, nnz)) {   // large batches: the decode stage reads the codes
+        const size_t lw = salr::linear_workspace_bytes(M, K, N, R);
+        if (!workspace || workspace_bytes < lw) return SALR_ERR_CAPACITY;
+        return linear_entry(x, M, K, N, bitmap, nullptr, row_offsets, nullptr, a_cat, b_cat, R, y, workspace, workspace_bytes, stream,
+                            codes, scales, nnz);
     }
     const size_t vbytes = salr::qsalr_values_bytes(nnz);
     const size_t need = vbytes + (K > 0 ? salr::linear_workspace_bytes(M, K, N, R) : 0);

@@ -9,6 +9,7 @@
 #include "salr_device.hpp"
 #include "salr_internal.hpp"
 #include "salr_linear_common.hpp"
+#include "salr_nf4.hpp"
 
 namespace salr {
 
@@ -153,11 +154,18 @@ __global__ __launch_bounds__(kCodecThreads) void decode_kernel(const uint32_t* _
 constexpr int kDecWaves = kCodecThreads / kWave;
 constexpr int kDecMaxGroups = 1024;   // rows up to 524288 columns
 
+// kNf4 (QSALR, paper Sec. 4): `values` are the 4-bit codes, eight to a dword where the bf16 kernel has a 16-byte vector of
+// eight values; a lane dequantises its dword (all eight codes lie in one scale block of 64) on the way into the slot,
+// and everything after that is the same.  scale_last: index of the last scale.
+template <bool kNf4>
 __global__ __launch_bounds__(kCodecThreads) void decode_rows_kernel(const uint32_t* __restrict__ bitmap,
                                                                     const uint16_t* __restrict__ values,
                                                                     const uint32_t* __restrict__ row_offsets, int64_t cols,
-                                                                    int64_t wpr, uint16_t* __restrict__ out) {
+                                                                    int64_t wpr, uint16_t* __restrict__ out,
+                                                                    const uint16_t* __restrict__ scales, uint32_t scale_last) {
     __shared__ uint32_t prefix[kDecMaxGroups + 1];
+    __shared__ float levels[16];
+    if (kNf4 && threadIdx.x < 16) levels[threadIdx.x] = kNf4Levels[threadIdx.x];
     __shared__ __attribute__((aligned(16))) uint32_t slot[kDecWaves][65 * 4 + 8];
     __shared__ uint32_t lut[kNibbleLutWords];
     nibble_lut_init(lut);
@@ -190,6 +198,21 @@ __global__ __launch_bounds__(kCodecThreads) void decode_rows_kernel(const uint32
     // ---- pass 2
     const uint8_t* mask_bytes = reinterpret_cast<const uint8_t*>(brow);
     const uint4* values128 = reinterpret_cast<const uint4*>(values);
+    const uint32_t* codes32 = reinterpret_cast<const uint32_t*>(values);
+    // vector j of the packed values as requested (16 bytes of bf16; or dword j of the codes in .x and its scale in .y)
+    // and as it goes into the slot (the codes dequantised: only then does the wave wait for the request)
+    auto fetch = [&](uint32_t j) -> uint4 {
+        if constexpr (kNf4) {
+            const uint32_t blk = j >> 3;
+            return make_uint4(codes32[j], scales[blk < scale_last ? blk : scale_last], 0u, 0u);
+        } else {
+            return values128[j];
+        }
+    };
+    auto ready = [&](const uint4& q) -> uint4 {
+        if constexpr (kNf4) return nf4_decode8(q.x, bf16_bits_to_f32(q.y), levels);
+        else return q;
+    };
     uint16_t* row_out = out + n * cols;
     const int64_t units = (cols + kUnit - 1) / kUnit;
     const uint32_t row_start = row_offsets[n];
@@ -205,7 +228,7 @@ __global__ __launch_bounds__(kCodecThreads) void decode_rows_kernel(const uint32
         // lanes past the piece repeat its last vector (clamped, not predicated); an empty piece loads nothing new
         const uint32_t li = nv ? ((uint32_t)lane < nv ? lane : nv - 1u) : 0u;
         vbase = cursor >> 3;
-        v = nv ? values128[vbase + li] : make_uint4(0, 0, 0, 0);
+        v = nv ? fetch(vbase + li) : make_uint4(0, 0, 0, 0);
     };
     uint32_t m, off, nv, vbase;
     uint4 v;
@@ -215,9 +238,9 @@ __global__ __launch_bounds__(kCodecThreads) void decode_rows_kernel(const uint32
         uint4 v2;
         group_loads(g + kDecWaves, m2, v2, off2, nv2, vbase2);   // next group of this wave, in flight while this one expands
         const uint32_t incl = wave_inclusive_scan(__popc(m));
-        if ((uint32_t)lane < nv) reinterpret_cast<uint4*>(my_slot)[lane] = v;
+        if ((uint32_t)lane < nv) reinterpret_cast<uint4*>(my_slot)[lane] = ready(v);
         // a full group that starts off a vector boundary spans 65 vectors: the last one is fetched on the spot
-        if (__builtin_amdgcn_readfirstlane(nv) > 64u && lane == 0) reinterpret_cast<uint4*>(my_slot)[64] = values128[vbase + 64];
+        if (__builtin_amdgcn_readfirstlane(nv) > 64u && lane == 0) reinterpret_cast<uint4*>(my_slot)[64] = ready(fetch(vbase + 64));
         __builtin_amdgcn_wave_barrier();
         const uint4 q = expand_byte(my_slot, lut, off + incl - __popc(m), m);
         __builtin_amdgcn_wave_barrier();
@@ -225,6 +248,24 @@ __global__ __launch_bounds__(kCodecThreads) void decode_rows_kernel(const uint32
         if (u < units) *reinterpret_cast<uint4*>(row_out + u * kUnit) = q;
         m = m2; v = v2; off = off2; nv = nv2; vbase = vbase2;
     }
+}
+
+static bool vec_ok(const void* p, int64_t cols);
+
+// QSALR: decode from the 4-bit codes straight into the dense matrix (no bf16 copy of the values in between)
+bool decode_nf4_takes(int64_t rows, int64_t cols, int64_t nnz, const void* codes, const void* out) {
+    const int64_t wpr = (cols + 31) / 32;
+    return rows > 0 && cols > 0 && nnz > 0 && vec_ok(out, cols) && (wpr + 15) / 16 <= kDecMaxGroups &&
+           (reinterpret_cast<uintptr_t>(codes) & 3u) == 0;
+}
+
+hipError_t launch_decode_nf4(const uint32_t* bitmap, const uint8_t* codes, const uint16_t* scales, int64_t nnz,
+                             const uint32_t* row_offsets, int64_t rows, int64_t cols, uint16_t* out, hipStream_t stream) {
+    const int64_t wpr = (cols + 31) / 32;
+    hipLaunchKernelGGL(decode_rows_kernel<true>, dim3((unsigned)rows), dim3(kCodecThreads), 0, stream, bitmap,
+                       reinterpret_cast<const uint16_t*>(codes), row_offsets, cols, wpr, out, scales,
+                       (uint32_t)((nnz + kNf4Block - 1) / kNf4Block - 1));
+    return hipGetLastError();
 }
 
 static bool vec_ok(const void* p, int64_t cols) {
@@ -252,7 +293,8 @@ hipError_t launch_decode(const uint32_t* bitmap, const uint16_t* values, const u
     if (rows == 0 || cols == 0) return hipSuccess;
     const int64_t wpr = (cols + 31) / 32;
     if (vec_ok(out, cols) && (wpr + 15) / 16 <= kDecMaxGroups && (reinterpret_cast<uintptr_t>(values) & 15u) == 0)
-        hipLaunchKernelGGL(decode_rows_kernel, dim3((unsigned)rows), dim3(kCodecThreads), 0, stream, bitmap, values, row_offsets, cols, wpr, out);
+        hipLaunchKernelGGL(decode_rows_kernel<false>, dim3((unsigned)rows), dim3(kCodecThreads), 0, stream, bitmap, values,
+                           row_offsets, cols, wpr, out, (const uint16_t*)nullptr, 0u);
     else if (vec_ok(out, cols))
         hipLaunchKernelGGL(decode_kernel<true>, dim3((unsigned)rows), dim3(kCodecThreads), 0, stream, bitmap, values, row_offsets, rows, cols, wpr, out);
     else

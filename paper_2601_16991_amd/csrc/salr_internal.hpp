@@ -52,6 +52,10 @@ struct LinearArgs {
     bool lean = false;  // large batches: no room for a decoded copy of the weight, take the fused kernel
     const uint32_t* slice_table = nullptr;  // optional: the layer's slice table (see kSliceTableSlices)
     bool build_table = false;  // slice_table points into the workspace and the adapter pre-kernel fills it in this call
+    // QSALR on the large-batch path: `values` is null and the decode stage reads these (nnz values, 4-bit codes)
+    const uint8_t* codes = nullptr;
+    const uint16_t* scales = nullptr;
+    int64_t nnz = 0;
 };
 
 // Slice table of a layer (a derived, kernel-private index; the three arrays of the format stay what is checked): for
@@ -182,6 +186,10 @@ hipError_t launch_check_2of4(const uint32_t* bitmap, int64_t rows, int64_t cols,
 
 // decode-sized batches (M <= 16, K % 128 == 0, 12288 <= K <= 32768): the streaming kernel that reads every bitmap word once
 bool linear_slice_takes(int64_t M, int64_t K, int64_t N);
+// Shapes that launch_linear sends down the two-stage path when the workspace has room for the decoded copy
+inline bool linear_takes_twostage(int64_t M, int64_t K, int64_t N) {
+    return M > kStreamMaxM && !uses_rowtile(M, K, N) && uses_twostage(M, K);
+}
 // A call without a slice table of the caller's builds one for itself where the adapter pre-kernel runs anyway (R > 0)
 // and a kernel that gains more from it than the build costs follows: the small-batch streaming kernel on rows of whole
 // chunks, and the row-tiled kernel when its split of K starts where table slices do.  (The long-row kernel reads a
@@ -242,6 +250,10 @@ size_t linear_nf4_workspace_bytes(int64_t M, int64_t N, int64_t R);
 hipError_t launch_linear_nf4(const LinearArgs& args, const uint8_t* codes, const uint16_t* scales, int64_t nnz,
                              hipStream_t stream, const TimingEvents& ev);
 
+// QSALR: decode from the 4-bit codes (the row-per-workgroup decode kernel's limits: cols % 8 == 0, 16-byte aligned out)
+bool decode_nf4_takes(int64_t rows, int64_t cols, int64_t nnz, const void* codes, const void* out);
+hipError_t launch_decode_nf4(const uint32_t* bitmap, const uint8_t* codes, const uint16_t* scales, int64_t nnz,
+                             const uint32_t* row_offsets, int64_t rows, int64_t cols, uint16_t* out, hipStream_t stream);
 // decode into the transposed dense matrix out_t [cols, rows] (cols a multiple of 128, 16-byte aligned buffers)
 bool decode_transposed_takes(int64_t rows, int64_t cols, const void* values, const void* out_t);
 hipError_t launch_decode_transposed(const uint32_t* bitmap, const uint16_t* values, const uint32_t* row_offsets, int64_t rows,

@@ -20,6 +20,7 @@
 #include "salr_device.hpp"
 #include "salr_internal.hpp"
 #include "salr_linear_common.hpp"
+#include "salr_nf4.hpp"
 
 namespace salr {
 
@@ -31,21 +32,6 @@ constexpr int kQSlotDwords = 84;      // LDS per row per chunk: 160 bf16 (five v
                                       // multiples of 4, so the rows of a wave start in different banks
 constexpr int kQLevelWords = 16;
 
-__device__ __constant__ float kQLevels[16] = {
-    -1.0f, -0.6961928009986877f, -0.5250730514526367f, -0.39491748809814453f,
-    -0.28444138169288635f, -0.18477343022823334f, -0.09105003625154495f, 0.0f,
-    0.07958029955625534f, 0.16093020141124725f, 0.24611230194568634f, 0.33791524171829224f,
-    0.44070982933044434f, 0.5626170039176941f, 0.7229568362236023f, 1.0f};
-
-typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-typedef float f32x2_t __attribute__((ext_vector_type(2)));
-
-// two floats -> two bf16 (round to nearest even), the first in the low half
-__device__ __forceinline__ uint32_t pack_bf16_rne(float a, float b) {
-    const f32x2_t v = {a, b};
-    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
-}
-
 template <int MT>
 struct NfStage {
     uint4 bm;                        // the chunk's 4 bitmap words of this lane's row
@@ -55,15 +41,6 @@ struct NfStage {
     uint32_t sc, sc4;                // bf16 scales of the blocks that vector g and the fifth vector lie in
     uint32_t off;                    // nibble offset of the piece inside its first vector (0..31)
 };
-
-// Dequantise the eight codes of c with one scale: eight bf16, value 0 in the low half of .x.
-__device__ __forceinline__ uint4 nf4_decode8(uint32_t c, float scale, const float* levels) {
-    float w[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) w[j] = __fmul_rn(levels[(c >> (4 * j)) & 15u], scale);
-    return make_uint4(pack_bf16_rne(w[0], w[1]), pack_bf16_rne(w[2], w[3]), pack_bf16_rne(w[4], w[5]),
-                      pack_bf16_rne(w[6], w[7]));
-}
 
 // MT m-tiles of 16 rows, S chunks in flight per wave.  K % 128 == 0, nnz > 0.
 template <int MT, int S>
@@ -151,7 +128,7 @@ __global__ __launch_bounds__(kQWaves * 64, (S == 2 && MT == 1) ? 4 : 1) void lin
         nibble_lut_entry(lane, a, b);
         lut[2 * lane] = a;
         lut[2 * lane + 1] = b;
-        levels[lane] = kQLevels[lane];
+        levels[lane] = kNf4Levels[lane];
     }
     __builtin_amdgcn_wave_barrier();
 

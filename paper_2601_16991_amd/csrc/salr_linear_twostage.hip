@@ -268,7 +268,9 @@ void launch_dense_stage(const uint16_t* x, int64_t M, int64_t K, int64_t N, cons
 hipError_t launch_linear_twostage(const LinearArgs& a, hipStream_t stream, const TimingEvents& ev) {
     const int R = (int)a.R, Rpad = (int)adapter_rank_padded(a.R);
     uint16_t* wd = reinterpret_cast<uint16_t*>(reinterpret_cast<char*>(a.t) + twostage_dense_offset(a.M, a.K, a.R));
-    hipError_t e = launch_decode(a.bitmap, a.values, a.row_offsets, a.N, a.K, wd, stream);
+    hipError_t e = a.codes != nullptr
+                       ? launch_decode_nf4(a.bitmap, a.codes, a.scales, a.nnz, a.row_offsets, a.N, a.K, wd, stream)
+                       : launch_decode(a.bitmap, a.values, a.row_offsets, a.N, a.K, wd, stream);
     if (e != hipSuccess) return e;
     if (R > 0) launch_adapter_t(a, stream);
     float* partial = reinterpret_cast<float*>(reinterpret_cast<char*>(wd) + round_up_256((size_t)a.N * (size_t)a.K * sizeof(uint16_t)));

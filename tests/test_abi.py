@@ -335,6 +335,9 @@ def test_qsalr_and_noalloc_validation(lib):
     assert q(65, 4096, 4096, 32, 1000) == _r256(2 * 1000) + g(65, 4096, 4096, 32)
     assert q(65, 4096, 4096, 32, 1001) == _r256(2 * 1008) + g(65, 4096, 4096, 32)
     assert q(16, 4128, 4096, 32, 1000) == _r256(2 * 1000) + g(16, 4128, 4096, 32)    # rows that are not whole chunks
+    # large batches on rows of whole 64-column steps: the decode stage reads the codes, the workspace is the plain layer's
+    assert q(2048, 4096, 4096, 32, 10 ** 6) == g(2048, 4096, 4096, 32)
+    assert q(300, 4128, 4096, 32, 1000) == _r256(2 * 1000) + g(300, 4128, 4096, 32)   # K % 64 != 0: dequantise first
     # up to 64 tokens on rows of whole 128-column chunks: no bf16 copy of the values, only the sixteen fp32 partials
     # of T and the call's slice table (64 bytes per weight row)
     assert q(16, 4096, 4096, 32, 1000) == 16 * 16 * 32 * 4 + 64 * 4096

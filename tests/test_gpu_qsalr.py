@@ -105,13 +105,16 @@ def _plain_on_dequantised(salr, x, rb, codes, scales, ro, nnz, a_cat, b_cat):
     (33, 512, 70, 24, 200, 9), (64, 1024, 131, 40, 200, 10), (4, 3968, 33, 12, 0, 11), (5, 640, 40, 4, 950, 12),
     (2, 384, 20, 256, 200, 13), (16, 8192, 40, 64, 200, 14), (9, 14336, 24, 32, 200, 15), (16, 512, 8200, 8, 200, 16),
     (65, 512, 40, 8, 200, 17), (16, 160, 40, 8, 200, 18),
+    # large batches: the decode stage of the two-stage path reads the codes (no bf16 copy of the values either)
+    (300, 512, 260, 8, 200, 19), (129, 1024, 100, 0, 500, 20), (2048, 256, 192, 16, 200, 21), (200, 4160, 70, 4, 0, 22),
 ])
 def test_qsalr_fused_equals_two_steps(M, K, N, R, permille, seed):
     """Up to 64 tokens on rows of whole chunks the call reads the 4-bit codes itself; it must give, bit for bit, what
     dequantising the values and running the plain layer gives wherever that takes its small-batch streaming kernels
     (the same products enter the same MFMA chain), and that in turn is held to the oracle by test_qsalr_linear and the layer's own parity tests.  Covers one to four m-tiles,
     slices of fewer, exactly and more chunks than a wave keeps in flight, ragged N, every density from all-dense rows
-    to 5 %, ranks from 0 to the maximum, and two shapes that take the two-step path inside the call."""
+    to 5 %, ranks from 0 to the maximum, two shapes that take the two-step path inside the call, and large batches, where the
+    decode stage in front of the dense MFMA stage reads the codes."""
     salr = _salr()
     w = wl.gaussian_bf16((N, K), 0.02, 900 + seed)
     keep = K - (K * permille) // 1000
