@@ -264,6 +264,11 @@ void launch_adapter_t(const LinearArgs& a, hipStream_t stream) {
     char* base = reinterpret_cast<char*>(a.t);
     uint16_t* a_t = reinterpret_cast<uint16_t*>(base + adapter_t_bytes(a.M, a.R));
     float* partial = reinterpret_cast<float*>(base + adapter_t_bytes(a.M, a.R) + adapter_at_bytes(a.K, a.R));
+    if (adapter_uses_prekernel(a.M)) {   // two launches: split-K partials from A_cat as it is, then their sum
+        launch_adapter_partial_to(a, partial, stream);
+        launch_splitk_reduce(partial, a.M * Rpad, kStreamTSlices, a.t, stream);
+        return;
+    }
     launch_adapter_transpose(a.a_cat, a.K, R, Rpad, a_t, stream);
     const int ksplit = adapter_ksplit(a.M, a.K);
     launch_tall_product(a.x, a.M, a.K, a_t, Rpad, ksplit, a.t, partial, false, stream);

@@ -112,7 +112,13 @@ inline int adapter_ksplit(int64_t M, int64_t K) {
     while (s < 64 && blocks * s * 2 <= 1024 && units / (s * 2) >= 8) s *= 2;
     return s;
 }
+// Up to kAdapterSmallM rows the small-batch pre-kernel computes T (one launch of many short workgroups reading A_cat as it
+// is, kStreamTSlices fp32 partials) and the reducing pass sums them; above, the transposing pass + tall product + sum.
+constexpr int64_t kAdapterSmallM = 1024;
+inline bool adapter_uses_prekernel(int64_t M) { return M <= kAdapterSmallM; }
 inline size_t adapter_partial_bytes(int64_t M, int64_t K, int64_t R) {
+    if (R > 0 && adapter_uses_prekernel(M))
+        return round_up_256((size_t)kStreamTSlices * (size_t)M * (size_t)adapter_rank_padded(R) * sizeof(float));
     const int s = adapter_ksplit(M, K);
     return (R > 0 && s > 1) ? round_up_256((size_t)s * (size_t)M * (size_t)adapter_rank_padded(R) * sizeof(float)) : 0;
 }
@@ -271,6 +277,8 @@ hipError_t launch_linear_2of4(const LinearArgs& args, hipStream_t stream, const 
 hipError_t launch_gemm_2of4(const LinearArgs& args, hipStream_t stream, const TimingEvents& ev);
 // split-K partials of T = X * A_cat (small batches): fp32 [kStreamTSlices, M, Rpad] at the start of the workspace
 void launch_adapter_partial(const LinearArgs& args, hipStream_t stream);
+// the same into `partial` [kStreamTSlices, M, Rpad] (no slice table)
+void launch_adapter_partial_to(const LinearArgs& args, float* partial, hipStream_t stream);
 // T = X * A_cat in bf16 [M, Rpad] at the start of the workspace (every path with M > kStreamMaxM)
 void launch_adapter_t(const LinearArgs& args, hipStream_t stream);
 // x [M, K] bf16 times the transpose of a_t [Rpad, K] bf16 (Rpad % 32 == 0, K % 32 == 0), K split over `ksplit`

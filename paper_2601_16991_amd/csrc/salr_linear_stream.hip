@@ -448,13 +448,21 @@ __global__ __launch_bounds__(kTpThreads) void adapter_partial_kernel(const uint1
     }
 }
 
-void launch_adapter_partial(const LinearArgs& a, hipStream_t stream) {
+static void launch_adapter_partial_impl(const LinearArgs& a, float* partial, bool build_table, hipStream_t stream) {
     const int R = (int)a.R, Rpad = (int)adapter_rank_padded(a.R);
     const int product_blocks = kStreamTSlices * (Rpad / 16) * (int)((a.M + 63) / 64);
-    const int table_blocks = a.build_table ? (int)((a.N + kSliceTableRowsPerBlock - 1) / kSliceTableRowsPerBlock) : 0;
+    const int table_blocks = build_table ? (int)((a.N + kSliceTableRowsPerBlock - 1) / kSliceTableRowsPerBlock) : 0;
     hipLaunchKernelGGL(adapter_partial_kernel, dim3((unsigned)(product_blocks + table_blocks)), dim3(kTpThreads), 0, stream, a.x,
-                       (int)a.M, a.K, a.a_cat, R, Rpad, kStreamTSlices, reinterpret_cast<float*>(a.t), product_blocks, a.bitmap,
-                       a.row_offsets, a.N, const_cast<uint32_t*>(a.build_table ? a.slice_table : nullptr));
+                       (int)a.M, a.K, a.a_cat, R, Rpad, kStreamTSlices, partial, product_blocks, a.bitmap, a.row_offsets, a.N,
+                       const_cast<uint32_t*>(build_table ? a.slice_table : nullptr));
+}
+
+void launch_adapter_partial(const LinearArgs& a, hipStream_t stream) {
+    launch_adapter_partial_impl(a, reinterpret_cast<float*>(a.t), a.build_table, stream);
+}
+
+void launch_adapter_partial_to(const LinearArgs& a, float* partial, hipStream_t stream) {
+    launch_adapter_partial_impl(a, partial, false, stream);
 }
 
 template <int MT, int NW, int S>

@@ -120,7 +120,7 @@ def _expected_workspace(M, K, N, R):
     b = 0
     if R:
         b += _r256(M * rp * 2) + _r256(K * rp * 2)
-        ks = _t_ksplit(M, K)
+        ks = 16 if M <= 1024 else _t_ksplit(M, K)   # up to 1024 rows: the sixteen partials of the small-batch pre-kernel
         if ks > 1:
             b += _r256(ks * M * rp * 4)
     if K >= 64 and K % 64 == 0:
